@@ -1,0 +1,326 @@
+"""CPU oracle for the HyperAttention forward pass (arXiv 2310.05869).
+
+TEST INFRASTRUCTURE ONLY.  This is a plain, slow, fp64 NumPy implementation
+written from the paper, used by the tests, by the smoke check and by the
+benchmark's CPU-baseline leg to judge the HIP path.  It shares no code with the
+HIP library and must never be imported by the product package.
+
+HyperAttention is an approximation, so apart from `exact_attention` (which is
+the definition of Section 1.1 written out) every function here follows the
+algorithm's steps in the paper's order and notation:
+
+  exact_attention      Section 1.1: Att = D^-1 A V, A = exp(Q K^T); Section 3.1
+                       for the causal form D_C^-1 (M^C . A) V
+  make_projection      Definition 1 read as r random hyperplanes (sign of a
+                       Gaussian projection), the family whose collision
+                       probability is exactly (1 - theta/pi)^r
+  lsh_project/lsh_codes  Definition 1 + Algorithm 1 step "hash rows of Q, K";
+                       buckets numbered by their position in the reflected
+                       binary Gray code, so buckets i and i+-1 (mod 2^r) differ
+                       in exactly one hyperplane
+  sort_lsh             Algorithm 1: permutations P_Q, P_K ordering rows by hash
+  block_part           Algorithm 1 mask M^H (equal floor(P/b)) evaluated as in
+                       the Implementation Detail paragraph of Section 4: the
+                       i-th group of sorted queries against the i-th group of
+                       sorted keys
+  sampled_part         Algorithm 2, the estimator d_i = (n/m) sum_j (1-M_{i,l_j})
+                       exp<q_i, k_{l_j}> with one index set shared by all rows
+                       and reused for the value product (Section 4,
+                       Implementation Detail), without the cap C_i and the
+                       lower cap, which that paragraph leaves out
+  merge_parts          Algorithm 2, last step: row sum = masked part + estimate
+  causal_forward       Algorithm 4 with the outputs combined by the same
+                       row-sum weights (D_21 + D_C22)
+  hyperattn_forward    Algorithm 3 in its Section 4 form over [B, H, n, d]
+
+Pins (tests/test_oracle_pins.py): brute-force equivalence in the degenerate
+cases (one block and no samples; causal base case; every key sampled exactly
+once), the closed-form collision and adjacent-bucket probabilities of
+Definition 1, unbiasedness of the estimator, row-stochasticity (V = 1 gives
+out = 1), permutation/stability invariants of the sort, and additivity of the
+causal row sums.  At the full benchmark configurations the randomised output
+itself has no independent pin beyond these (no worked example is printed in
+the paper): there the oracle is trusted as the same code that passed them.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+_MASK64 = (1 << 64) - 1
+_GOLDEN = 0x9E3779B97F4A7C15
+
+STREAM_PROJECTION = 1      # counter stream of the hyperplane matrix R
+STREAM_SAMPLES = 2         # + heap index of the node: counter stream of its samples
+
+
+# --------------------------------------------------------------------------
+# Counter-based random numbers (the method's random draws).  The HIP library
+# implements the same generator independently; a test compares the two.
+# --------------------------------------------------------------------------
+def _mix64(z: int) -> int:
+    """SplitMix64 output function (Steele, Lea, Flood 2014)."""
+    z &= _MASK64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _MASK64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _MASK64
+    return z ^ (z >> 31)
+
+
+def rand_u64(seed: int, stream: int, ctr: int) -> int:
+    key = _mix64(seed + _GOLDEN * (stream + 1))
+    return _mix64(key + _GOLDEN * (ctr + 1))
+
+
+def _unit_open(u: int) -> float:
+    """Top 53 bits of u mapped to the open interval (0, 1)."""
+    return ((u >> 11) + 0.5) * (2.0 ** -53)
+
+
+def _round_fp32_to_bf16(x: np.ndarray) -> np.ndarray:
+    bits = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    bits = bits + np.uint64(0x7FFF) + ((bits >> np.uint64(16)) & np.uint64(1))
+    return (bits & np.uint64(0xFFFF0000)).astype(np.uint32).view(np.float32)
+
+
+def make_projection(seed: int, d: int, r: int) -> np.ndarray:
+    """R in R^{d x r}: i.i.d. N(0,1) hyperplane normals (Definition 1).
+
+    Entry (c, k) is a Box-Muller normal from counters 2*(8c+k), 2*(8c+k)+1 of
+    the projection stream, rounded to fp32 and then to the nearest bf16 value,
+    so that products with bf16 inputs are exact in fp32.  Returned as fp64.
+    """
+    R = np.empty((d, r), dtype=np.float64)
+    for c in range(d):
+        for k in range(r):
+            ctr = 2 * (8 * c + k)
+            u1 = _unit_open(rand_u64(seed, STREAM_PROJECTION, ctr))
+            u2 = _unit_open(rand_u64(seed, STREAM_PROJECTION, ctr + 1))
+            R[c, k] = math.sqrt(-2.0 * math.log(u1)) * math.cos(2.0 * math.pi * u2)
+    return _round_fp32_to_bf16(R.astype(np.float32)).astype(np.float64).reshape(d, r)
+
+
+def make_samples(seed: int, level: int, node: int, n_keys: int, m: int) -> np.ndarray:
+    """l_1..l_m i.i.d. uniform on [0, n_keys), with replacement (Algorithm 2).
+
+    One index set per node of the causal recursion (level 0, node 0 for the
+    unmasked problem), shared by every batch, head and query row.
+    """
+    stream = STREAM_SAMPLES + (1 << level) + node
+    out = np.empty(m, dtype=np.int64)
+    for j in range(m):
+        hi = rand_u64(seed, stream, j) >> 32
+        out[j] = (hi * n_keys) >> 32
+    return out
+
+
+# --------------------------------------------------------------------------
+# Section 1.1 / 3.1: the definition (brute force; small n only)
+# --------------------------------------------------------------------------
+def exact_attention(Q, K, V, causal=False):
+    """Att = D^-1 A V with A = exp(Q K^T) (no 1/sqrt(d)); returns (Att, log D)."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    S = Q @ K.T
+    if causal:
+        i = np.arange(S.shape[0])[:, None]
+        j = np.arange(S.shape[1])[None, :]
+        S = np.where(i >= j, S, -np.inf)          # M^C_{ij} = 1{i >= j}
+    mx = S.max(axis=1, keepdims=True)
+    A = np.exp(S - mx)
+    D = A.sum(axis=1, keepdims=True)
+    return (A @ V) / D, (mx + np.log(D))[:, 0]
+
+
+# --------------------------------------------------------------------------
+# Definition 1 + Algorithm 1: sortLSH
+# --------------------------------------------------------------------------
+def lsh_project(X, R):
+    """p[i, k] = <x_i, R[:, k]> in fp64."""
+    return np.asarray(X, dtype=np.float64) @ np.asarray(R, dtype=np.float64)
+
+
+def gray_rank_table(r: int) -> np.ndarray:
+    """rank[s] = position of the r-bit word s in the reflected Gray sequence."""
+    rank = np.empty(1 << r, dtype=np.int64)
+    for i in range(1 << r):
+        rank[i ^ (i >> 1)] = i
+    return rank
+
+
+def lsh_bits(p) -> np.ndarray:
+    """Sign bits: bit k of a row is 1 iff its projection on hyperplane k is > 0."""
+    return np.asarray(p) > 0
+
+
+def codes_from_bits(bits, r: int) -> np.ndarray:
+    """Bucket index: hyperplane k contributes bit k of the word; the bucket is
+    the word's position in the reflected Gray sequence."""
+    word = np.zeros(bits.shape[0], dtype=np.int64)
+    for k in range(r):
+        word |= bits[:, k].astype(np.int64) << k
+    return gray_rank_table(r)[word]
+
+
+def lsh_codes(p, r: int) -> np.ndarray:
+    """Bucket index of each row from its r projections."""
+    return codes_from_bits(lsh_bits(p), r)
+
+
+def sort_lsh(codes):
+    """Algorithm 1: perm[pos] = row, rows ordered by bucket; ties keep the
+    original row order (any order satisfies the algorithm; this one is unique).
+    Returns (perm, pos) with pos[perm[p]] == p."""
+    perm = np.argsort(np.asarray(codes), kind="stable")
+    pos = np.empty_like(perm)
+    pos[perm] = np.arange(perm.shape[0])
+    return perm, pos
+
+
+# --------------------------------------------------------------------------
+# One unmasked node: s queries against s keys (Algorithms 1-3, Section 4 form)
+# --------------------------------------------------------------------------
+def block_part(Qn, Kn, Vn, perm_q, perm_k, b):
+    """Entries selected by M^H: sorted query group t against sorted key group t.
+
+    Returns (O_b, LSE_b) in the node's original row order: the normalised
+    output of the masked entries and the log of their row sum."""
+    s, d = Qn.shape
+    O = np.zeros((s, d), dtype=np.float64)
+    L = np.full(s, -np.inf, dtype=np.float64)
+    for t in range(s // b):
+        I = perm_q[t * b:(t + 1) * b]
+        J = perm_k[t * b:(t + 1) * b]
+        S = Qn[I] @ Kn[J].T
+        mx = S.max(axis=1, keepdims=True)
+        A = np.exp(S - mx)
+        den = A.sum(axis=1, keepdims=True)
+        O[I] = (A @ Vn[J]) / den
+        L[I] = (mx + np.log(den))[:, 0]
+    return O, L
+
+
+def sampled_part(Qn, Kn, Vn, pos_q, pos_k, b, samples):
+    """Algorithm 2's estimator of the unmasked row sum and, with the same
+    indices, of the unmasked part of A V.
+
+    den_i = (s/m) sum_j (1 - M_{i,l_j}) exp<q_i, k_{l_j}>, and the numerator
+    carries v_{l_j} along.  Returns (O_r, LSE_r) with LSE_r = log den (-inf and
+    a zero row when every sample of a row is masked, or m = 0)."""
+    s, d = Qn.shape
+    m = len(samples)
+    O = np.zeros((s, d), dtype=np.float64)
+    L = np.full(s, -np.inf, dtype=np.float64)
+    if m == 0:
+        return O, L
+    samples = np.asarray(samples, dtype=np.int64)
+    S = Qn @ Kn[samples].T                                         # s x m
+    keep = (pos_q[:, None] // b) != (pos_k[samples][None, :] // b)  # 1 - M
+    S = np.where(keep, S, -np.inf)
+    mx = S.max(axis=1, keepdims=True)
+    live = np.isfinite(mx[:, 0])
+    mx = np.where(np.isfinite(mx), mx, 0.0)
+    A = np.exp(S - mx)
+    den = A.sum(axis=1)
+    num = A @ Vn[samples]
+    O[live] = num[live] / den[live][:, None]
+    L[live] = mx[live, 0] + np.log(den[live]) + math.log(s / m)
+    return O, L
+
+
+def merge_parts(O1, L1, O2, L2):
+    """Row sums add (d~_i = masked part + estimate); outputs are combined with
+    the corresponding weights.  L = log(exp L1 + exp L2)."""
+    L = np.logaddexp(L1, L2)
+    with np.errstate(invalid="ignore"):
+        w1 = np.where(np.isfinite(L1), np.exp(L1 - L), 0.0)
+        w2 = np.where(np.isfinite(L2), np.exp(L2 - L), 0.0)
+    return w1[:, None] * O1 + w2[:, None] * O2, L
+
+
+def node_forward(Qn, Kn, Vn, codes_q, codes_k, b, samples, parts=None):
+    """Unmasked HyperAttention on one node: sortLSH, masked part, estimate."""
+    perm_q, pos_q = sort_lsh(codes_q)
+    perm_k, pos_k = sort_lsh(codes_k)
+    O_b, L_b = block_part(Qn, Kn, Vn, perm_q, perm_k, b)
+    O_r, L_r = sampled_part(Qn, Kn, Vn, pos_q, pos_k, b, samples)
+    if parts is not None:
+        parts.update(perm_q=perm_q, perm_k=perm_k, pos_q=pos_q, pos_k=pos_k,
+                     O_b=O_b, L_b=L_b, O_r=O_r, L_r=L_r)
+    return merge_parts(O_b, L_b, O_r, L_r)
+
+
+# --------------------------------------------------------------------------
+# Algorithm 4: causal masking by recursive halving
+# --------------------------------------------------------------------------
+def causal_forward(Q, K, V, codes_q, codes_k, b, n_min, sample_fn, level=0, node=0):
+    """Returns (out, lse) for causal attention on n rows.
+
+    n <= n_min: the definition (exact causal attention).  Otherwise the two
+    diagonal halves recurse and the off-diagonal block A_21 = (Q_2, K_1, V_1)
+    is an unmasked node; the lower half's row sum is D_21 + D_C22."""
+    n = Q.shape[0]
+    if n <= n_min:
+        return exact_attention(Q, K, V, causal=True)
+    h = n // 2
+    O1, L1 = causal_forward(Q[:h], K[:h], V[:h], codes_q[:h], codes_k[:h], b, n_min,
+                            sample_fn, level + 1, 2 * node)
+    O22, L22 = causal_forward(Q[h:], K[h:], V[h:], codes_q[h:], codes_k[h:], b, n_min,
+                              sample_fn, level + 1, 2 * node + 1)
+    O21, L21 = node_forward(Q[h:], K[:h], V[:h], codes_q[h:], codes_k[:h], b,
+                            sample_fn(level, node, h))
+    O2, L2 = merge_parts(O21, L21, O22, L22)
+    return np.concatenate([O1, O2]), np.concatenate([L1, L2])
+
+
+# --------------------------------------------------------------------------
+# Whole forward pass over [B, H, n, d]
+# --------------------------------------------------------------------------
+def hyperattn_forward(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0,
+                      R=None, sample_fn=None, flip=None, stages=None):
+    """HyperAttention forward.  Q, K, V: [B, H, n, d] (already rounded to the
+    storage dtype).  R / sample_fn override the seed-derived hyperplanes and
+    per-node index sets.  `flip`, if given, is a list of (tensor, bh, row, k)
+    sign bits to invert before bucketing (tensor 0 = Q, 1 = K): used to follow
+    the HIP path through projections too close to zero to call.  `stages`, if
+    a dict, receives codes and (unmasked case) the per-head intermediate
+    parts.  Returns (out [B,H,n,d], lse [B,H,n]) in fp64."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    B, H, n, d = Q.shape
+    if R is None:
+        R = make_projection(seed, d, r)
+    if sample_fn is None:
+        def sample_fn(level, node, n_keys):
+            return make_samples(seed, level, node, n_keys, m)
+    out = np.empty((B, H, n, d), dtype=np.float64)
+    lse = np.empty((B, H, n), dtype=np.float64)
+    all_codes = np.empty((2, B * H, n), dtype=np.int64)
+    all_proj = np.empty((2, B * H, n, r), dtype=np.float64)
+    for bh in range(B * H):
+        q, k, v = (x.reshape(B * H, n, d)[bh] for x in (Q, K, V))
+        pq, pk = lsh_project(q, R), lsh_project(k, R)
+        all_proj[0, bh], all_proj[1, bh] = pq, pk
+        bits = [lsh_bits(pq), lsh_bits(pk)]
+        if flip:
+            for (t, fbh, row, kk) in flip:
+                if fbh == bh:
+                    bits[t][row, kk] = ~bits[t][row, kk]
+        codes = [codes_from_bits(bits[t], r) for t in range(2)]
+        cq, ck = codes
+        all_codes[0, bh], all_codes[1, bh] = cq, ck
+        if causal:
+            o, l = causal_forward(q, k, v, cq, ck, b, n_min, sample_fn)
+        else:
+            parts = {} if stages is not None else None
+            o, l = node_forward(q, k, v, cq, ck, b, sample_fn(0, 0, n), parts)
+            if stages is not None:
+                stages.setdefault("parts", []).append(parts)
+        out.reshape(B * H, n, d)[bh] = o
+        lse.reshape(B * H, n)[bh] = l
+    if stages is not None:
+        stages["codes"] = all_codes
+        stages["proj"] = all_proj
+    return out, lse

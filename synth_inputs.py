@@ -1,0 +1,102 @@
+"""Seeded synthetic inputs for the HyperAttention forward path.
+
+This module holds input generation only: it draws Q, K, V with the shapes and
+value distributions of the benchmark workloads and rounds them once to the
+storage dtype.  None of the method's arithmetic (hashing, sorting, softmax,
+sampling) lives here, so the CPU oracle and the HIP path can both be fed from
+it without sharing any code of the method itself.
+
+Workloads (Q, K, V are [B, H, n, d]):
+
+  iid      Q, K, V ~ N(0, 1) / d**0.25           (the single-layer timing shape
+           of the paper's Section 4.2 and the ChatGLM2-like layer shape of
+           Section 4.1, with the softmax scale folded into Q and K because the
+           paper's attention matrix is exp(Q K^T) with no 1/sqrt(d) factor)
+  mixture  Q, K rows drawn from a 64-centre Gaussian mixture per (batch, head):
+           centres ~ N(0, 4 I), within-cluster sigma 0.5, cluster k chosen with
+           probability proportional to k**-1.1; V ~ N(0, 1).  Uneven LSH
+           buckets and large attention entries.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+DATA_SEED = 1234
+
+
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round fp32 values to the nearest bf16 (ties to even); result is fp32."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    bits = x.view(np.uint32).astype(np.uint64)
+    bits = bits + np.uint64(0x7FFF) + ((bits >> np.uint64(16)) & np.uint64(1))
+    bits = (bits & np.uint64(0xFFFF0000)).astype(np.uint32)
+    return bits.view(np.float32).reshape(x.shape)
+
+
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """uint16 bit patterns of bf16-representable fp32 values."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    return (x.view(np.uint32) >> np.uint32(16)).astype(np.uint16).reshape(x.shape)
+
+
+def _finish(arrs, dtype):
+    if dtype == "bf16":
+        return tuple(round_to_bf16(a) for a in arrs)
+    if dtype == "fp32":
+        return tuple(np.ascontiguousarray(a, dtype=np.float32) for a in arrs)
+    raise ValueError(f"unknown dtype {dtype!r}")
+
+
+def iid_qkv(B, H, n, d, dtype="bf16", seed=DATA_SEED):
+    """Q, K, V iid N(0,1)/d**0.25, rounded once to `dtype` (returned as fp32)."""
+    rng = np.random.default_rng(seed)
+    scale = np.float32(d ** -0.25)
+    out = []
+    for _ in range(3):
+        a = rng.standard_normal((B, H, n, d), dtype=np.float32)
+        a *= scale
+        out.append(a)
+    return _finish(out, dtype)
+
+
+def mixture_qkv(B, H, n, d, dtype="bf16", seed=DATA_SEED, centres=64,
+                centre_sigma=2.0, within_sigma=0.5, zipf_s=1.1):
+    """Clustered Q, K (shared centres per (batch, head)), V iid N(0,1)."""
+    rng = np.random.default_rng(seed)
+    pk = np.arange(1, centres + 1, dtype=np.float64) ** (-zipf_s)
+    pk /= pk.sum()
+    Q = np.empty((B, H, n, d), dtype=np.float32)
+    K = np.empty((B, H, n, d), dtype=np.float32)
+    for bi in range(B):
+        for hi in range(H):
+            C = (centre_sigma * rng.standard_normal((centres, d))).astype(np.float32)
+            for dst in (Q, K):
+                which = rng.choice(centres, size=n, p=pk)
+                noise = rng.standard_normal((n, d), dtype=np.float32)
+                dst[bi, hi] = C[which] + np.float32(within_sigma) * noise
+    V = rng.standard_normal((B, H, n, d), dtype=np.float32)
+    return _finish((Q, K, V), dtype)
+
+
+# The benchmark configurations: shape, dtype, input law and algorithm parameters.
+CONFIGS = {
+    "cfg1_n1k_fp32": dict(B=1, H=1, n=1024, d=64, dtype="fp32", law="iid",
+                          b=64, m=64, r=7, causal=0, n_min=4096, seed=0),
+    "cfg2_n32k": dict(B=1, H=32, n=32768, d=128, dtype="bf16", law="iid",
+                      b=256, m=256, r=7, causal=0, n_min=4096, seed=0),
+    "cfg3_n32k_causal": dict(B=1, H=32, n=32768, d=128, dtype="bf16", law="iid",
+                             b=256, m=256, r=7, causal=1, n_min=4096, seed=0),
+    "cfg4_n131k_causal": dict(B=1, H=32, n=131072, d=128, dtype="bf16", law="iid",
+                              b=256, m=256, r=7, causal=1, n_min=4096, seed=0),
+    "cfg5_n65k_mixture": dict(B=2, H=32, n=65536, d=64, dtype="bf16", law="mixture",
+                              b=256, m=512, r=7, causal=0, n_min=4096, seed=0),
+}
+
+
+def make_qkv(cfg: dict, seed=DATA_SEED, B=None, H=None, n=None):
+    """Inputs for a CONFIGS entry (optionally with B, H or n overridden)."""
+    B = cfg["B"] if B is None else B
+    H = cfg["H"] if H is None else H
+    n = cfg["n"] if n is None else n
+    gen = iid_qkv if cfg["law"] == "iid" else mixture_qkv
+    return gen(B, H, n, cfg["d"], cfg["dtype"], seed)

@@ -1,0 +1,329 @@
+"""Pins for the CPU oracle: it is checked here against what the paper and the
+mathematics fix, never against itself or the HIP path.
+
+  * Section 1.1 definition, re-derived by explicit loops on tiny inputs
+  * degenerate cases in which HyperAttention must equal exact attention:
+    one block and no samples; every key sampled exactly once (any b, r, seed);
+    causal base case; causal recursion with identity sampling at every node
+  * Definition 1: collision probability (1-theta/pi)^r and adjacent-bucket
+    probability 2 theta/pi (1-theta/pi)^(r-1), cyclic in 2^r
+  * Algorithm 1: M^H has exactly b ones per row and column; sort invariants
+  * Algorithm 2: the estimator is unbiased for the unmasked row sum
+  * Algorithm 4: lower-half row sums are D_21 + D_C22
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import hyperattn_oracle as orc
+
+
+def _rand_qkv(n, d, seed, scale=None):
+    rng = np.random.default_rng(seed)
+    scale = d ** -0.25 if scale is None else scale
+    return tuple(rng.standard_normal((n, d)) * scale for _ in range(3))
+
+
+def _loops_attention(Q, K, V, causal):
+    """Section 1.1 / 3.1 with scalar loops: out_i = sum_j A_ij v_j / sum_j A_ij."""
+    n, d = Q.shape
+    dv = V.shape[1]
+    out = np.zeros((n, dv))
+    lse = np.zeros(n)
+    for i in range(n):
+        num = [0.0] * dv
+        den = 0.0
+        for j in range(K.shape[0]):
+            if causal and j > i:
+                continue
+            a = math.exp(sum(Q[i, c] * K[j, c] for c in range(d)))
+            den += a
+            for c in range(dv):
+                num[c] += a * V[j, c]
+        out[i] = [x / den for x in num]
+        lse[i] = math.log(den)
+    return out, lse
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_exact_attention_matches_scalar_loops(causal):
+    Q, K, V = _rand_qkv(7, 3, seed=11, scale=0.8)
+    out, lse = orc.exact_attention(Q, K, V, causal)
+    ref_o, ref_l = _loops_attention(Q, K, V, causal)
+    np.testing.assert_allclose(out, ref_o, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(lse, ref_l, rtol=1e-12, atol=1e-14)
+
+
+def test_exact_attention_is_not_transposed():
+    # n_q != n_k makes a transposed operand fail on shape; values pin the rest.
+    rng = np.random.default_rng(5)
+    Q = rng.standard_normal((4, 3)); K = rng.standard_normal((6, 3)); V = rng.standard_normal((6, 2))
+    out, lse = orc.exact_attention(Q, K, V)
+    ref_o, ref_l = _loops_attention(Q, K, V, False)
+    np.testing.assert_allclose(out, ref_o, rtol=1e-12)
+    np.testing.assert_allclose(lse, ref_l, rtol=1e-12)
+
+
+# ---------------------------------------------------------------- generator
+def test_splitmix_known_vector():
+    # First output of SplitMix64 seeded with 0 (published reference value).
+    assert orc._mix64(0x9E3779B97F4A7C15) == 0xE220A8397B1DCDAF
+
+
+def test_projection_is_standard_normal_and_bf16_representable():
+    R = np.concatenate([orc.make_projection(s, 128, 8).ravel() for s in range(6)])
+    assert R.shape[0] == 6 * 1024
+    assert abs(R.mean()) < 4 / math.sqrt(R.size)
+    assert abs(R.var() - 1.0) < 0.06
+    # kurtosis of a normal is 3
+    assert abs((R ** 4).mean() - 3.0) < 0.5
+    bits = R.astype(np.float32).view(np.uint32)
+    assert np.all((bits & 0xFFFF) == 0)
+    assert np.all(R.astype(np.float32).astype(np.float64) == R)
+    # entry (c,k) does not depend on r or d
+    np.testing.assert_array_equal(orc.make_projection(3, 64, 5), orc.make_projection(3, 128, 8)[:64, :5])
+
+
+def test_samples_are_uniform_in_range():
+    s = orc.make_samples(0, 0, 0, 1000, 20000)
+    assert s.min() >= 0 and s.max() < 1000
+    counts = np.bincount(s, minlength=1000)
+    chi2 = ((counts - 20.0) ** 2 / 20.0).sum()
+    assert 800 < chi2 < 1200        # 999 dof, +-4.5 sigma
+    # different nodes draw different sets; the set does not depend on batch/head
+    assert not np.array_equal(orc.make_samples(0, 1, 0, 1000, 64), orc.make_samples(0, 1, 1, 1000, 64))
+    assert not np.array_equal(orc.make_samples(0, 1, 0, 1000, 64), orc.make_samples(1, 1, 0, 1000, 64))
+
+
+# ---------------------------------------------------------------- Definition 1
+def test_gray_rank_inverts_reflected_gray_code():
+    for r in range(1, 9):
+        rank = orc.gray_rank_table(r)
+        assert sorted(rank.tolist()) == list(range(1 << r))
+        for s in range(1 << r):
+            i = int(rank[s])
+            assert i ^ (i >> 1) == s
+        # consecutive buckets (cyclically) differ in exactly one hyperplane
+        inv = np.argsort(rank)
+        for i in range(1 << r):
+            diff = int(inv[i]) ^ int(inv[(i + 1) % (1 << r)])
+            assert bin(diff).count("1") == 1
+
+
+def test_negated_vector_gets_complement_word():
+    r = 7
+    R = orc.make_projection(2, 16, r)
+    x = np.random.default_rng(0).standard_normal((50, 16))
+    inv = np.argsort(orc.gray_rank_table(r))       # bucket -> word
+    w_pos = inv[orc.lsh_codes(orc.lsh_project(x, R), r)]
+    w_neg = inv[orc.lsh_codes(orc.lsh_project(-x, R), r)]
+    np.testing.assert_array_equal(w_pos ^ w_neg, (1 << r) - 1)
+
+
+@pytest.mark.parametrize("theta_frac,r", [(0.15, 7), (0.35, 4), (0.08, 7)])
+def test_lsh_collision_and_adjacency_probabilities(theta_frac, r):
+    """Monte-Carlo over hyperplane draws for a pair at angle theta."""
+    theta = theta_frac * math.pi
+    x = np.array([[1.0, 0.0, 0.0]])
+    y = np.array([[math.cos(theta), math.sin(theta), 0.0]])
+    trials = 6000
+    same = adj = 0
+    nb = 1 << r
+    for seed in range(trials):
+        R = orc.make_projection(1000 + seed, 3, r)
+        cx = int(orc.lsh_codes(orc.lsh_project(x, R), r)[0])
+        cy = int(orc.lsh_codes(orc.lsh_project(y, R), r)[0])
+        same += cx == cy
+        adj += ((cx - cy) % nb) in (1, nb - 1)
+    p_same = (1 - theta / math.pi) ** r
+    p_adj = 2 * theta / math.pi * (1 - theta / math.pi) ** (r - 1)
+    for got, p in ((same, p_same), (adj, p_adj)):
+        sigma = math.sqrt(p * (1 - p) / trials)
+        assert abs(got / trials - p) < 4.5 * sigma, (got / trials, p)
+
+
+# ---------------------------------------------------------------- Algorithm 1
+def test_sort_invariants_and_mask_counts():
+    rng = np.random.default_rng(3)
+    n, b = 96, 16
+    cq = rng.integers(0, 8, n); ck = rng.integers(0, 8, n)
+    for codes in (cq, ck):
+        perm, pos = orc.sort_lsh(codes)
+        assert sorted(perm.tolist()) == list(range(n))
+        np.testing.assert_array_equal(pos[perm], np.arange(n))
+        sc = codes[perm]
+        assert np.all(np.diff(sc) >= 0)
+        ties = np.diff(sc) == 0
+        assert np.all(np.diff(perm)[ties] > 0)      # equal codes keep row order
+    _, pos_q = orc.sort_lsh(cq)
+    _, pos_k = orc.sort_lsh(ck)
+    M = (pos_q[:, None] // b) == (pos_k[None, :] // b)
+    assert np.all(M.sum(axis=0) == b) and np.all(M.sum(axis=1) == b)
+
+
+def test_block_part_equals_masked_attention():
+    """block_part must be D_M^-1 (M^H . A) V with the mask of Algorithm 1."""
+    n, d, b, r = 64, 8, 16, 4
+    Q, K, V = _rand_qkv(n, d, seed=4)
+    R = orc.make_projection(9, d, r)
+    cq = orc.lsh_codes(orc.lsh_project(Q, R), r)
+    ck = orc.lsh_codes(orc.lsh_project(K, R), r)
+    perm_q, pos_q = orc.sort_lsh(cq)
+    perm_k, pos_k = orc.sort_lsh(ck)
+    O_b, L_b = orc.block_part(Q, K, V, perm_q, perm_k, b)
+    M = (pos_q[:, None] // b) == (pos_k[None, :] // b)
+    A = np.exp(Q @ K.T) * M
+    np.testing.assert_allclose(O_b, (A @ V) / A.sum(1, keepdims=True), rtol=1e-11)
+    np.testing.assert_allclose(L_b, np.log(A.sum(1)), rtol=1e-11)
+
+
+# ---------------------------------------------------------------- degenerate = exact
+def _as4(x):
+    return x[None, None]
+
+
+def test_one_block_no_samples_is_exact():
+    n, d = 48, 8
+    Q, K, V = _rand_qkv(n, d, seed=1)
+    out, lse = orc.hyperattn_forward(_as4(Q), _as4(K), _as4(V), b=n, m=0, r=5, seed=3)
+    ref_o, ref_l = orc.exact_attention(Q, K, V)
+    np.testing.assert_allclose(out[0, 0], ref_o, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(lse[0, 0], ref_l, rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("b,r,seed", [(8, 3, 0), (16, 6, 5), (32, 1, 7)])
+def test_identity_sampling_is_exact(b, r, seed):
+    """m = n and l = (0..n-1): each unmasked key counted once with weight 1, so
+    masked part + estimate is the full row sum whatever the LSH produced."""
+    n, d = 64, 8
+    Q, K, V = _rand_qkv(n, d, seed=seed + 20)
+    ident = lambda level, node, n_keys: np.arange(n_keys)
+    out, lse = orc.hyperattn_forward(_as4(Q), _as4(K), _as4(V), b=b, m=n, r=r, seed=seed,
+                                     sample_fn=ident)
+    ref_o, ref_l = orc.exact_attention(Q, K, V)
+    np.testing.assert_allclose(out[0, 0], ref_o, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(lse[0, 0], ref_l, rtol=1e-10, atol=1e-12)
+
+
+def test_duplicated_samples_count_with_multiplicity():
+    """l = every key twice, m = 2n: weight n/m = 1/2 per hit, still exact."""
+    n, d, b = 32, 4, 8
+    Q, K, V = _rand_qkv(n, d, seed=2)
+    twice = lambda level, node, n_keys: np.repeat(np.arange(n_keys), 2)
+    out, lse = orc.hyperattn_forward(_as4(Q), _as4(K), _as4(V), b=b, m=2 * n, r=4, seed=1,
+                                     sample_fn=twice)
+    ref_o, ref_l = orc.exact_attention(Q, K, V)
+    np.testing.assert_allclose(out[0, 0], ref_o, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(lse[0, 0], ref_l, rtol=1e-10, atol=1e-12)
+
+
+def test_rows_are_normalised():
+    n, d = 128, 8
+    Q, K, _ = _rand_qkv(n, d, seed=9)
+    V = np.ones((n, d))
+    out, _ = orc.hyperattn_forward(_as4(Q), _as4(K), _as4(V), b=16, m=24, r=5, seed=4)
+    np.testing.assert_allclose(out, 1.0, rtol=1e-12)
+    out, _ = orc.hyperattn_forward(_as4(Q), _as4(K), _as4(V), b=16, m=24, r=5, seed=4,
+                                   causal=True, n_min=32)
+    np.testing.assert_allclose(out, 1.0, rtol=1e-12)
+
+
+def test_estimator_is_unbiased_for_unmasked_row_sum():
+    """E[(s/m) sum_j (1-M_{i,l_j}) exp<q_i,k_{l_j}>] = sum_j (1-M_ij) A_ij."""
+    n, d, b, r, m = 64, 8, 16, 4, 16
+    Q, K, V = _rand_qkv(n, d, seed=6, scale=0.45)
+    R = orc.make_projection(0, d, r)
+    _, pos_q = orc.sort_lsh(orc.lsh_codes(orc.lsh_project(Q, R), r))
+    _, pos_k = orc.sort_lsh(orc.lsh_codes(orc.lsh_project(K, R), r))
+    A = np.exp(Q @ K.T)
+    unmasked = (pos_q[:, None] // b) != (pos_k[None, :] // b)
+    target_den = (A * unmasked).sum(1)
+    target_num = (A * unmasked) @ V
+    trials = 1500
+    dens = np.zeros((trials, n)); nums = np.zeros((trials, n, d))
+    for t in range(trials):
+        smp = orc.make_samples(t, 0, 0, n, m)
+        O_r, L_r = orc.sampled_part(Q, K, V, pos_q, pos_k, b, smp)
+        dens[t] = np.exp(L_r)
+        nums[t] = np.exp(L_r)[:, None] * O_r
+    se = dens.std(0, ddof=1) / math.sqrt(trials)
+    assert np.all(np.abs(dens.mean(0) - target_den) < 5 * se)
+    se_n = nums.std(0, ddof=1) / math.sqrt(trials)
+    assert np.all(np.abs(nums.mean(0) - target_num) < 5.5 * se_n + 1e-12)
+
+
+def test_all_samples_masked_gives_empty_residual():
+    n, d, b = 16, 4, 16          # one block: every sample falls in the row's own block
+    Q, K, V = _rand_qkv(n, d, seed=8)
+    pos = np.arange(n)
+    O_r, L_r = orc.sampled_part(Q, K, V, pos, pos, b, np.array([1, 5, 5]))
+    assert np.all(L_r == -np.inf) and np.all(O_r == 0)
+    O_b, L_b = orc.block_part(Q, K, V, pos, pos, b)
+    O, L = orc.merge_parts(O_b, L_b, O_r, L_r)
+    np.testing.assert_array_equal(O, O_b); np.testing.assert_array_equal(L, L_b)
+
+
+# ---------------------------------------------------------------- Algorithm 4
+def test_causal_base_case_is_exact():
+    n, d = 40, 8
+    Q, K, V = _rand_qkv(n, d, seed=12)
+    out, lse = orc.hyperattn_forward(_as4(Q), _as4(K), _as4(V), b=8, m=8, r=4, causal=True, n_min=64)
+    ref_o, ref_l = orc.exact_attention(Q, K, V, causal=True)
+    np.testing.assert_allclose(out[0, 0], ref_o, rtol=1e-12); np.testing.assert_allclose(lse[0, 0], ref_l, rtol=1e-12)
+
+
+def test_causal_one_split_full_block_is_exact():
+    n, d = 64, 8
+    Q, K, V = _rand_qkv(n, d, seed=13)
+    out, lse = orc.hyperattn_forward(_as4(Q), _as4(K), _as4(V), b=32, m=0, r=4, causal=True, n_min=32)
+    ref_o, ref_l = orc.exact_attention(Q, K, V, causal=True)
+    np.testing.assert_allclose(out[0, 0], ref_o, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(lse[0, 0], ref_l, rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("n,n_min,b", [(128, 16, 8), (64, 32, 16)])
+def test_causal_identity_sampling_is_exact_at_any_depth(n, n_min, b):
+    d = 8
+    Q, K, V = _rand_qkv(n, d, seed=14)
+    ident = lambda level, node, n_keys: np.arange(n_keys)
+    out, lse = orc.hyperattn_forward(_as4(Q), _as4(K), _as4(V), b=b, m=0, r=5, causal=True,
+                                     n_min=n_min, sample_fn=ident)
+    ref_o, ref_l = orc.exact_attention(Q, K, V, causal=True)
+    np.testing.assert_allclose(out[0, 0], ref_o, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(lse[0, 0], ref_l, rtol=1e-10, atol=1e-12)
+
+
+def test_causal_row_sums_add_and_nodes_use_their_own_samples():
+    """exp(lse) of the lower half = D_21 + D_C22, with D_21 from an unmasked
+    node on (Q_2, K_1) drawing the (level 0, node 0) index set."""
+    n, d, b, m, r, n_min, seed = 64, 8, 8, 8, 4, 32, 5
+    Q, K, V = _rand_qkv(n, d, seed=15)
+    out, lse = orc.hyperattn_forward(_as4(Q), _as4(K), _as4(V), b=b, m=m, r=r, causal=True,
+                                     n_min=n_min, seed=seed)
+    h = n // 2
+    R = orc.make_projection(seed, d, r)
+    cq = orc.lsh_codes(orc.lsh_project(Q, R), r); ck = orc.lsh_codes(orc.lsh_project(K, R), r)
+    O21, L21 = orc.node_forward(Q[h:], K[:h], V[:h], cq[h:], ck[:h], b,
+                                orc.make_samples(seed, 0, 0, h, m))
+    O22, L22 = orc.exact_attention(Q[h:], K[h:], V[h:], causal=True)
+    np.testing.assert_allclose(np.exp(lse[0, 0, h:]), np.exp(L21) + np.exp(L22), rtol=1e-11)
+    w = np.exp(L21) / (np.exp(L21) + np.exp(L22))
+    np.testing.assert_allclose(out[0, 0, h:], w[:, None] * O21 + (1 - w)[:, None] * O22, rtol=1e-10, atol=1e-13)
+    O1, L1 = orc.exact_attention(Q[:h], K[:h], V[:h], causal=True)
+    np.testing.assert_allclose(out[0, 0, :h], O1, rtol=1e-12); np.testing.assert_allclose(lse[0, 0, :h], L1, rtol=1e-12)
+
+
+def test_approximation_error_shrinks_with_more_samples():
+    """Sanity on the method itself: more sampled columns, closer to exact."""
+    n, d = 512, 16
+    Q, K, V = _rand_qkv(n, d, seed=16)
+    ref, _ = orc.exact_attention(Q, K, V)
+    errs = []
+    for m in (8, 128):
+        e = 0.0
+        for seed in range(4):
+            out, _ = orc.hyperattn_forward(_as4(Q), _as4(K), _as4(V), b=32, m=m, r=4, seed=seed)
+            e += np.linalg.norm(out[0, 0] - ref) / np.linalg.norm(ref)
+        errs.append(e / 4)
+    assert errs[1] < 0.6 * errs[0]
