@@ -1,0 +1,188 @@
+/*
+ * hyperattn.h - C ABI of the MI355X (gfx950) HyperAttention forward library.
+ *
+ * HyperAttention (arXiv 2310.05869) approximates softmax attention
+ * Att = D^-1 A V, A = exp(Q K^T) (Section 1.1; no 1/sqrt(d) factor: fold any
+ * scale into Q or K) in near-linear time:
+ *   1. sortLSH (Definition 1, Algorithm 1): every row of Q and K is hashed by r
+ *      random hyperplanes; the sign word's position in the reflected Gray code is
+ *      the bucket; a stable sort by bucket gives permutations P_Q, P_K and the
+ *      mask M^H = 1{floor(P_Q(i)/b) == floor(P_K(j)/b)}: the b x b diagonal
+ *      blocks of the sorted attention matrix, which are computed exactly;
+ *   2. the rest of each row is estimated from m key indices drawn uniformly
+ *      with replacement, one set shared by all rows and reused for the value
+ *      product (Algorithm 2 without its caps, as in the Implementation Detail
+ *      paragraph of Section 4): weight (#keys/m), samples that fall in the row's
+ *      own block contribute nothing;
+ *   3. both parts share one normaliser: row sum = block part + estimate;
+ *   4. causal masking (Section 3.1, Algorithm 4): recursive halving; the
+ *      off-diagonal block (Q_2, K_1, V_1) of every split is an unmasked problem
+ *      handled by 1-3, diagonal blocks of n_min rows are exact causal
+ *      attention, and a row's partial results are combined by their row sums.
+ *
+ * Conventions for every entry point
+ *   - Tensors are contiguous [B, H, n, d] in DEVICE memory, caller-owned, of the
+ *     dtype in ha_shape (HA_BF16: 16-bit bfloat; HA_FP32: IEEE float).  `lse` is
+ *     float [B, H, n], natural log of the (estimated) row sum.
+ *   - The library allocates no device memory, never synchronises and enqueues
+ *     only on `stream` (a hipStream_t passed as void*; NULL = the null stream).
+ *     Scratch comes from the caller: `workspace` of at least
+ *     ha_workspace_bytes() bytes, 256-byte aligned, device memory.  Two calls may
+ *     overlap only if they use different workspaces.
+ *   - Inputs are not modified; outputs must not alias inputs.
+ *   - Return value: HA_OK (0) or a negative ha_status; nothing aborts.  Argument
+ *     errors are detected on the host before anything is enqueued.
+ *   - Same inputs, parameters and seed give bit-identical outputs (no floating
+ *     point atomics anywhere).
+ *   - Pointers named *_host are host memory, everything else is device memory.
+ */
+#ifndef HYPERATTN_H
+#define HYPERATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { HA_BF16 = 0, HA_FP32 = 1 } ha_dtype;
+
+typedef enum {
+  HA_OK = 0,
+  HA_ERR_NULL = -1,      /* a required pointer is NULL */
+  HA_ERR_DTYPE = -2,     /* dtype is neither HA_BF16 nor HA_FP32 */
+  HA_ERR_SHAPE = -3,     /* shape or parameters outside what is supported (see each call) */
+  HA_ERR_WORKSPACE = -4, /* workspace too small or not 256-byte aligned */
+  HA_ERR_LAUNCH = -5     /* the HIP runtime refused a launch (hipGetLastError) */
+} ha_status;
+
+/* [B, H, n, d]; d must be 64 or 128. */
+typedef struct {
+  int32_t B, H, n, d;
+  int32_t dtype; /* ha_dtype */
+} ha_shape;
+
+/* b: block size of the sorted diagonal blocks; m: sampled key columns per node
+ * (0 = block part only); r: LSH hyperplanes, 1..8; causal: 0/1; n_min: causal
+ * recursion stops (exact causal attention) at n <= n_min; seed: selects the
+ * hyperplanes and the sample indices. */
+typedef struct {
+  int32_t b, m, r, causal, n_min;
+  uint64_t seed;
+} ha_params;
+
+/* Byte offsets of the regions of the workspace, for inspection after a forward
+ * call (stage-by-stage parity checks).  `levels` is 1 for the unmasked problem
+ * and log2(n / n_min) for the causal one (0 if n <= n_min); n_cov is the number
+ * of query (= key) rows all nodes of one level cover per head: n (unmasked) or
+ * n/2 (causal).  Node j of level l has s = n_cov >> l rows (causal) and owns
+ * entries [j*s, (j+1)*s) of its level's arrays.
+ *   codes_q, codes_k  uint8  [B*H][n]                 bucket index of each row
+ *   perm_q, perm_k    int32  [levels][B*H][n_cov]     row (index within the head) at each sorted position
+ *   pos_k             int32  [levels][B*H][n_cov]     sorted position (within the node) of each key
+ *   samples           int32  [total_nodes][m]         l_1..l_m of each node, heap order (level l node j -> 2^l - 1 + j)
+ *   proj              float  [d][r]                   hyperplane matrix R
+ *   part_o, part_l    float  [levels][B*H][n_cov][d] / [levels][B*H][n_cov]   causal only: per-level partial outputs and log row sums
+ */
+typedef struct {
+  int32_t levels, total_nodes;
+  int64_t n_cov;
+  size_t codes_q, codes_k, perm_q, perm_k, pos_k, samples, proj, part_o, part_l;
+  size_t total_bytes;
+} ha_ws_layout;
+
+/* Host only.  Validates shape/params as hyperattn_forward does and fills
+ * *layout.  Returns HA_OK or the error hyperattn_forward would return. */
+int ha_workspace_layout(const ha_shape* shape, const ha_params* params, ha_ws_layout* layout);
+
+/* Host only.  Bytes of workspace hyperattn_forward needs; 0 if shape/params are invalid. */
+size_t ha_workspace_bytes(const ha_shape* shape, const ha_params* params);
+
+/* HyperAttention forward (Algorithm 3 in its Section 4 form; Algorithm 4 when
+ * params->causal).  out: [B,H,n,d] of shape->dtype; lse: float [B,H,n].
+ * HA_ERR_SHAPE unless: d in {64,128}; 1 <= r <= 8; b >= 1; 0 <= m <= 4096;
+ * b <= 4096; unmasked: n % b == 0; causal: n_min >= 1 and either n <= n_min
+ * (plain exact causal attention) or n / n_min is a power of two with
+ * n_min % b == 0.  The hyperplanes and sample indices are those
+ * ha_make_projection / ha_make_samples return for params->seed. */
+int hyperattn_forward(const void* Q, const void* K, const void* V, void* out, float* lse,
+                      const ha_shape* shape, const ha_params* params,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same, with the random draws supplied by the caller: R_dev is float [d][r]
+ * (NULL = derive from the seed); samples_dev is int32 [total_nodes][m] in heap
+ * order, node-local key indices in [0, s) (NULL = derive from the seed).  Both
+ * are device memory and are copied into the workspace on `stream`. */
+int hyperattn_forward_ex(const void* Q, const void* K, const void* V, void* out, float* lse,
+                         const ha_shape* shape, const ha_params* params,
+                         const float* R_dev, const int32_t* samples_dev,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Plain exact attention D^-1 A V (Section 1.1), or D_C^-1 (M^C . A) V with
+ * M^C_ij = 1{i >= j} (Section 3.1) when causal != 0; the denominator of the
+ * speed-up ratio.  Any n >= 1; d in {64,128}.  Needs no workspace. */
+int exact_attn_forward(const void* Q, const void* K, const void* V, void* out, float* lse,
+                       const ha_shape* shape, int causal, void* stream);
+
+/* Host only.  The r hyperplane normals used for `seed` (Definition 1 read as
+ * sign-of-Gaussian-projection LSH): R_host[c*r + k], c < d, k < r, i.i.d. N(0,1)
+ * rounded to bf16-representable floats.  Entry (c,k) depends on (seed,c,k) only. */
+int ha_make_projection(uint64_t seed, int32_t d, int32_t r, float* R_host);
+
+/* Host only.  The m key indices, i.i.d. uniform on [0, n_keys) with
+ * replacement (Algorithm 2), that node `node` of recursion level `level` uses
+ * (level 0, node 0 for the unmasked problem); shared by all batches and heads. */
+int ha_make_samples(uint64_t seed, int32_t level, int32_t node, int32_t n_keys, int32_t m,
+                    int32_t* idx_host);
+
+/* ---- single stages, for stage-by-stage parity and profiling ---------------- */
+
+/* sortLSH hashing (Definition 1; Algorithm 1 "hash rows of Q, K"): codes[i] =
+ * Gray-sequence position of the sign word of X[i,:] R.  X: [rows][d] of dtype,
+ * R_dev: float [d][r], codes: uint8 [rows].  Projections accumulate in fp64. */
+int ha_lsh_hash(const void* X, uint8_t* codes, int64_t rows, int32_t d, int32_t dtype,
+                const float* R_dev, int32_t r, void* stream);
+
+/* Algorithm 1's permutation: n_seg independent segments of seg_len consecutive
+ * codes each; stable ascending sort.  perm[g*seg_len + p] = index (within the
+ * segment) of the row at sorted position p; pos = inverse.  seg_len <= 2^24. */
+int ha_seg_sort(const uint8_t* codes, int32_t* perm, int32_t* pos, int32_t n_seg,
+                int32_t seg_len, void* stream);
+
+/* Row permutation ("permuting n rows", Section 4): dst[g][p][:] = src[g][idx[g*n + p]][:]
+ * for g < groups, p < n; rows of d elements of dtype. */
+int ha_gather_rows(const void* src, const int32_t* idx, void* dst, int32_t groups, int32_t n,
+                   int32_t d, int32_t dtype, void* stream);
+
+/* Block-diagonal part alone on inputs ALREADY in sorted order (Section 4,
+ * Implementation Detail: i-th group of b sorted queries against the i-th group
+ * of b sorted keys).  Qs,Ks,Vs: [groups][n][d]; o_b float [groups][n][d] and
+ * lse_b float [groups][n], both in sorted order. */
+int ha_block_attn(const void* Qs, const void* Ks, const void* Vs, float* o_b, float* lse_b,
+                  int32_t groups, int32_t n, int32_t d, int32_t dtype, int32_t b, void* stream);
+
+/* Sampled residual part alone (Algorithm 2's estimator with shared indices):
+ * Qs in sorted order [groups][n][d]; K, V in ORIGINAL order [groups][n][d];
+ * samples int32 [m] (original key indices), pos_k int32 [groups][n].  Sample j
+ * is skipped for the rows of block floor(pos_k[l_j]/b).  o_r float
+ * [groups][n][d], lse_r float [groups][n] (includes log(n/m); -inf and zero
+ * row where nothing is kept), sorted order. */
+int ha_sampled_attn(const void* Qs, const void* K, const void* V, const int32_t* samples,
+                    const int32_t* pos_k, float* o_r, float* lse_r, int32_t groups, int32_t n,
+                    int32_t d, int32_t dtype, int32_t b, int32_t m, void* stream);
+
+/* Shared normaliser and inverse permutation: L = log(exp lse_b + exp lse_r),
+ * out[g][perm_q[g*n+p]] = exp(lse_b-L) o_b[g][p] + exp(lse_r-L) o_r[g][p],
+ * lse[g][perm_q[..]] = L.  out is of dtype. */
+int ha_merge_unpermute(const float* o_b, const float* lse_b, const float* o_r, const float* lse_r,
+                       const int32_t* perm_q, void* out, float* lse, int32_t groups, int32_t n,
+                       int32_t d, int32_t dtype, void* stream);
+
+/* Text for an ha_status value. */
+const char* ha_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HYPERATTN_H */

@@ -186,8 +186,8 @@ def block_part(Qn, Kn, Vn, perm_q, perm_k, b):
 
     Returns (O_b, LSE_b) in the node's original row order: the normalised
     output of the masked entries and the log of their row sum."""
-    s, d = Qn.shape
-    O = np.zeros((s, d), dtype=np.float64)
+    s = Qn.shape[0]
+    O = np.zeros((s, Vn.shape[1]), dtype=np.float64)
     L = np.full(s, -np.inf, dtype=np.float64)
     for t in range(s // b):
         I = perm_q[t * b:(t + 1) * b]
@@ -208,9 +208,9 @@ def sampled_part(Qn, Kn, Vn, pos_q, pos_k, b, samples):
     den_i = (s/m) sum_j (1 - M_{i,l_j}) exp<q_i, k_{l_j}>, and the numerator
     carries v_{l_j} along.  Returns (O_r, LSE_r) with LSE_r = log den (-inf and
     a zero row when every sample of a row is masked, or m = 0)."""
-    s, d = Qn.shape
+    s = Qn.shape[0]
     m = len(samples)
-    O = np.zeros((s, d), dtype=np.float64)
+    O = np.zeros((s, Vn.shape[1]), dtype=np.float64)
     L = np.full(s, -np.inf, dtype=np.float64)
     if m == 0:
         return O, L
@@ -295,12 +295,14 @@ def hyperattn_forward(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0,
     if sample_fn is None:
         def sample_fn(level, node, n_keys):
             return make_samples(seed, level, node, n_keys, m)
-    out = np.empty((B, H, n, d), dtype=np.float64)
+    dv = V.shape[-1]                      # V may be wider or narrower than Q, K
+    out = np.empty((B, H, n, dv), dtype=np.float64)
     lse = np.empty((B, H, n), dtype=np.float64)
     all_codes = np.empty((2, B * H, n), dtype=np.int64)
     all_proj = np.empty((2, B * H, n, r), dtype=np.float64)
     for bh in range(B * H):
-        q, k, v = (x.reshape(B * H, n, d)[bh] for x in (Q, K, V))
+        q, k = (x.reshape(B * H, n, d)[bh] for x in (Q, K))
+        v = V.reshape(B * H, n, dv)[bh]
         pq, pk = lsh_project(q, R), lsh_project(k, R)
         all_proj[0, bh], all_proj[1, bh] = pq, pk
         bits = [lsh_bits(pq), lsh_bits(pk)]
@@ -318,7 +320,7 @@ def hyperattn_forward(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0,
             o, l = node_forward(q, k, v, cq, ck, b, sample_fn(0, 0, n), parts)
             if stages is not None:
                 stages.setdefault("parts", []).append(parts)
-        out.reshape(B * H, n, d)[bh] = o
+        out.reshape(B * H, n, dv)[bh] = o
         lse.reshape(B * H, n)[bh] = l
     if stages is not None:
         stages["codes"] = all_codes

@@ -1,0 +1,294 @@
+"""ctypes binding of libhyperattn.so: argument marshalling only.
+
+Every function has the name and meaning of the C entry point it wraps (see
+include/hyperattn.h).  PyTorch supplies device memory and the current HIP
+stream; every step of the computation runs in the library's kernels.  There is
+no fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, c_char_p, c_float, c_int, c_int32, c_int64, c_size_t, c_uint64, c_void_p
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libhyperattn.so")
+
+HA_BF16, HA_FP32 = 0, 1
+
+
+class HaShape(ctypes.Structure):
+    _fields_ = [("B", c_int32), ("H", c_int32), ("n", c_int32), ("d", c_int32), ("dtype", c_int32)]
+
+
+class HaParams(ctypes.Structure):
+    _fields_ = [("b", c_int32), ("m", c_int32), ("r", c_int32), ("causal", c_int32), ("n_min", c_int32),
+                ("seed", c_uint64)]
+
+
+class HaWsLayout(ctypes.Structure):
+    _fields_ = [("levels", c_int32), ("total_nodes", c_int32), ("n_cov", c_int64),
+                ("codes_q", c_size_t), ("codes_k", c_size_t), ("perm_q", c_size_t), ("perm_k", c_size_t),
+                ("pos_k", c_size_t), ("samples", c_size_t), ("proj", c_size_t), ("part_o", c_size_t),
+                ("part_l", c_size_t), ("total_bytes", c_size_t)]
+
+
+class HyperAttnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+_SIGNATURES = {
+    "ha_workspace_layout": (c_int, [POINTER(HaShape), POINTER(HaParams), POINTER(HaWsLayout)]),
+    "ha_workspace_bytes": (c_size_t, [POINTER(HaShape), POINTER(HaParams)]),
+    "hyperattn_forward": (c_int, [c_void_p] * 5 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_size_t, c_void_p]),
+    "hyperattn_forward_ex": (c_int, [c_void_p] * 5 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_void_p,
+                                                     c_void_p, c_size_t, c_void_p]),
+    "exact_attn_forward": (c_int, [c_void_p] * 5 + [POINTER(HaShape), c_int, c_void_p]),
+    "ha_make_projection": (c_int, [c_uint64, c_int32, c_int32, POINTER(c_float)]),
+    "ha_make_samples": (c_int, [c_uint64, c_int32, c_int32, c_int32, c_int32, POINTER(c_int32)]),
+    "ha_lsh_hash": (c_int, [c_void_p, c_void_p, c_int64, c_int32, c_int32, c_void_p, c_int32, c_void_p]),
+    "ha_seg_sort": (c_int, [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p]),
+    "ha_gather_rows": (c_int, [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_void_p]),
+    "ha_block_attn": (c_int, [c_void_p] * 5 + [c_int32] * 5 + [c_void_p]),
+    "ha_sampled_attn": (c_int, [c_void_p] * 7 + [c_int32] * 6 + [c_void_p]),
+    "ha_merge_unpermute": (c_int, [c_void_p] * 7 + [c_int32] * 4 + [c_void_p]),
+    "ha_strerror": (c_char_p, [c_int]),
+}
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2310_05869_amd.build`")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def exported_symbols():
+    return sorted(_SIGNATURES)
+
+
+def strerror(status: int) -> str:
+    return lib().ha_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise HyperAttnError(status, where)
+
+
+# ---------------------------------------------------------------- host-only calls
+def make_shape(B, H, n, d, dtype) -> HaShape:
+    return HaShape(B, H, n, d, dtype)
+
+
+def make_params(b, m, r, causal=False, n_min=4096, seed=0) -> HaParams:
+    return HaParams(b, m, r, int(bool(causal)), n_min, seed)
+
+
+def ha_workspace_layout(shape: HaShape, params: HaParams) -> HaWsLayout:
+    lay = HaWsLayout()
+    _check(lib().ha_workspace_layout(ctypes.byref(shape), ctypes.byref(params), ctypes.byref(lay)),
+           "ha_workspace_layout")
+    return lay
+
+
+def ha_workspace_bytes(shape: HaShape, params: HaParams) -> int:
+    return int(lib().ha_workspace_bytes(ctypes.byref(shape), ctypes.byref(params)))
+
+
+def ha_make_projection(seed: int, d: int, r: int) -> np.ndarray:
+    R = np.empty((d, r), dtype=np.float32)
+    _check(lib().ha_make_projection(seed, d, r, R.ctypes.data_as(POINTER(c_float))), "ha_make_projection")
+    return R
+
+
+def ha_make_samples(seed: int, level: int, node: int, n_keys: int, m: int) -> np.ndarray:
+    idx = np.empty(max(m, 1), dtype=np.int32)
+    _check(lib().ha_make_samples(seed, level, node, n_keys, m, idx.ctypes.data_as(POINTER(c_int32))),
+           "ha_make_samples")
+    return idx[:m]
+
+
+# ---------------------------------------------------------------- device calls
+def _torch():
+    import torch
+    return torch
+
+
+def _dtype_code(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.bfloat16:
+        return HA_BF16
+    if t.dtype == torch.float32:
+        return HA_FP32
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _dev(t, name):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    torch = _torch()
+    return (torch.cuda.current_stream() if stream is None else stream).cuda_stream
+
+
+def alloc_workspace(shape: HaShape, params: HaParams, device="cuda"):
+    torch = _torch()
+    nbytes = ha_workspace_bytes(shape, params)
+    if nbytes == 0:
+        _check(lib().ha_workspace_layout(ctypes.byref(shape), ctypes.byref(params), ctypes.byref(HaWsLayout())),
+               "ha_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def hyperattn_forward(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0, R=None, samples=None,
+                      workspace=None, out=None, lse=None, stream=None):
+    """out, lse = HyperAttention(Q, K, V).  Q, K, V: [B, H, n, d] device tensors
+    (bf16 or fp32).  R (float32 [d, r]) / samples (int32 [total_nodes, m]) are
+    optional device tensors overriding the seed-derived draws."""
+    torch = _torch()
+    B, H, n, d = Q.shape
+    shape = make_shape(B, H, n, d, _dtype_code(Q))
+    params = make_params(b, m, r, causal, n_min, seed)
+    if workspace is None:
+        workspace = alloc_workspace(shape, params, Q.device)
+    if out is None:
+        out = torch.empty_like(Q)
+    if lse is None:
+        lse = torch.empty((B, H, n), dtype=torch.float32, device=Q.device)
+    ptrs = [_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"), _dev(lse, "lse")]
+    if R is None and samples is None:
+        st = lib().hyperattn_forward(*ptrs, ctypes.byref(shape), ctypes.byref(params), workspace.data_ptr(),
+                                     workspace.numel(), _stream(stream))
+    else:
+        st = lib().hyperattn_forward_ex(*ptrs, ctypes.byref(shape), ctypes.byref(params),
+                                        None if R is None else _dev(R, "R"),
+                                        None if samples is None else _dev(samples, "samples"),
+                                        workspace.data_ptr(), workspace.numel(), _stream(stream))
+    _check(st, "hyperattn_forward")
+    return out, lse
+
+
+def exact_attn_forward(Q, K, V, causal=False, out=None, lse=None, stream=None):
+    torch = _torch()
+    B, H, n, d = Q.shape
+    shape = make_shape(B, H, n, d, _dtype_code(Q))
+    if out is None:
+        out = torch.empty_like(Q)
+    if lse is None:
+        lse = torch.empty((B, H, n), dtype=torch.float32, device=Q.device)
+    _check(lib().exact_attn_forward(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"), _dev(lse, "lse"),
+                                    ctypes.byref(shape), int(bool(causal)), _stream(stream)), "exact_attn_forward")
+    return out, lse
+
+
+def workspace_views(workspace, shape: HaShape, params: HaParams):
+    """Typed views of the workspace regions after a forward call."""
+    torch = _torch()
+    lay = ha_workspace_layout(shape, params)
+    BH, n, d = shape.B * shape.H, shape.n, shape.d
+    cov = lay.levels * BH * lay.n_cov
+
+    def view(off, count, dtype, shp):
+        esz = torch.empty((), dtype=dtype).element_size()
+        return workspace[off:off + count * esz].view(dtype).view(*shp)
+
+    v = {
+        "layout": lay,
+        "codes_q": view(lay.codes_q, BH * n, torch.uint8, (BH, n)),
+        "codes_k": view(lay.codes_k, BH * n, torch.uint8, (BH, n)),
+        "proj": view(lay.proj, d * params.r, torch.float32, (d, params.r)),
+    }
+    if cov:
+        for name in ("perm_q", "perm_k", "pos_k"):
+            v[name] = view(getattr(lay, name), cov, torch.int32, (lay.levels, BH, lay.n_cov))
+        if params.m and lay.total_nodes:
+            v["samples"] = view(lay.samples, lay.total_nodes * params.m, torch.int32, (lay.total_nodes, params.m))
+        if params.causal:
+            v["part_o"] = view(lay.part_o, cov * d, torch.float32, (lay.levels, BH, lay.n_cov, d))
+            v["part_l"] = view(lay.part_l, cov, torch.float32, (lay.levels, BH, lay.n_cov))
+    return v
+
+
+def ha_lsh_hash(X, R, stream=None):
+    """codes (uint8 [rows]) of the rows of X ([..., d]); R: float32 [d, r] device tensor."""
+    torch = _torch()
+    d = X.shape[-1]
+    rows = X.numel() // d
+    codes = torch.empty(rows, dtype=torch.uint8, device=X.device)
+    _check(lib().ha_lsh_hash(_dev(X, "X"), codes.data_ptr(), rows, d, _dtype_code(X), _dev(R, "R"), R.shape[1],
+                             _stream(stream)), "ha_lsh_hash")
+    return codes.view(X.shape[:-1])
+
+
+def ha_seg_sort(codes, stream=None):
+    """codes: uint8 [n_seg, seg_len] -> (perm, pos) int32 [n_seg, seg_len]."""
+    torch = _torch()
+    n_seg, seg_len = codes.shape
+    perm = torch.empty((n_seg, seg_len), dtype=torch.int32, device=codes.device)
+    pos = torch.empty_like(perm)
+    _check(lib().ha_seg_sort(_dev(codes, "codes"), perm.data_ptr(), pos.data_ptr(), n_seg, seg_len,
+                             _stream(stream)), "ha_seg_sort")
+    return perm, pos
+
+
+def ha_gather_rows(src, idx, stream=None):
+    """src: [groups, n, d]; idx: int32 [groups, n] -> dst[g, p] = src[g, idx[g, p]]."""
+    torch = _torch()
+    groups, n, d = src.shape
+    dst = torch.empty_like(src)
+    _check(lib().ha_gather_rows(_dev(src, "src"), _dev(idx, "idx"), dst.data_ptr(), groups, n, d,
+                                _dtype_code(src), _stream(stream)), "ha_gather_rows")
+    return dst
+
+
+def ha_block_attn(Qs, Ks, Vs, b, stream=None):
+    torch = _torch()
+    groups, n, d = Qs.shape
+    o = torch.empty((groups, n, d), dtype=torch.float32, device=Qs.device)
+    l = torch.empty((groups, n), dtype=torch.float32, device=Qs.device)
+    _check(lib().ha_block_attn(_dev(Qs, "Qs"), _dev(Ks, "Ks"), _dev(Vs, "Vs"), o.data_ptr(), l.data_ptr(),
+                               groups, n, d, _dtype_code(Qs), b, _stream(stream)), "ha_block_attn")
+    return o, l
+
+
+def ha_sampled_attn(Qs, K, V, samples, pos_k, b, stream=None):
+    torch = _torch()
+    groups, n, d = Qs.shape
+    m = samples.numel()
+    o = torch.empty((groups, n, d), dtype=torch.float32, device=Qs.device)
+    l = torch.empty((groups, n), dtype=torch.float32, device=Qs.device)
+    _check(lib().ha_sampled_attn(_dev(Qs, "Qs"), _dev(K, "K"), _dev(V, "V"), _dev(samples, "samples"),
+                                 _dev(pos_k, "pos_k"), o.data_ptr(), l.data_ptr(), groups, n, d,
+                                 _dtype_code(Qs), b, m, _stream(stream)), "ha_sampled_attn")
+    return o, l
+
+
+def ha_merge_unpermute(o_b, lse_b, o_r, lse_r, perm_q, dtype, stream=None):
+    torch = _torch()
+    groups, n, d = o_b.shape
+    out = torch.empty((groups, n, d), dtype=dtype, device=o_b.device)
+    lse = torch.empty((groups, n), dtype=torch.float32, device=o_b.device)
+    _check(lib().ha_merge_unpermute(_dev(o_b, "o_b"), _dev(lse_b, "lse_b"), _dev(o_r, "o_r"), _dev(lse_r, "lse_r"),
+                                    _dev(perm_q, "perm_q"), out.data_ptr(), lse.data_ptr(), groups, n, d,
+                                    _dtype_code(out), _stream(stream)), "ha_merge_unpermute")
+    return out, lse

@@ -1,0 +1,391 @@
+// extern "C" entry points of libhyperattn: argument validation, workspace
+// layout and the launch sequence of a forward call.  Everything here is host
+// code; it enqueues kernels on the caller's stream and returns.
+//
+// Launch sequence of hyperattn_forward (Algorithm 3 in its Section 4 form;
+// Algorithm 4 when causal):
+//   prep        R and the per-node sample indices into the workspace
+//   lsh_hash    x2 (Q, K): one pass over all rows; the causal recursion reuses
+//               the same codes at every node (same hyperplanes everywhere)
+//   seg_sort    all nodes of all levels, Q and K, in one launch
+//   attention   all nodes of all levels in one launch (block part + sampled
+//               residual, shared normaliser); unmasked problem: final output;
+//               causal: fp32 partial results per level
+//   base case   causal only: exact causal attention on the n_min diagonal
+//               blocks, merging the partial results of every level per row
+#include <cmath>
+#include <cstring>
+
+#include "ha_common.h"
+
+namespace ha {
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static int make_geometry(const ha_shape* sh, const ha_params* p, Geometry* g) {
+  if (!sh || !p) return HA_ERR_NULL;
+  if (sh->dtype != HA_BF16 && sh->dtype != HA_FP32) return HA_ERR_DTYPE;
+  if (sh->B < 0 || sh->H < 0 || sh->n < 0) return HA_ERR_SHAPE;
+  if (sh->d != 64 && sh->d != 128) return HA_ERR_SHAPE;
+  if (p->r < 1 || p->r > 8) return HA_ERR_SHAPE;
+  if (p->b < 1 || p->b > 4096 || p->m < 0 || p->m > 4096) return HA_ERR_SHAPE;
+  if ((int64_t)sh->B * sh->H > (1 << 20) || sh->n > (1 << 24)) return HA_ERR_SHAPE;
+  g->BH = sh->B * sh->H;
+  g->n = sh->n;
+  g->d = sh->d;
+  g->dtype = sh->dtype;
+  g->b = p->b;
+  g->m = p->m;
+  g->r = p->r;
+  g->causal = p->causal ? 1 : 0;
+  g->n_min = p->n_min;
+  g->base_len = 0;
+  if (!g->causal) {
+    if (sh->n % p->b != 0) return HA_ERR_SHAPE;
+    g->levels = 1;
+    g->total_nodes = 1;
+    g->n_cov = sh->n;
+  } else {
+    if (p->n_min < 1) return HA_ERR_SHAPE;
+    if (sh->n <= p->n_min) {
+      g->levels = 0;
+      g->total_nodes = 0;
+      g->n_cov = 0;
+      g->base_len = sh->n;
+    } else {
+      if (sh->n % p->n_min != 0) return HA_ERR_SHAPE;
+      const int ratio = sh->n / p->n_min;
+      if ((ratio & (ratio - 1)) != 0) return HA_ERR_SHAPE;
+      if (p->n_min % p->b != 0) return HA_ERR_SHAPE;
+      int L = 0;
+      while ((1 << L) < ratio) ++L;
+      g->levels = L;
+      g->total_nodes = (1 << L) - 1;
+      g->n_cov = sh->n / 2;
+      g->base_len = p->n_min;
+    }
+  }
+  if (g->BH == 0 || g->n == 0) {
+    g->levels = 0;
+    g->total_nodes = 0;
+    g->n_cov = 0;
+  }
+  return HA_OK;
+}
+
+static void fill_layout(const Geometry& g, ha_ws_layout* l) {
+  std::memset(l, 0, sizeof(*l));
+  l->levels = g.levels;
+  l->total_nodes = g.total_nodes;
+  l->n_cov = g.n_cov;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off = align256(off + bytes);
+    return at;
+  };
+  const size_t rows = (size_t)g.BH * g.n;
+  const size_t cov = (size_t)g.levels * g.BH * g.n_cov;
+  l->codes_q = take(rows);
+  l->codes_k = take(rows);
+  l->perm_q = take(cov * 4);
+  l->perm_k = take(cov * 4);
+  l->pos_k = take(cov * 4);
+  l->samples = take((size_t)g.total_nodes * g.m * 4);
+  l->proj = take((size_t)g.d * g.r * 4);
+  const bool partials = g.causal && g.levels > 0;
+  l->part_o = take(partials ? cov * g.d * 4 : 0);
+  l->part_l = take(partials ? cov * 4 : 0);
+  l->total_bytes = off < 256 ? 256 : off;
+}
+
+// Definition 1's hyperplane normals: Box-Muller normals from the projection
+// stream, rounded to fp32 and then to bf16 (ties to even); returned as bf16 bits.
+static uint16_t projection_bits(uint64_t seed, int c, int k) {
+  const uint64_t ctr = 2ull * (8ull * (uint64_t)c + (uint64_t)k);
+  const double u1 = ((double)(rand_u64(seed, kStreamProjection, ctr) >> 11) + 0.5) * 0x1.0p-53;
+  const double u2 = ((double)(rand_u64(seed, kStreamProjection, ctr + 1) >> 11) + 0.5) * 0x1.0p-53;
+  const double z = std::sqrt(-2.0 * std::log(u1)) * std::cos(2.0 * M_PI * u2);
+  const float f = (float)z;
+  uint32_t bits;
+  std::memcpy(&bits, &f, 4);
+  bits += 0x7FFFu + ((bits >> 16) & 1u);
+  return (uint16_t)(bits >> 16);
+}
+
+static bool use_mfma(const Geometry& g) { return g.dtype == HA_BF16; }
+
+static int run_attention(const AttnArgs& a, int mode, hipStream_t st) {
+  return use_mfma(a.g) ? launch_attn_mfma(a, mode, st) : launch_attn_generic(a, mode, st);
+}
+
+static int forward_impl(const void* Q, const void* K, const void* V, void* out, float* lse, const ha_shape* sh,
+                        const ha_params* p, const float* R_dev, const int32_t* samples_dev, void* ws,
+                        size_t ws_bytes, void* stream) {
+  Geometry g;
+  int rc = make_geometry(sh, p, &g);
+  if (rc != HA_OK) return rc;
+  if (g.BH == 0 || g.n == 0) return HA_OK;
+  if (!Q || !K || !V || !out || !lse) return HA_ERR_NULL;
+  ha_ws_layout lay;
+  fill_layout(g, &lay);
+  if (!ws) return HA_ERR_NULL;
+  if (ws_bytes < lay.total_bytes || ((uintptr_t)ws & 255) != 0) return HA_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  unsigned char* base = (unsigned char*)ws;
+  uint8_t* codes_q = base + lay.codes_q;
+  uint8_t* codes_k = base + lay.codes_k;
+  int32_t* perm_q = (int32_t*)(base + lay.perm_q);
+  int32_t* perm_k = (int32_t*)(base + lay.perm_k);
+  int32_t* pos_k = (int32_t*)(base + lay.pos_k);
+  int32_t* samples = (int32_t*)(base + lay.samples);
+  float* proj = (float*)(base + lay.proj);
+  float* part_o = (float*)(base + lay.part_o);
+  float* part_l = (float*)(base + lay.part_l);
+  const int64_t head_stride = (int64_t)g.n * g.d;
+
+  if (g.levels > 0) {
+    uint16_t Rb[1024];
+    if (!R_dev)
+      for (int c = 0; c < g.d; ++c)
+        for (int k = 0; k < g.r; ++k) Rb[c * g.r + k] = projection_bits(p->seed, c, k);
+    rc = launch_prep(proj, R_dev, R_dev ? nullptr : Rb, samples, samples_dev, g, p->seed, st);
+    if (rc != HA_OK) return rc;
+    rc = launch_lsh_hash(Q, codes_q, (int64_t)g.BH * g.n, g.d, g.dtype, proj, g.r, st);
+    if (rc != HA_OK) return rc;
+    rc = launch_lsh_hash(K, codes_k, (int64_t)g.BH * g.n, g.d, g.dtype, proj, g.r, st);
+    if (rc != HA_OK) return rc;
+    rc = launch_seg_sort_nodes(codes_q, codes_k, perm_q, perm_k, pos_k, g, st);
+    if (rc != HA_OK) return rc;
+
+    AttnArgs a{};
+    a.Q = Q;
+    a.K = K;
+    a.V = V;
+    a.q_bh_stride = a.k_bh_stride = head_stride;
+    a.perm_q = perm_q;
+    a.perm_k = perm_k;
+    a.pos_k = pos_k;
+    a.samples = g.m > 0 ? samples : nullptr;
+    a.use_block = 1;
+    a.out_bh_stride = head_stride;
+    a.scatter_out = 1;
+    a.g = g;
+    if (g.causal) {
+      a.part_o = part_o;
+      a.part_l = part_l;
+    } else {
+      a.out = out;
+      a.lse = lse;
+    }
+    rc = run_attention(a, kModeNode, st);
+    if (rc != HA_OK) return rc;
+  }
+  if (g.causal) {
+    AttnArgs a{};
+    a.Q = Q;
+    a.K = K;
+    a.V = V;
+    a.q_bh_stride = a.k_bh_stride = head_stride;
+    a.out = out;
+    a.lse = lse;
+    a.out_bh_stride = head_stride;
+    a.part_o = part_o;
+    a.part_l = part_l;
+    a.g = g;
+    a.exact_rows_q = a.exact_rows_k = g.n;
+    a.exact_block = g.base_len;
+    a.exact_causal = 1;
+    a.merge_levels = g.levels;
+    rc = run_attention(a, kModeExact, st);
+    if (rc != HA_OK) return rc;
+  }
+  return HA_OK;
+}
+
+static int stage_geometry(Geometry* g, int groups, int n, int d, int dtype, int b, int m) {
+  if (dtype != HA_BF16 && dtype != HA_FP32) return HA_ERR_DTYPE;
+  if (d != 64 && d != 128) return HA_ERR_SHAPE;
+  if (groups < 0 || n < 0 || b < 1 || b > 4096 || m < 0 || m > 4096) return HA_ERR_SHAPE;
+  if (n % b != 0) return HA_ERR_SHAPE;
+  std::memset(g, 0, sizeof(*g));
+  g->BH = groups;
+  g->n = n;
+  g->d = d;
+  g->dtype = dtype;
+  g->b = b;
+  g->m = m;
+  g->r = 1;
+  g->levels = 1;
+  g->total_nodes = 1;
+  g->n_cov = n;
+  return HA_OK;
+}
+
+}  // namespace ha
+
+using namespace ha;
+
+extern "C" {
+
+int ha_workspace_layout(const ha_shape* shape, const ha_params* params, ha_ws_layout* layout) {
+  if (!layout) return HA_ERR_NULL;
+  Geometry g;
+  const int rc = make_geometry(shape, params, &g);
+  if (rc != HA_OK) return rc;
+  fill_layout(g, layout);
+  return HA_OK;
+}
+
+size_t ha_workspace_bytes(const ha_shape* shape, const ha_params* params) {
+  ha_ws_layout l;
+  return ha_workspace_layout(shape, params, &l) == HA_OK ? l.total_bytes : 0;
+}
+
+int hyperattn_forward(const void* Q, const void* K, const void* V, void* out, float* lse, const ha_shape* shape,
+                      const ha_params* params, void* workspace, size_t workspace_bytes, void* stream) {
+  return forward_impl(Q, K, V, out, lse, shape, params, nullptr, nullptr, workspace, workspace_bytes, stream);
+}
+
+int hyperattn_forward_ex(const void* Q, const void* K, const void* V, void* out, float* lse,
+                         const ha_shape* shape, const ha_params* params, const float* R_dev,
+                         const int32_t* samples_dev, void* workspace, size_t workspace_bytes, void* stream) {
+  return forward_impl(Q, K, V, out, lse, shape, params, R_dev, samples_dev, workspace, workspace_bytes, stream);
+}
+
+int exact_attn_forward(const void* Q, const void* K, const void* V, void* out, float* lse, const ha_shape* sh,
+                       int causal, void* stream) {
+  if (!sh) return HA_ERR_NULL;
+  if (sh->dtype != HA_BF16 && sh->dtype != HA_FP32) return HA_ERR_DTYPE;
+  if (sh->B < 0 || sh->H < 0 || sh->n < 0 || (sh->d != 64 && sh->d != 128)) return HA_ERR_SHAPE;
+  if ((int64_t)sh->B * sh->H > (1 << 20) || sh->n > (1 << 24)) return HA_ERR_SHAPE;
+  if (sh->B == 0 || sh->H == 0 || sh->n == 0) return HA_OK;
+  if (!Q || !K || !V || !out || !lse) return HA_ERR_NULL;
+  AttnArgs a{};
+  a.Q = Q;
+  a.K = K;
+  a.V = V;
+  a.q_bh_stride = a.k_bh_stride = a.out_bh_stride = (int64_t)sh->n * sh->d;
+  a.out = out;
+  a.lse = lse;
+  a.g.BH = sh->B * sh->H;
+  a.g.n = sh->n;
+  a.g.d = sh->d;
+  a.g.dtype = sh->dtype;
+  a.g.b = 1;
+  a.exact_rows_q = a.exact_rows_k = sh->n;
+  a.exact_block = sh->n;
+  a.exact_causal = causal ? 1 : 0;
+  a.merge_levels = 0;
+  return run_attention(a, kModeExact, (hipStream_t)stream);
+}
+
+int ha_make_projection(uint64_t seed, int32_t d, int32_t r, float* R_host) {
+  if (!R_host) return HA_ERR_NULL;
+  if (d < 1 || d > 128 || r < 1 || r > 8) return HA_ERR_SHAPE;
+  for (int c = 0; c < d; ++c)
+    for (int k = 0; k < r; ++k) {
+      const uint32_t bits = (uint32_t)projection_bits(seed, c, k) << 16;
+      std::memcpy(&R_host[c * r + k], &bits, 4);
+    }
+  return HA_OK;
+}
+
+int ha_make_samples(uint64_t seed, int32_t level, int32_t node, int32_t n_keys, int32_t m, int32_t* idx_host) {
+  if (m > 0 && !idx_host) return HA_ERR_NULL;
+  if (level < 0 || level > 30 || node < 0 || node >= (1 << level) || n_keys < 1 || m < 0) return HA_ERR_SHAPE;
+  for (int j = 0; j < m; ++j) idx_host[j] = sample_index(seed, level, node, n_keys, j);
+  return HA_OK;
+}
+
+int ha_lsh_hash(const void* X, uint8_t* codes, int64_t rows, int32_t d, int32_t dtype, const float* R_dev,
+                int32_t r, void* stream) {
+  if (dtype != HA_BF16 && dtype != HA_FP32) return HA_ERR_DTYPE;
+  if (rows < 0 || (d != 64 && d != 128) || r < 1 || r > 8) return HA_ERR_SHAPE;
+  if (rows == 0) return HA_OK;
+  if (!X || !codes || !R_dev) return HA_ERR_NULL;
+  return launch_lsh_hash(X, codes, rows, d, dtype, R_dev, r, (hipStream_t)stream);
+}
+
+int ha_seg_sort(const uint8_t* codes, int32_t* perm, int32_t* pos, int32_t n_seg, int32_t seg_len,
+                void* stream) {
+  if (n_seg < 0 || seg_len < 0 || seg_len > (1 << 24)) return HA_ERR_SHAPE;
+  if (n_seg == 0 || seg_len == 0) return HA_OK;
+  if (!codes || !perm || !pos) return HA_ERR_NULL;
+  return launch_seg_sort_flat(codes, perm, pos, n_seg, seg_len, (hipStream_t)stream);
+}
+
+int ha_gather_rows(const void* src, const int32_t* idx, void* dst, int32_t groups, int32_t n, int32_t d,
+                   int32_t dtype, void* stream) {
+  if (dtype != HA_BF16 && dtype != HA_FP32) return HA_ERR_DTYPE;
+  if (groups < 0 || n < 0 || (d != 64 && d != 128)) return HA_ERR_SHAPE;
+  if (groups == 0 || n == 0) return HA_OK;
+  if (!src || !idx || !dst) return HA_ERR_NULL;
+  return launch_gather_rows(src, idx, dst, groups, n, d, dtype, (hipStream_t)stream);
+}
+
+int ha_block_attn(const void* Qs, const void* Ks, const void* Vs, float* o_b, float* lse_b, int32_t groups,
+                  int32_t n, int32_t d, int32_t dtype, int32_t b, void* stream) {
+  Geometry g;
+  const int rc = stage_geometry(&g, groups, n, d, dtype, b, 0);
+  if (rc != HA_OK) return rc;
+  if (groups == 0 || n == 0) return HA_OK;
+  if (!Qs || !Ks || !Vs || !o_b || !lse_b) return HA_ERR_NULL;
+  AttnArgs a{};
+  a.Q = Qs;
+  a.K = Ks;
+  a.V = Vs;
+  a.q_bh_stride = a.k_bh_stride = a.out_bh_stride = (int64_t)n * d;
+  a.use_block = 1;
+  a.part_o = o_b;
+  a.part_l = lse_b;
+  a.g = g;
+  return run_attention(a, kModeNode, (hipStream_t)stream);
+}
+
+int ha_sampled_attn(const void* Qs, const void* K, const void* V, const int32_t* samples, const int32_t* pos_k,
+                    float* o_r, float* lse_r, int32_t groups, int32_t n, int32_t d, int32_t dtype, int32_t b,
+                    int32_t m, void* stream) {
+  Geometry g;
+  const int rc = stage_geometry(&g, groups, n, d, dtype, b, m);
+  if (rc != HA_OK) return rc;
+  if (groups == 0 || n == 0) return HA_OK;
+  if (!Qs || !K || !V || !o_r || !lse_r || !pos_k || (m > 0 && !samples)) return HA_ERR_NULL;
+  AttnArgs a{};
+  a.Q = Qs;
+  a.K = K;
+  a.V = V;
+  a.q_bh_stride = a.k_bh_stride = a.out_bh_stride = (int64_t)n * d;
+  a.pos_k = pos_k;
+  a.samples = m > 0 ? samples : nullptr;
+  a.use_block = 0;
+  a.part_o = o_r;
+  a.part_l = lse_r;
+  a.g = g;
+  return run_attention(a, kModeNode, (hipStream_t)stream);
+}
+
+int ha_merge_unpermute(const float* o_b, const float* lse_b, const float* o_r, const float* lse_r,
+                       const int32_t* perm_q, void* out, float* lse, int32_t groups, int32_t n, int32_t d,
+                       int32_t dtype, void* stream) {
+  if (dtype != HA_BF16 && dtype != HA_FP32) return HA_ERR_DTYPE;
+  if (groups < 0 || n < 0 || (d != 64 && d != 128)) return HA_ERR_SHAPE;
+  if (groups == 0 || n == 0) return HA_OK;
+  if (!o_b || !lse_b || !o_r || !lse_r || !perm_q || !out || !lse) return HA_ERR_NULL;
+  return launch_merge_unpermute(o_b, lse_b, o_r, lse_r, perm_q, out, lse, groups, n, d, dtype,
+                                (hipStream_t)stream);
+}
+
+const char* ha_strerror(int status) {
+  switch (status) {
+    case HA_OK: return "ok";
+    case HA_ERR_NULL: return "a required pointer is NULL";
+    case HA_ERR_DTYPE: return "unsupported dtype";
+    case HA_ERR_SHAPE: return "unsupported shape or parameters";
+    case HA_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case HA_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

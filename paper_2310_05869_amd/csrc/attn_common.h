@@ -1,0 +1,206 @@
+// Work decomposition and key-list construction shared by the MFMA and the
+// generic attention kernels.
+//
+// One workgroup = one tile of QT consecutive sorted query positions inside one
+// b-block of one node (node mode), or QT consecutive query rows of one diagonal
+// block (exact mode).  In node mode the workgroup attends to ONE list of keys:
+//   [0, nb)        the b keys of the block, M^H of Algorithm 1, bias 0
+//   [nb, nkeys)    the sampled keys l_j of Algorithm 2 that are NOT in the
+//                  row's own block (factor 1 - M_{i,l_j}), bias log(s/m)
+// so the block part, the residual estimate and their shared normaliser come out
+// of a single softmax pass: sum_block exp(S) + (s/m) sum_kept exp(S).
+#pragma once
+
+#include "ha_common.h"
+
+namespace ha {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct TileWork {
+  int bh;
+  int rows_valid;    // query rows of this tile that exist
+  // node mode
+  int level, t, p0;  // block index within the node, first sorted position (node-local) of the tile
+  NodeRef nr;
+  int64_t seg_off;   // offset of the node in perm_q / perm_k / pos_k / part_*
+  // exact mode
+  int q0;            // first query row (within the head)
+  int k0, k1;        // key rows [k0, k1) this tile attends to (before causal masking)
+};
+
+// XCD-aware ordering: consecutive workgroup ids are dealt round-robin to the 8
+// XCDs, each with its own L2.  Give every XCD a contiguous range of logical
+// tiles so that tiles sharing K/V (same block, same node) meet in one L2.
+__device__ inline int logical_block(int bid, int total) {
+  if (total % 8 != 0) return bid;
+  return (bid & 7) * (total >> 3) + (bid >> 3);
+}
+
+template <int QT>
+__device__ inline TileWork decode_node_tile(const AttnArgs& a, int idx) {
+  const Geometry& g = a.g;
+  TileWork w{};
+  const int tpb = (g.b + QT - 1) / QT;  // tiles per block
+  const int tiles_per_level = (g.n_cov / g.b) * tpb;
+  const int tile = idx % tiles_per_level;
+  const int rest = idx / tiles_per_level;
+  w.bh = rest % g.BH;
+  w.level = rest / g.BH;
+  const int blk = tile / tpb, chunk = tile % tpb;
+  const NodeRef probe = node_ref(g, w.level, 0);
+  const int bpn = probe.s / g.b;  // blocks per node
+  const int node = blk / bpn;
+  w.t = blk % bpn;
+  w.nr = node_ref(g, w.level, node);
+  w.p0 = w.t * g.b + chunk * QT;
+  w.rows_valid = min(QT, g.b - chunk * QT);
+  w.seg_off = ((int64_t)w.level * g.BH + w.bh) * g.n_cov + (int64_t)node * w.nr.s;
+  return w;
+}
+
+template <int QT>
+__host__ __device__ inline int node_grid(const Geometry& g) {
+  const int tpb = (g.b + QT - 1) / QT;
+  return g.levels * g.BH * (g.n_cov / g.b) * tpb;
+}
+
+template <int QT>
+__device__ inline TileWork decode_exact_tile(const AttnArgs& a, int idx) {
+  TileWork w{};
+  const int eb = a.exact_block;
+  const int tpb = (eb + QT - 1) / QT;
+  const int nblk = (a.exact_rows_q + eb - 1) / eb;
+  const int qt = tpb - 1 - (idx % tpb);  // heavy (late) causal tiles first
+  const int rest = idx / tpb;
+  const int blk = rest % nblk;
+  w.bh = rest / nblk;
+  w.q0 = blk * eb + qt * QT;
+  const int blk_rows = min(eb, a.exact_rows_q - blk * eb);
+  w.rows_valid = max(0, min(QT, blk_rows - qt * QT));
+  w.k0 = blk * eb;
+  w.k1 = min(a.exact_rows_k, (blk + 1) * eb);
+  if (a.exact_causal) w.k1 = min(w.k1, w.q0 + w.rows_valid);
+  return w;
+}
+
+template <int QT>
+__host__ __device__ inline int exact_grid(const AttnArgs& a) {
+  const int eb = a.exact_block;
+  const int tpb = (eb + QT - 1) / QT;
+  const int nblk = (a.exact_rows_q + eb - 1) / eb;
+  return a.g.BH * nblk * tpb;
+}
+
+// Builds the key list of a node tile in LDS.  `list` has room for b + m entries
+// rounded up to a multiple of 64; `scratch` for (NT/64 + 1) ints.  All NT
+// threads call it; on return (after its final barrier) list[0..pad) holds row
+// indices within the head, *nb_out the block keys and the return value nkeys.
+template <int NT>
+__device__ inline int build_key_list(const AttnArgs& a, const TileWork& w, int32_t* list, int32_t* scratch,
+                                     int* nb_out) {
+  const Geometry& g = a.g;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  constexpr int NW = NT / 64;
+  int nb = 0;
+  if (a.use_block) {
+    nb = g.b;
+    for (int i = tid; i < nb; i += NT)
+      list[i] = a.perm_k ? a.perm_k[w.seg_off + w.t * g.b + i] : w.nr.k_start + w.t * g.b + i;
+  }
+  int base = nb;
+  const int m = (a.samples != nullptr) ? g.m : 0;
+  for (int j0 = 0; j0 < m; j0 += NT) {
+    const int j = j0 + tid;
+    int l = 0;
+    bool keep = false;
+    if (j < m) {
+      l = a.samples[(int64_t)w.nr.heap * g.m + j];
+      const int pk = a.pos_k ? a.pos_k[w.seg_off + l] : l;
+      keep = (pk / g.b) != w.t;  // 1 - M_{i, l_j}: same for every row of the block
+    }
+    const unsigned long long bal = __ballot(keep);
+    if (lane == 0) scratch[wave] = __popcll(bal);
+    __syncthreads();
+    int before = 0, total = 0;
+#pragma unroll
+    for (int ww = 0; ww < NW; ++ww) {
+      const int c = scratch[ww];
+      if (ww < wave) before += c;
+      total += c;
+    }
+    if (keep) list[base + before + __popcll(bal & ((1ull << lane) - 1ull))] = w.nr.k_start + l;
+    base += total;
+    __syncthreads();
+  }
+  const int nkeys = base;
+  const int pad = (nkeys + 63) & ~63;
+  for (int i = nkeys + tid; i < pad; i += NT) list[i] = w.nr.k_start;  // loadable, masked by position
+  __syncthreads();
+  *nb_out = nb;
+  return nkeys;
+}
+
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+  typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+  typedef float f2 __attribute__((ext_vector_type(2)));
+  const bf2 p = __builtin_convertvector((f2){lo, hi}, bf2);
+  return *reinterpret_cast<const uint32_t*>(&p);
+}
+
+// Where a finished query row goes.
+struct RowDest {
+  bool valid;
+  int64_t out_row;   // row index into out / lse (head offset included), final output
+  int64_t part_row;  // row index into part_o / part_l (node mode partial)
+  int row_in_head;   // exact mode: for the per-level merge
+};
+
+__device__ inline RowDest node_row_dest(const AttnArgs& a, const TileWork& w, int r_in_tile) {
+  RowDest d{};
+  d.valid = r_in_tile < w.rows_valid;
+  const int p = w.p0 + (d.valid ? r_in_tile : 0);
+  const int row = (a.scatter_out && a.perm_q) ? a.perm_q[w.seg_off + p] : w.nr.q_start + p;
+  d.row_in_head = row;
+  d.out_row = (int64_t)w.bh * (a.out_bh_stride / a.g.d) + row;
+  d.part_row = w.seg_off + (row - w.nr.q_start);
+  return d;
+}
+
+// Causal merge (Algorithm 4): the row sum of row i is the base-case row sum
+// plus the row sums of the off-diagonal nodes it belongs to.  Level l touches
+// row i iff i lies in the second half of its level-l node; *prow is then the
+// row's index in part_o / part_l.
+__device__ inline bool level_touches(const Geometry& g, int bh, int i, int l, int64_t* prow) {
+  const int s = g.n >> (l + 1);
+  *prow = ((int64_t)l * g.BH + bh) * g.n_cov + (int64_t)(i / (2 * s)) * s + (i % s);
+  return ((i / s) & 1) != 0;
+}
+
+// Combined log row sum of the base-case result (lse_own) and the partials;
+// *mx_out is the reference the weights exp(l - mx) / den are taken against.
+__device__ inline float merged_lse(const AttnArgs& a, int bh, int i, float lse_own, float* mx_out,
+                                   float* den_out) {
+  float mx = lse_own;
+  for (int l = 0; l < a.merge_levels; ++l) {
+    int64_t pr;
+    if (level_touches(a.g, bh, i, l, &pr)) mx = fmaxf(mx, a.part_l[pr]);
+  }
+  if (mx == -INFINITY) {
+    *mx_out = 0.f;
+    *den_out = 1.f;
+    return -INFINITY;
+  }
+  float den = expf(lse_own - mx);
+  for (int l = 0; l < a.merge_levels; ++l) {
+    int64_t pr;
+    if (level_touches(a.g, bh, i, l, &pr)) den += expf(a.part_l[pr] - mx);
+  }
+  *mx_out = mx;
+  *den_out = den;
+  return mx + logf(den);
+}
+
+}  // namespace ha

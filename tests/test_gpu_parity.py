@@ -1,0 +1,288 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the
+same seeded inputs.  Integer stages (bucket codes, permutations, gathers) must
+be bit-exact; floating point outputs must be within the stated tolerance
+(bf16: 2e-3 + half a bf16 ulp of the result; fp32: 1e-5 + 1e-5 |result|)."""
+import numpy as np
+import pytest
+
+import synth_inputs
+from oracle import hyperattn_oracle as orc
+from ha_testutil import (assert_close, assert_lse_close, compare_codes, have_gpu, run_oracle, to_device, to_host)
+
+pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not have_gpu(), reason="needs a GPU")]
+
+
+@pytest.fixture(scope="module")
+def ha():
+    import paper_2310_05869_amd as mod
+    mod.lib()
+    return mod
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    return t
+
+
+# ------------------------------------------------------------------ a1: lsh_hash
+@pytest.mark.parametrize("dtype,d,r,rows", [("bf16", 128, 7, 4099), ("bf16", 64, 7, 777), ("bf16", 128, 8, 64),
+                                           ("bf16", 64, 1, 5), ("fp32", 64, 7, 1024), ("fp32", 128, 3, 1001),
+                                           ("bf16", 128, 7, 1)])
+def test_lsh_hash_bit_exact(ha, torch, dtype, d, r, rows):
+    print(f"lsh_hash {dtype} d={d} r={r} rows={rows}", flush=True)
+    X = synth_inputs.iid_qkv(1, 1, rows, d, dtype, seed=7)[0].reshape(rows, d)
+    R = orc.make_projection(5, d, r)
+    p = orc.lsh_project(X, R)
+    ref = orc.lsh_codes(p, r)
+    got = ha.ha_lsh_hash(to_device(X, dtype), torch.from_numpy(R.astype(np.float32)).cuda())
+    got = got.cpu().numpy().astype(np.int64)
+    bad = np.nonzero(got != ref)[0]
+    for i in bad:
+        assert np.abs(p[i]).min() < 1e-6
+    print(f"  disagreements (all with |p|<1e-6): {len(bad)}", flush=True)
+    assert len(bad) <= 1
+
+
+def test_lsh_hash_arbitrary_fp32_R_and_zero_rows(ha, torch):
+    rng = np.random.default_rng(0)
+    d, r, rows = 64, 6, 300
+    X = rng.standard_normal((rows, d)).astype(np.float32)
+    X[5] = 0.0                      # projections exactly 0 -> all bits 0 -> bucket 0
+    R = rng.standard_normal((d, r)).astype(np.float32)
+    ref = orc.lsh_codes(orc.lsh_project(X, R), r)
+    got = ha.ha_lsh_hash(torch.from_numpy(X).cuda(), torch.from_numpy(R).cuda()).cpu().numpy()
+    np.testing.assert_array_equal(got, ref)
+    assert got[5] == 0
+
+
+# ------------------------------------------------------------------ a2: seg_sort
+@pytest.mark.parametrize("n_seg,seg_len,nb", [(3, 1, 4), (2, 63, 128), (5, 64, 128), (4, 65, 2), (3, 1000, 128),
+                                              (2, 40000, 256), (1, 70000, 1), (6, 4096, 128)])
+def test_seg_sort_bit_exact(ha, torch, n_seg, seg_len, nb):
+    print(f"seg_sort n_seg={n_seg} seg_len={seg_len} buckets={nb}", flush=True)
+    rng = np.random.default_rng(seg_len)
+    codes = rng.integers(0, nb, size=(n_seg, seg_len)).astype(np.uint8)
+    perm, pos = ha.ha_seg_sort(torch.from_numpy(codes).cuda())
+    perm, pos = perm.cpu().numpy(), pos.cpu().numpy()
+    for g in range(n_seg):
+        rp, rq = orc.sort_lsh(codes[g])
+        np.testing.assert_array_equal(perm[g], rp)
+        np.testing.assert_array_equal(pos[g], rq)
+
+
+# ------------------------------------------------------------------ a3: gather
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp32", 64)])
+def test_gather_rows_exact(ha, torch, dtype, d):
+    groups, n = 3, 517
+    X = synth_inputs.iid_qkv(1, groups, n, d, dtype, seed=3)[0][0]
+    idx = np.stack([np.random.default_rng(g).permutation(n) for g in range(groups)]).astype(np.int32)
+    got = to_host(ha.ha_gather_rows(to_device(X, dtype), torch.from_numpy(idx).cuda()))
+    for g in range(groups):
+        np.testing.assert_array_equal(got[g], X[g][idx[g]])
+
+
+# ------------------------------------------------------------------ a4-a6: stages
+STAGE_CASES = [("bf16", 128, 512, 128, 96), ("bf16", 64, 768, 256, 512), ("fp32", 64, 256, 64, 64),
+               ("bf16", 128, 384, 96, 40), ("fp32", 128, 192, 48, 7)]
+
+
+@pytest.mark.parametrize("dtype,d,n,b,m", STAGE_CASES)
+def test_block_sampled_merge_stages(ha, torch, dtype, d, n, b, m):
+    """Stage entry points on one node, in the order of the Section 4 pipeline:
+    sort -> gather -> block part / sampled part (sorted order) -> merge."""
+    print(f"stages {dtype} d={d} n={n} b={b} m={m}", flush=True)
+    groups = 2
+    Q, K, V = (x[0] for x in synth_inputs.iid_qkv(1, groups, n, d, dtype, seed=21))
+    r = 5
+    R = orc.make_projection(1, d, r)
+    Rd = torch.from_numpy(R.astype(np.float32)).cuda()
+    Qd, Kd, Vd = (to_device(x, dtype) for x in (Q, K, V))
+    cq = ha.ha_lsh_hash(Qd, Rd)
+    ck = ha.ha_lsh_hash(Kd, Rd)
+    perm_q, _ = ha.ha_seg_sort(cq)
+    perm_k, pos_k = ha.ha_seg_sort(ck)
+    Qs = ha.ha_gather_rows(Qd, perm_q)
+    Ks = ha.ha_gather_rows(Kd, perm_k)
+    Vs = ha.ha_gather_rows(Vd, perm_k)
+    samples = orc.make_samples(3, 0, 0, n, m).astype(np.int32)
+    o_b, l_b = ha.ha_block_attn(Qs, Ks, Vs, b)
+    o_r, l_r = ha.ha_sampled_attn(Qs, Kd, Vd, torch.from_numpy(samples).cuda(), pos_k, b)
+    out_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+    out, lse = ha.ha_merge_unpermute(o_b, l_b, o_r, l_r, perm_q, out_dtype)
+    for g in range(groups):
+        pq, posq = orc.sort_lsh(orc.lsh_codes(orc.lsh_project(Q[g], R), r))
+        pk, posk = orc.sort_lsh(orc.lsh_codes(orc.lsh_project(K[g], R), r))
+        np.testing.assert_array_equal(perm_q[g].cpu().numpy(), pq)
+        np.testing.assert_array_equal(perm_k[g].cpu().numpy(), pk)
+        q64, k64, v64 = (x[g].astype(np.float64) for x in (Q, K, V))
+        Ob, Lb = orc.block_part(q64, k64, v64, pq, pk, b)
+        Or, Lr = orc.sampled_part(q64, k64, v64, posq, posk, b, samples)
+        # stage outputs are in sorted order
+        assert_close(to_host(o_b[g]), Ob[pq], "fp32" if dtype == "fp32" else "bf16", "o_b")
+        assert_lse_close(to_host(l_b[g]), Lb[pq], dtype, "lse_b")
+        assert_close(to_host(o_r[g]), Or[pq], "fp32" if dtype == "fp32" else "bf16", "o_r")
+        assert_lse_close(to_host(l_r[g]), Lr[pq], dtype, "lse_r")
+        Om, Lm = orc.merge_parts(Ob, Lb, Or, Lr)
+        assert_close(to_host(out[g]), Om, dtype, "merged out")
+        assert_lse_close(to_host(lse[g]), Lm, dtype, "merged lse")
+
+
+# ------------------------------------------------------------------ a8: exact attention
+@pytest.mark.parametrize("dtype,d,n,causal", [("bf16", 128, 300, False), ("bf16", 128, 300, True),
+                                             ("bf16", 64, 1000, True), ("bf16", 64, 129, False),
+                                             ("fp32", 64, 200, True), ("fp32", 128, 77, False),
+                                             ("bf16", 128, 1, True), ("bf16", 128, 1024, True)])
+def test_exact_attn_matches_definition(ha, torch, dtype, d, n, causal):
+    print(f"exact {dtype} d={d} n={n} causal={causal}", flush=True)
+    Q, K, V = synth_inputs.iid_qkv(1, 2, n, d, dtype, seed=31)
+    out, lse = ha.exact_attn_forward(*(to_device(x, dtype) for x in (Q, K, V)), causal=causal)
+    for h in range(2):
+        ro, rl = orc.exact_attention(Q[0, h], K[0, h], V[0, h], causal)
+        assert_close(to_host(out[0, h]), ro, dtype, "exact out")
+        assert_lse_close(to_host(lse[0, h]), rl, dtype, "exact lse")
+
+
+# ------------------------------------------------------------------ whole forward
+def _forward_and_compare(ha, torch, cfg, Q, K, V, R=None, samples=None, sample_fn=None, p_rounding_term=False):
+    """p_rounding_term: widen the bf16 tolerance by 2^-8 sum_j p_j|v_j| (inputs with large |V|)."""
+    dtype = cfg["dtype"]
+    B, H, n, d = Q.shape
+    shape = ha.make_shape(B, H, n, d, ha.HA_BF16 if dtype == "bf16" else ha.HA_FP32)
+    params = ha.make_params(cfg["b"], cfg["m"], cfg["r"], cfg["causal"], cfg["n_min"], cfg["seed"])
+    ws = ha.alloc_workspace(shape, params)
+    Rd = None if R is None else torch.from_numpy(R.astype(np.float32)).cuda()
+    sd = None if samples is None else torch.from_numpy(samples.astype(np.int32)).cuda()
+    out, lse = ha.hyperattn_forward(*(to_device(x, dtype) for x in (Q, K, V)), cfg["b"], cfg["m"], cfg["r"],
+                                    causal=cfg["causal"], n_min=cfg["n_min"], seed=cfg["seed"], R=Rd, samples=sd,
+                                    workspace=ws)
+    torch.cuda.synchronize()
+    views = ha.workspace_views(ws, shape, params)
+    lay = views["layout"]
+    # stage 1: codes
+    stages = {}
+    ref_out, ref_lse, absv = run_oracle(Q, K, V, cfg, R=R, sample_fn=sample_fn, stages=stages, with_absv=True)
+    flips = []
+    if lay.levels > 0:
+        gpu_codes = np.stack([views["codes_q"].cpu().numpy(), views["codes_k"].cpu().numpy()])
+        flips = compare_codes(gpu_codes, stages, cfg["r"])
+        if flips:
+            print(f"  replaying {len(flips)} near-zero sign bits in the oracle", flush=True)
+            stages = {}
+            ref_out, ref_lse, absv = run_oracle(Q, K, V, cfg, R=R, sample_fn=sample_fn, flip=flips, stages=stages,
+                                                with_absv=True)
+        # stage 2: permutations of every node
+        pq, pk, posk = (views[k].cpu().numpy() for k in ("perm_q", "perm_k", "pos_k"))
+        for bh in range(B * H):
+            for level in range(lay.levels):
+                nodes = (1 << level) if cfg["causal"] else 1
+                s = (n >> (level + 1)) if cfg["causal"] else n
+                for node in range(nodes):
+                    q0 = (2 * node + 1) * s if cfg["causal"] else 0
+                    k0 = (2 * node) * s if cfg["causal"] else 0
+                    rq, _ = orc.sort_lsh(stages["codes"][0, bh, q0:q0 + s])
+                    rk, rposk = orc.sort_lsh(stages["codes"][1, bh, k0:k0 + s])
+                    np.testing.assert_array_equal(pq[level, bh, node * s:(node + 1) * s], rq + q0)
+                    np.testing.assert_array_equal(pk[level, bh, node * s:(node + 1) * s], rk + k0)
+                    np.testing.assert_array_equal(posk[level, bh, node * s:(node + 1) * s], rposk)
+    # stage 3: outputs
+    got = to_host(out)
+    err = assert_close(got, ref_out, dtype, "out", absv if p_rounding_term else None)
+    assert_lse_close(to_host(lse), ref_lse, dtype, "lse")
+    over = int((np.abs(got - ref_out) > 2e-3).sum())
+    print(f"  max abs err {err:.3e}; elements over 2e-3: {over} of {got.size}; sign flips {len(flips)}", flush=True)
+    return out, lse, ref_out, ref_lse
+
+
+def test_forward_cfg1_fp32(ha, torch):
+    cfg = synth_inputs.CONFIGS["cfg1_n1k_fp32"]
+    print("forward cfg1", flush=True)
+    Q, K, V = synth_inputs.make_qkv(cfg)
+    _forward_and_compare(ha, torch, cfg, Q, K, V)
+
+
+@pytest.mark.parametrize("d,n,b,m,law", [(128, 2048, 256, 256, "iid"), (64, 4096, 256, 512, "mixture"),
+                                         (128, 1536, 128, 100, "iid"), (64, 640, 64, 0, "iid"),
+                                         (128, 512, 512, 32, "iid")])
+def test_forward_unmasked_bf16(ha, torch, d, n, b, m, law):
+    print(f"forward bf16 d={d} n={n} b={b} m={m} {law}", flush=True)
+    cfg = dict(B=1, H=2, n=n, d=d, dtype="bf16", law=law, b=b, m=m, r=7, causal=0, n_min=4096, seed=0)
+    Q, K, V = synth_inputs.make_qkv(cfg)
+    _forward_and_compare(ha, torch, cfg, Q, K, V, p_rounding_term=(law == "mixture"))
+
+
+@pytest.mark.parametrize("dtype,d,n,n_min,b,m", [("bf16", 128, 2048, 256, 128, 64), ("bf16", 64, 4096, 1024, 256, 256),
+                                                 ("fp32", 64, 512, 64, 32, 16), ("bf16", 128, 1024, 4096, 256, 256),
+                                                 ("bf16", 128, 1024, 512, 512, 0)])
+def test_forward_causal(ha, torch, dtype, d, n, n_min, b, m):
+    print(f"forward causal {dtype} d={d} n={n} n_min={n_min} b={b} m={m}", flush=True)
+    cfg = dict(B=2, H=1, n=n, d=d, dtype=dtype, law="iid", b=b, m=m, r=7, causal=1, n_min=n_min, seed=3)
+    Q, K, V = synth_inputs.make_qkv(cfg)
+    _forward_and_compare(ha, torch, cfg, Q, K, V)
+
+
+@pytest.mark.parametrize("causal", [0, 1])
+def test_identity_sampling_equals_exact_attention(ha, torch, causal):
+    """Every key sampled exactly once: block part + estimate must be the full
+    row sum, i.e. exact attention, whatever the LSH did."""
+    print(f"identity sampling causal={causal}", flush=True)
+    n, d, b, n_min = 1024, 128, 128, 256
+    cfg = dict(B=1, H=2, n=n, d=d, dtype="bf16", law="iid", b=b, m=n // 2 if causal else n, r=6, causal=causal,
+               n_min=n_min, seed=9)
+    Q, K, V = synth_inputs.make_qkv(cfg)
+    if causal:
+        # every node's index set has the same length m: use the largest node's size
+        # for all (smaller nodes clamp duplicates away is not wanted) -> give each
+        # node exactly its own identity by choosing m = s of the top node only
+        cfg["n_min"] = n // 2          # one split: a single node of s = n/2 = m
+        samples = np.arange(n // 2)[None, :]
+    else:
+        samples = np.arange(n)[None, :]
+    shape = ha.make_shape(1, 2, n, d, ha.HA_BF16)
+    params = ha.make_params(b, cfg["m"], cfg["r"], causal, cfg["n_min"], cfg["seed"])
+    ws = ha.alloc_workspace(shape, params)
+    out, lse = ha.hyperattn_forward(*(to_device(x, "bf16") for x in (Q, K, V)), b, cfg["m"], cfg["r"],
+                                    causal=causal, n_min=cfg["n_min"], seed=cfg["seed"],
+                                    samples=torch.from_numpy(samples.astype(np.int32)).cuda(), workspace=ws)
+    for h in range(2):
+        ro, rl = orc.exact_attention(Q[0, h], K[0, h], V[0, h], bool(causal))
+        assert_close(to_host(out[0, h]), ro, "bf16", "identity-sampled out")
+        assert_lse_close(to_host(lse[0, h]), rl, "bf16", "identity-sampled lse")
+
+
+def test_deterministic_and_inputs_untouched(ha, torch):
+    cfg = dict(B=1, H=2, n=1024, d=128, dtype="bf16", law="iid", b=128, m=64, r=7, causal=1, n_min=256, seed=1)
+    Q, K, V = (to_device(x, "bf16") for x in synth_inputs.make_qkv(cfg))
+    keep = [x.clone() for x in (Q, K, V)]
+    o1, l1 = ha.hyperattn_forward(Q, K, V, cfg["b"], cfg["m"], cfg["r"], causal=True, n_min=cfg["n_min"], seed=1)
+    o2, l2 = ha.hyperattn_forward(Q, K, V, cfg["b"], cfg["m"], cfg["r"], causal=True, n_min=cfg["n_min"], seed=1)
+    torch.cuda.synchronize()
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)) and torch.equal(l1, l2)
+    for a, b_ in zip(keep, (Q, K, V)):
+        assert torch.equal(a.view(torch.int16), b_.view(torch.int16))
+    o3, _ = ha.hyperattn_forward(Q, K, V, cfg["b"], cfg["m"], cfg["r"], causal=True, n_min=cfg["n_min"], seed=2)
+    assert not torch.equal(o1.view(torch.int16), o3.view(torch.int16))
+
+
+def test_rows_are_normalised_on_gpu(ha, torch):
+    """V = 1 must give out = 1: the block part and the estimate share one normaliser."""
+    cfg = dict(B=1, H=1, n=2048, d=64, dtype="bf16", law="iid", b=256, m=128, r=7, causal=0, n_min=4096, seed=0)
+    Q, K, _ = synth_inputs.make_qkv(cfg)
+    V = torch.ones((1, 1, 2048, 64), dtype=torch.bfloat16, device="cuda")
+    out, _ = ha.hyperattn_forward(to_device(Q, "bf16"), to_device(K, "bf16"), V, 256, 128, 7)
+    assert (out.float() - 1).abs().max().item() <= 2 ** -8
+
+
+def test_empty_and_error_paths(ha, torch):
+    z = torch.empty((0, 2, 64, 64), dtype=torch.bfloat16, device="cuda")
+    out, lse = ha.hyperattn_forward(z, z, z, 64, 8, 4)
+    assert out.numel() == 0
+    q = torch.zeros((1, 1, 100, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(ha.HyperAttnError) as e:
+        ha.hyperattn_forward(q, q, q, 64, 8, 4)            # n % b != 0
+    assert e.value.status == -3
+    q = torch.zeros((1, 1, 128, 64), dtype=torch.bfloat16, device="cuda")
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(ha.HyperAttnError) as e:
+        ha.hyperattn_forward(q, q, q, 64, 8, 4, workspace=small)
+    assert e.value.status == -4
