@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the HyperAttention forward pass on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one whole forward call (hash, sort, block + sampled attention of every
+node, causal base case and merge) on one batch of synthetic input that is
+already resident in HBM.  The default workload is the long-context target:
+causal, 32 heads, n = 131072, d = 128, bf16, b = m = 256, r = 7, n_min = 4096.
+Prints ONE JSON line (see the keys below); nothing else goes to stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+import synth_inputs  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def device_inputs(cfg, torch, host_heads=1):
+    """Q, K, V on the device.  Heads [0, host_heads) of batch 0 come from the
+    seeded host generator (so the oracle can be fed the identical rounded
+    arrays); the rest is drawn on the device from the same law."""
+    B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
+    dt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+    g = torch.Generator(device="cuda")
+    g.manual_seed(synth_inputs.DATA_SEED)
+    host = synth_inputs.make_qkv(cfg, B=1, H=host_heads)
+    out = []
+    for i in range(3):
+        if cfg["law"] == "iid":
+            t = torch.randn((B, H, n, d), generator=g, device="cuda", dtype=torch.float32)
+            t.mul_(d ** -0.25)
+            t = t.to(dt)
+        else:
+            full = synth_inputs.make_qkv(cfg)[i]
+            t = torch.from_numpy(full).cuda().to(dt)
+        t[0, :host_heads] = torch.from_numpy(host[i][0]).cuda().to(dt)
+        out.append(t.contiguous())
+    return out, host
+
+
+def algorithmic_work(cfg):
+    """Flops and bytes per forward call, from the stage definitions:
+    4 d (b + m) flop per query row of every node; 4 n_min^2 d / 2 per causal base
+    block; hashing reads every row of Q and K once and writes one byte per row."""
+    B, H, n, d, b, m = cfg["B"], cfg["H"], cfg["n"], cfg["d"], cfg["b"], cfg["m"]
+    BH = B * H
+    esz = 2 if cfg["dtype"] == "bf16" else 4
+    w = {}
+    if cfg["causal"] and n > cfg["n_min"]:
+        levels = int(np.log2(n // cfg["n_min"]))
+        node_rows = levels * (n // 2)
+        base_blocks = n // cfg["n_min"]
+        w["base_flop"] = BH * base_blocks * 4.0 * cfg["n_min"] ** 2 * d / 2
+    elif cfg["causal"]:
+        node_rows, w["base_flop"] = 0, BH * 4.0 * n * n * d / 2
+    else:
+        node_rows, w["base_flop"] = n, 0.0
+    w["node_flop"] = BH * node_rows * 4.0 * d * (b + m)
+    w["hash_bytes"] = 2 * BH * n * (d * esz + 1)
+    w["exact_flop"] = BH * 4.0 * n * n * d * (0.5 if cfg["causal"] else 1.0)
+    return w
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg4_n131k_causal", choices=sorted(synth_inputs.CONFIGS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-exact", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (heads shard with no communication; see DESIGN.md); "
+                 "use --gpus 1")
+
+    import torch
+    import paper_2310_05869_amd as ha
+    ha.lib()  # fails loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+
+    cfg = dict(synth_inputs.CONFIGS[args.workload])
+    B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
+    log(f"[bench] workload {args.workload}: B{B} H{H} n{n} d{d} {cfg['dtype']} b{cfg['b']} m{cfg['m']} r{cfg['r']} "
+        f"causal={cfg['causal']} n_min={cfg['n_min']}")
+    (Q, K, V), host = device_inputs(cfg, torch)
+    shape = ha.make_shape(B, H, n, d, ha.HA_BF16 if cfg["dtype"] == "bf16" else ha.HA_FP32)
+    params = ha.make_params(cfg["b"], cfg["m"], cfg["r"], cfg["causal"], cfg["n_min"], cfg["seed"])
+    ws = ha.alloc_workspace(shape, params)
+    out = torch.empty_like(Q)
+    lse = torch.empty((B, H, n), dtype=torch.float32, device="cuda")
+    kw = dict(causal=cfg["causal"], n_min=cfg["n_min"], seed=cfg["seed"], workspace=ws, out=out, lse=lse)
+
+    def step():
+        ha.hyperattn_forward(Q, K, V, cfg["b"], cfg["m"], cfg["r"], **kw)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    log(f"[bench] {ms_per_step:.3f} ms per forward")
+
+    # per-stage durations from HIP events recorded on the launch stream
+    stage = {k: 0.0 for k in ha.binding.STAGE_NAMES}
+    for _ in range(args.steps):
+        _, _, ms = ha.hyperattn_forward_timed(Q, K, V, cfg["b"], cfg["m"], cfg["r"], **kw)
+        for k, v in ms.items():
+            stage[k] += v / args.steps
+    log("[bench] stage ms: " + ", ".join(f"{k} {v:.3f}" for k, v in stage.items()))
+
+    work = algorithmic_work(cfg)
+    stages_out = {k: round(v, 4) for k, v in stage.items()}
+    tflops = lambda flop, ms: flop / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+    node_tf = tflops(work["node_flop"], stage["node_attn"])
+    base_tf = tflops(work["base_flop"], stage["causal_base"])
+    hash_gbs = work["hash_bytes"] / (stage["lsh_hash"] * 1e-3) / 1e9 if stage["lsh_hash"] > 0 else 0.0
+    # the dominant kernel: the causal base case when there is one, else the node attention
+    if stage["causal_base"] >= stage["node_attn"]:
+        dom, dom_tf, dom_flop, dom_ms = "attn_mfma_kernel<exact> (causal base case)", base_tf, work["base_flop"], stage["causal_base"]
+    else:
+        dom, dom_tf, dom_flop, dom_ms = "attn_mfma_kernel<node> (block + sampled)", node_tf, work["node_flop"], stage["node_attn"]
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(dom_tf, 2), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(dom_tf / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "flop_per_launch": dom_flop, "ms_per_launch": round(dom_ms, 4)}
+
+    result = {
+        "metric": "HyperAttention fwd ms", "value": round(ms_per_step, 4), "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload, "B": B, "H": H, "n": n, "d": d, "b": cfg["b"], "m": cfg["m"],
+                   "r": cfg["r"], "causal": bool(cfg["causal"]), "n_min": cfg["n_min"], "law": cfg["law"]},
+        "roofline": roofline,
+        "stages_ms": stages_out,
+        "stage_rates": {"node_attn_TFLOPs": round(node_tf, 2), "node_attn_frac_mfma": round(node_tf / PEAK_BF16_TFLOPS, 4),
+                        "causal_base_TFLOPs": round(base_tf, 2), "causal_base_frac_mfma": round(base_tf / PEAK_BF16_TFLOPS, 4),
+                        "lsh_hash_GBs": round(hash_gbs, 1), "lsh_hash_frac_hbm": round(hash_gbs / PEAK_HBM_GBS, 4)},
+        "tokens_per_s": round(B * n / (ms_per_step * 1e-3), 1),
+    }
+
+    if not args.no_exact:
+        eo = torch.empty_like(Q)
+        el = torch.empty_like(lse)
+        ha.exact_attn_forward(Q, K, V, causal=cfg["causal"], out=eo, lse=el)
+        torch.cuda.synchronize()
+        reps = 2
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            ha.exact_attn_forward(Q, K, V, causal=cfg["causal"], out=eo, lse=el)
+        torch.cuda.synchronize()
+        exact_ms = (time.perf_counter() - t0) * 1e3 / reps
+        result["exact_attn_ms"] = round(exact_ms, 3)
+        result["exact_attn_TFLOPs"] = round(tflops(work["exact_flop"], exact_ms), 2)
+        result["speedup_vs_exact"] = round(exact_ms / ms_per_step, 3)
+        log(f"[bench] exact attention {exact_ms:.2f} ms -> speedup {exact_ms / ms_per_step:.2f}x")
+        del eo, el
+
+    if not args.no_cpu_baseline:
+        # The oracle (tests' reference, untuned) on the host cores, on head 0 of batch 0
+        # of this very workload; scaled by the head count to the whole job.
+        from oracle import hyperattn_oracle as orc
+        Qh, Kh, Vh = host
+        t0 = time.perf_counter()
+        ro, rl = orc.hyperattn_forward(Qh, Kh, Vh, b=cfg["b"], m=cfg["m"], r=cfg["r"], causal=bool(cfg["causal"]),
+                                       n_min=cfg["n_min"], seed=cfg["seed"])
+        cpu_s = time.perf_counter() - t0
+        got = out[0, 0].float().cpu().numpy().astype(np.float64)
+        err = float(np.abs(got - ro[0, 0]).max())
+        cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
+        try:
+            from threadpoolctl import threadpool_info
+            nt = [p["num_threads"] for p in threadpool_info() if p.get("user_api") == "blas"]
+            threads = max(nt) if nt else cores
+        except Exception:
+            threads = cores
+        result["cpu_baseline"] = {"value": round(cpu_s * 1e3 * B * H, 1), "unit": "ms", "cores": int(threads),
+                                  "kind": "oracle",
+                                  "sample": f"head 0 of batch 0 of the same workload ({cpu_s:.1f} s measured), "
+                                            f"multiplied by B*H = {B * H} heads"}
+        result["parity_sample_max_abs_err"] = err
+        log(f"[bench] oracle {cpu_s:.1f} s for one head on {threads} threads; GPU-vs-oracle max abs err on it {err:.2e}")
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

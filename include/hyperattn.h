@@ -119,6 +119,19 @@ int hyperattn_forward_ex(const void* Q, const void* K, const void* V, void* out,
                          const float* R_dev, const int32_t* samples_dev,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/* Measurement variant of hyperattn_forward (same computation, same launches):
+ * HIP events are recorded on `stream` between the stages, the call WAITS for the
+ * last one, and stage_ms_host[0..5] (host memory) receive the elapsed
+ * milliseconds of: [0] random draws into the workspace, [1] sortLSH hashing of Q
+ * and K, [2] the sort (Algorithm 1's permutations), [3] block + sampled
+ * attention of all nodes, [4] the exact causal base case with the Algorithm 4
+ * merge (0 when not causal), [5] the whole call.  Unlike every other entry
+ * point this one synchronises with the stream. */
+int hyperattn_forward_timed(const void* Q, const void* K, const void* V, void* out, float* lse,
+                            const ha_shape* shape, const ha_params* params,
+                            void* workspace, size_t workspace_bytes, void* stream,
+                            float* stage_ms_host);
+
 /* Plain exact attention D^-1 A V (Section 1.1), or D_C^-1 (M^C . A) V with
  * M^C_ij = 1{i >= j} (Section 3.1) when causal != 0; the denominator of the
  * speed-up ratio.  Any n >= 1; d in {64,128}.  Needs no workspace. */

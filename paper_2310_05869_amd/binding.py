@@ -47,6 +47,8 @@ _SIGNATURES = {
     "hyperattn_forward": (c_int, [c_void_p] * 5 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_size_t, c_void_p]),
     "hyperattn_forward_ex": (c_int, [c_void_p] * 5 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_void_p,
                                                      c_void_p, c_size_t, c_void_p]),
+    "hyperattn_forward_timed": (c_int, [c_void_p] * 5 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_size_t,
+                                                        c_void_p, POINTER(c_float)]),
     "exact_attn_forward": (c_int, [c_void_p] * 5 + [POINTER(HaShape), c_int, c_void_p]),
     "ha_make_projection": (c_int, [c_uint64, c_int32, c_int32, POINTER(c_float)]),
     "ha_make_samples": (c_int, [c_uint64, c_int32, c_int32, c_int32, c_int32, POINTER(c_int32)]),
@@ -186,6 +188,31 @@ def hyperattn_forward(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0, R=None
                                         workspace.data_ptr(), workspace.numel(), _stream(stream))
     _check(st, "hyperattn_forward")
     return out, lse
+
+
+STAGE_NAMES = ("prep", "lsh_hash", "seg_sort", "node_attn", "causal_base", "total")
+
+
+def hyperattn_forward_timed(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0, workspace=None, out=None,
+                            lse=None, stream=None):
+    """As hyperattn_forward, but waits for the result and also returns the
+    per-stage milliseconds (dict keyed by STAGE_NAMES) from HIP events."""
+    torch = _torch()
+    B, H, n, d = Q.shape
+    shape = make_shape(B, H, n, d, _dtype_code(Q))
+    params = make_params(b, m, r, causal, n_min, seed)
+    if workspace is None:
+        workspace = alloc_workspace(shape, params, Q.device)
+    if out is None:
+        out = torch.empty_like(Q)
+    if lse is None:
+        lse = torch.empty((B, H, n), dtype=torch.float32, device=Q.device)
+    ms = (c_float * 6)()
+    st = lib().hyperattn_forward_timed(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"), _dev(lse, "lse"),
+                                       ctypes.byref(shape), ctypes.byref(params), workspace.data_ptr(),
+                                       workspace.numel(), _stream(stream), ms)
+    _check(st, "hyperattn_forward_timed")
+    return out, lse, dict(zip(STAGE_NAMES, [float(x) for x in ms]))
 
 
 def exact_attn_forward(Q, K, V, causal=False, out=None, lse=None, stream=None):

@@ -119,9 +119,11 @@ static int run_attention(const AttnArgs& a, int mode, hipStream_t st) {
   return use_mfma(a.g) ? launch_attn_mfma(a, mode, st) : launch_attn_generic(a, mode, st);
 }
 
+// ev, when non-null, receives 6 events recorded on the stream: start, after
+// prep, after hashing, after sorting, after the node attention, after the base case.
 static int forward_impl(const void* Q, const void* K, const void* V, void* out, float* lse, const ha_shape* sh,
                         const ha_params* p, const float* R_dev, const int32_t* samples_dev, void* ws,
-                        size_t ws_bytes, void* stream) {
+                        size_t ws_bytes, void* stream, hipEvent_t* ev = nullptr) {
   Geometry g;
   int rc = make_geometry(sh, p, &g);
   if (rc != HA_OK) return rc;
@@ -143,7 +145,11 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
   float* part_o = (float*)(base + lay.part_o);
   float* part_l = (float*)(base + lay.part_l);
   const int64_t head_stride = (int64_t)g.n * g.d;
+  auto mark = [&](int i) {
+    if (ev) (void)hipEventRecord(ev[i], st);
+  };
 
+  mark(0);
   if (g.levels > 0) {
     uint16_t Rb[1024];
     if (!R_dev)
@@ -151,12 +157,15 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
         for (int k = 0; k < g.r; ++k) Rb[c * g.r + k] = projection_bits(p->seed, c, k);
     rc = launch_prep(proj, R_dev, R_dev ? nullptr : Rb, samples, samples_dev, g, p->seed, st);
     if (rc != HA_OK) return rc;
+    mark(1);
     rc = launch_lsh_hash(Q, codes_q, (int64_t)g.BH * g.n, g.d, g.dtype, proj, g.r, st);
     if (rc != HA_OK) return rc;
     rc = launch_lsh_hash(K, codes_k, (int64_t)g.BH * g.n, g.d, g.dtype, proj, g.r, st);
     if (rc != HA_OK) return rc;
+    mark(2);
     rc = launch_seg_sort_nodes(codes_q, codes_k, perm_q, perm_k, pos_k, g, st);
     if (rc != HA_OK) return rc;
+    mark(3);
 
     AttnArgs a{};
     a.Q = Q;
@@ -180,7 +189,12 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
     }
     rc = run_attention(a, kModeNode, st);
     if (rc != HA_OK) return rc;
+  } else {
+    mark(1);
+    mark(2);
+    mark(3);
   }
+  mark(4);
   if (g.causal) {
     AttnArgs a{};
     a.Q = Q;
@@ -200,6 +214,7 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
     rc = run_attention(a, kModeExact, st);
     if (rc != HA_OK) return rc;
   }
+  mark(5);
   return HA_OK;
 }
 
@@ -251,6 +266,30 @@ int hyperattn_forward_ex(const void* Q, const void* K, const void* V, void* out,
                          const ha_shape* shape, const ha_params* params, const float* R_dev,
                          const int32_t* samples_dev, void* workspace, size_t workspace_bytes, void* stream) {
   return forward_impl(Q, K, V, out, lse, shape, params, R_dev, samples_dev, workspace, workspace_bytes, stream);
+}
+
+int hyperattn_forward_timed(const void* Q, const void* K, const void* V, void* out, float* lse,
+                            const ha_shape* shape, const ha_params* params, void* workspace,
+                            size_t workspace_bytes, void* stream, float* stage_ms_host) {
+  if (!stage_ms_host) return HA_ERR_NULL;
+  hipEvent_t ev[6];
+  for (int i = 0; i < 6; ++i)
+    if (hipEventCreate(&ev[i]) != hipSuccess) {
+      for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
+      return HA_ERR_LAUNCH;
+    }
+  int rc = forward_impl(Q, K, V, out, lse, shape, params, nullptr, nullptr, workspace, workspace_bytes, stream, ev);
+  for (int i = 0; i < 6; ++i) stage_ms_host[i] = 0.f;
+  Geometry g;
+  const bool ran = rc == HA_OK && make_geometry(shape, params, &g) == HA_OK && g.BH > 0 && g.n > 0;
+  if (ran) {
+    if (hipEventSynchronize(ev[5]) != hipSuccess) rc = HA_ERR_LAUNCH;
+    for (int i = 0; i < 5 && rc == HA_OK; ++i)
+      if (hipEventElapsedTime(&stage_ms_host[i], ev[i], ev[i + 1]) != hipSuccess) rc = HA_ERR_LAUNCH;
+    if (rc == HA_OK && hipEventElapsedTime(&stage_ms_host[5], ev[0], ev[5]) != hipSuccess) rc = HA_ERR_LAUNCH;
+  }
+  for (int i = 0; i < 6; ++i) (void)hipEventDestroy(ev[i]);
+  return rc;
 }
 
 int exact_attn_forward(const void* Q, const void* K, const void* V, void* out, float* lse, const ha_shape* sh,
