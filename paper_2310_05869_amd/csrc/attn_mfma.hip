@@ -33,6 +33,9 @@ namespace ha {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kQT = 128;      // queries per workgroup
 constexpr int kNT = 256;      // threads
@@ -40,10 +43,10 @@ constexpr int kKT = 64;       // keys per step
 
 template <int D>
 struct Lds {
-  static constexpr int KSTR = (D + 8) * 2;        // bytes per K row (padded: conflict-free 16-byte reads)
-  static constexpr int VSTR = (kKT + 8) * 2;      // bytes per V^T row
+  static constexpr int KSTR = (D + 8) * 2;        // bytes per K row (+16: conflict-free 16-byte row reads)
+  static constexpr int VSTR = (D + 32) * 2;       // bytes per V row (+64: conflict-free transposing reads)
   static constexpr int K_BYTES = kKT * KSTR;
-  static constexpr int V_BYTES = D * VSTR;
+  static constexpr int V_BYTES = kKT * VSTR;
   static constexpr int BUF = K_BYTES + V_BYTES;
 };
 
@@ -59,10 +62,7 @@ __host__ __device__ inline size_t mfma_lds_bytes(int b, int m, int mode) {
 template <int D>
 struct TileRegs {
   static constexpr int CPR = D / 8;              // 16-byte chunks per K row
-  static constexpr int NKC = kKT * CPR / kNT;    // K chunks per thread
-  static constexpr int NVB = (kKT / 4) * (D / 4) / kNT;  // 4x4 V blocks per thread
-  uint4 k[NKC];
-  uint2 v[NVB][4];
+  static constexpr int NKC = kKT * CPR / kNT;    // K (and V) chunks per thread
 };
 
 template <int D, int MODE>
@@ -119,12 +119,9 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
   }
   bf16x8 qreg[KS];
   {
-    const uint4* qp = reinterpret_cast<const uint4*>(Qh + (int64_t)qrow_load * D + 8 * h);
+    const u32x4* qp = reinterpret_cast<const u32x4*>(Qh + (int64_t)qrow_load * D + 8 * h);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const uint4 raw = qp[2 * ks];
-      qreg[ks] = *reinterpret_cast<const bf16x8*>(&raw);
-    }
+    for (int ks = 0; ks < KS; ++ks) qreg[ks] = __builtin_bit_cast(bf16x8, qp[2 * ks]);
   }
 
   // ---- tile movers ----
@@ -133,51 +130,30 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
     const int r = w.k0 + kt * kKT + j;
     return r < w.k1 ? r : w.k1 - 1;
   };
-  auto load_tile = [&](int kt, TR& t) {
+  u32x4 kreg[TR::NKC], vreg[TR::NKC];
+  auto load_tile = [&](int kt) {
 #pragma unroll
     for (int i = 0; i < TR::NKC; ++i) {
       const int c = tid + i * kNT;
       const int key = c / TR::CPR, col = c % TR::CPR;
-      t.k[i] = *reinterpret_cast<const uint4*>(Kh + (int64_t)key_row(kt, key) * D + col * 8);
-    }
-#pragma unroll
-    for (int i = 0; i < TR::NVB; ++i) {
-      const int bidx = tid + i * kNT;
-      const int dg = bidx % (D / 4), kg = bidx / (D / 4);
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
-        t.v[i][kk] = *reinterpret_cast<const uint2*>(Vh + (int64_t)key_row(kt, 4 * kg + kk) * D + 4 * dg);
+      const int64_t off = (int64_t)key_row(kt, key) * D + col * 8;
+      kreg[i] = *reinterpret_cast<const u32x4*>(Kh + off);
+      vreg[i] = *reinterpret_cast<const u32x4*>(Vh + off);
     }
   };
-  auto store_tile = [&](unsigned char* buf, const TR& t) {
+  auto store_tile = [&](unsigned char* buf) {
 #pragma unroll
     for (int i = 0; i < TR::NKC; ++i) {
       const int c = tid + i * kNT;
       const int key = c / TR::CPR, col = c % TR::CPR;
-      *reinterpret_cast<uint4*>(buf + key * L::KSTR + col * 16) = t.k[i];
-    }
-#pragma unroll
-    for (int i = 0; i < TR::NVB; ++i) {
-      const int bidx = tid + i * kNT;
-      const int dg = bidx % (D / 4), kg = bidx / (D / 4);
-      // keys are stored with bits 2 and 3 of their index swapped: the order in
-      // which a lane's accumulator registers hold the keys of a 16-key step
-      const int kgs = (kg & ~3) | ((kg & 1) << 1) | ((kg >> 1) & 1);
-      const uint2 a0 = t.v[i][0], a1 = t.v[i][1], a2 = t.v[i][2], a3 = t.v[i][3];
-      uint2 o[4];
-      o[0].x = (a0.x & 0xFFFFu) | (a1.x << 16);
-      o[0].y = (a2.x & 0xFFFFu) | (a3.x << 16);
-      o[1].x = (a0.x >> 16) | (a1.x & 0xFFFF0000u);
-      o[1].y = (a2.x >> 16) | (a3.x & 0xFFFF0000u);
-      o[2].x = (a0.y & 0xFFFFu) | (a1.y << 16);
-      o[2].y = (a2.y & 0xFFFFu) | (a3.y << 16);
-      o[3].x = (a0.y >> 16) | (a1.y & 0xFFFF0000u);
-      o[3].y = (a2.y >> 16) | (a3.y & 0xFFFF0000u);
-      unsigned char* vb = buf + L::K_BYTES + (4 * dg) * L::VSTR + (4 * kgs) * 2;
-#pragma unroll
-      for (int dd = 0; dd < 4; ++dd) *reinterpret_cast<uint2*>(vb + dd * L::VSTR) = o[dd];
+      *reinterpret_cast<u32x4*>(buf + key * L::KSTR + col * 16) = kreg[i];
+      *reinterpret_cast<u32x4*>(buf + L::K_BYTES + key * L::VSTR + col * 16) = vreg[i];
     }
   };
+  // V^T fragments come from the row-major V tile through the transposing LDS
+  // read: the 16 lanes of a group fetch a 4-key x 16-d patch (lane i: key i/4,
+  // d 4*(i%4)..+3) and lane n receives the 4 keys of column n.
+  const int vtr_off = ((lane & 15) >> 2) * L::VSTR + ((lane & 3) * 4 + ((lane >> 4) & 1) * 16) * 2 + (4 * h) * L::VSTR;
 
   // ---- state ----
   f32x16 o[DT];
@@ -188,10 +164,9 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
   float m_run = -INFINITY;  // running max, log2 domain
   float l_run = 0.f;        // this lane's share of the row sum
 
-  TR regs;
   if (ntiles > 0) {
-    load_tile(0, regs);
-    store_tile(bufs, regs);
+    load_tile(0);
+    store_tile(bufs);
   }
   __syncthreads();
 
@@ -199,54 +174,65 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
 
   for (int kt = 0; kt < ntiles; ++kt) {
     unsigned char* buf = bufs + (kt & 1) * L::BUF;
-    if (kt + 1 < ntiles) load_tile(kt + 1, regs);
+    if (kt + 1 < ntiles) load_tile(kt + 1);
 
     const int key_base = kt * kKT;  // position in the key list / offset from k0
     const bool skip = (MODE == kModeExact) && a.exact_causal && (w.k0 + key_base > wave_q_last);
     if (!skip) {
-      // ---- S^T tile: 64 keys x 32 queries ----
+      // ---- S^T tile: 64 keys x 32 queries; the two 32-key halves are
+      // independent accumulators, interleaved so no MFMA waits on the previous one ----
       f32x16 c[2];
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub) {
+      for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int i = 0; i < 16; ++i) c[sub][i] = 0.f;
-        const unsigned char* kp = buf + (32 * sub + lq) * L::KSTR + 16 * h;
+      {
+        const unsigned char* kp0 = buf + lq * L::KSTR + 16 * h;
+        const unsigned char* kp1 = kp0 + 32 * L::KSTR;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kp + 32 * ks);
-          c[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qreg[ks], c[sub], 0, 0, 0);
+        for (int kh = 0; kh < KS; kh += 4) {
+          bf16x8 kf0[4], kf1[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            kf0[j] = *reinterpret_cast<const bf16x8*>(kp0 + 32 * (kh + j));
+            kf1[j] = *reinterpret_cast<const bf16x8*>(kp1 + 32 * (kh + j));
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            c[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0[j], qreg[kh + j], c[0], 0, 0, 0);
+            c[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1[j], qreg[kh + j], c[1], 0, 0, 0);
+          }
         }
       }
-      // ---- scores to the log2 domain, bias and masks ----
+      // ---- masks (rare tiles only): tail of the key list, causal diagonal, and a
+      // tile that straddles the block / sampled boundary ----
       const bool tail = key_base + kKT > nkeys;
       const bool mixed = (key_base < nb) && (key_base + kKT > nb);
       const bool diag = (MODE == kModeExact) && a.exact_causal && (w.k0 + key_base + kKT - 1 > w.q0 + wave * 32);
-      if (!(tail || mixed || diag)) {
-        const float bias = (key_base >= nb) ? bias2 : 0.f;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) c[sub][i] = __builtin_fmaf(c[sub][i], kLog2e, bias);
-      } else {
+      float bias = (key_base >= nb) ? bias2 : 0.f;  // log2 domain, uniform over the tile
+      if (tail || mixed || diag) {
+        int lim = nkeys;
+        if (MODE == kModeExact && a.exact_causal) lim = min(lim, q_global - w.k0 + 1);
+        const int lim2 = lim - key_base - 4 * h;           // element i is masked iff koff_i >= lim2
+        const int nb2 = mixed ? nb - key_base - 4 * h : 0x7fffffff;
+        const float nat_bias = bias2 * kLn2;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
-            const int kpos = key_base + 32 * sub + 8 * (i / 4) + 4 * h + (i % 4);
-            float v = __builtin_fmaf(c[sub][i], kLog2e, kpos >= nb ? bias2 : 0.f);
-            bool masked = kpos >= nkeys;
-            if (MODE == kModeExact && a.exact_causal) masked = masked || (w.k0 + kpos > q_global);
-            c[sub][i] = masked ? -INFINITY : v;
+            const int koff = 32 * sub + 8 * (i / 4) + (i % 4);
+            float v = c[sub][i];
+            if (koff >= nb2) v += nat_bias;
+            c[sub][i] = (koff >= lim2) ? -INFINITY : v;
           }
+        if (mixed) bias = 0.f;
       }
-      // ---- online softmax ----
-      float mx = c[0][0];
+      // ---- online softmax (exp2 domain) ----
+      float mx = fmaxf(c[0][0], c[1][0]);
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, c[sub][i]);
+      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(c[0][i], c[1][i]));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, mx);
+      const float m_new = fmaxf(m_run, __builtin_fmaf(mx, kLog2e, bias));
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
       if (__any(m_new > m_run)) {
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
@@ -257,33 +243,43 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
         l_run *= alpha;
       }
       m_run = m_new;
+      const float shift = bias - m_use;
       bf16x8 pf[4];
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
-          uint32_t pk[4];
+          u32x4 pk;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float p0 = __builtin_amdgcn_exp2f(c[sub][8 * jj + 2 * e] - m_use);
-            const float p1 = __builtin_amdgcn_exp2f(c[sub][8 * jj + 2 * e + 1] - m_use);
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(c[sub][8 * jj + 2 * e], kLog2e, shift));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(c[sub][8 * jj + 2 * e + 1], kLog2e, shift));
             l_run += p0 + p1;
             pk[e] = pack_bf16x2(p0, p1);
           }
-          pf[2 * sub + jj] = *reinterpret_cast<const bf16x8*>(pk);
+          pf[2 * sub + jj] = __builtin_bit_cast(bf16x8, pk);
         }
       // ---- O^T += V^T P^T ----
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        const unsigned char* vp = buf + L::K_BYTES + (32 * dt + lq) * L::VSTR + 16 * h;
+      // slot e of a lane's P registers holds key 8*(e/4) + 4*h + e%4 of the 16-key step
+      {
+        typedef short s16x4 __attribute__((ext_vector_type(4)));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+        const unsigned char* vb = buf + L::K_BYTES + vtr_off;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vp + 32 * j);
-          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[j], o[dt], 0, 0, 0);
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) {
+            const unsigned char* vp = vb + (16 * j) * L::VSTR + (32 * dt) * 2;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * L::VSTR));
+            const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[j], o[dt], 0, 0, 0);
+          }
         }
       }
     }
-    if (kt + 1 < ntiles) store_tile(bufs + ((kt + 1) & 1) * L::BUF, regs);
+    if (kt + 1 < ntiles) store_tile(bufs + ((kt + 1) & 1) * L::BUF);
     __syncthreads();
   }
 
@@ -305,8 +301,8 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
-        const float4 v = make_float4(o[dt][4 * g4], o[dt][4 * g4 + 1], o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]);
-        *reinterpret_cast<float4*>(po + 32 * dt + 8 * g4 + 4 * h) = v;
+        const f32x4 v = {o[dt][4 * g4], o[dt][4 * g4 + 1], o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]};
+        *reinterpret_cast<f32x4*>(po + 32 * dt + 8 * g4 + 4 * h) = v;
       }
     if (h == 0) a.part_l[dest.part_row] = lse_own;
     return;
@@ -331,7 +327,7 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
-          const float4 v = *reinterpret_cast<const float4*>(po + 32 * dt + 8 * g4 + 4 * h);
+          const f32x4 v = *reinterpret_cast<const f32x4*>(po + 32 * dt + 8 * g4 + 4 * h);
           o[dt][4 * g4] += wl * v.x;
           o[dt][4 * g4 + 1] += wl * v.y;
           o[dt][4 * g4 + 2] += wl * v.z;
@@ -347,10 +343,10 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
-        uint2 v;
+        u32x2 v;
         v.x = pack_bf16x2(o[dt][4 * g4], o[dt][4 * g4 + 1]);
         v.y = pack_bf16x2(o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]);
-        *reinterpret_cast<uint2*>(op + 32 * dt + 8 * g4 + 4 * h) = v;
+        *reinterpret_cast<u32x2*>(op + 32 * dt + 8 * g4 + 4 * h) = v;
       }
   }
   if (a.lse != nullptr && h == 0) a.lse[dest.out_row] = lse_own;
