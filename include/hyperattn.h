@@ -57,7 +57,7 @@ typedef enum {
   HA_ERR_LAUNCH = -5     /* the HIP runtime refused a launch (hipGetLastError) */
 } ha_status;
 
-/* [B, H, n, d]; d must be 64 or 128. */
+/* [B, H, n, d]; d must be 64 or 128; n <= 2^22; B*H <= 2^20. */
 typedef struct {
   int32_t B, H, n, d;
   int32_t dtype; /* ha_dtype */

@@ -29,7 +29,7 @@ static int make_geometry(const ha_shape* sh, const ha_params* p, Geometry* g) {
   if (sh->d != 64 && sh->d != 128) return HA_ERR_SHAPE;
   if (p->r < 1 || p->r > 8) return HA_ERR_SHAPE;
   if (p->b < 1 || p->b > 4096 || p->m < 0 || p->m > 4096) return HA_ERR_SHAPE;
-  if ((int64_t)sh->B * sh->H > (1 << 20) || sh->n > (1 << 24)) return HA_ERR_SHAPE;
+  if ((int64_t)sh->B * sh->H > (1 << 20) || sh->n > (1 << 22)) return HA_ERR_SHAPE;
   g->BH = sh->B * sh->H;
   g->n = sh->n;
   g->d = sh->d;
@@ -297,7 +297,7 @@ int exact_attn_forward(const void* Q, const void* K, const void* V, void* out, f
   if (!sh) return HA_ERR_NULL;
   if (sh->dtype != HA_BF16 && sh->dtype != HA_FP32) return HA_ERR_DTYPE;
   if (sh->B < 0 || sh->H < 0 || sh->n < 0 || (sh->d != 64 && sh->d != 128)) return HA_ERR_SHAPE;
-  if ((int64_t)sh->B * sh->H > (1 << 20) || sh->n > (1 << 24)) return HA_ERR_SHAPE;
+  if ((int64_t)sh->B * sh->H > (1 << 20) || sh->n > (1 << 22)) return HA_ERR_SHAPE;
   if (sh->B == 0 || sh->H == 0 || sh->n == 0) return HA_OK;
   if (!Q || !K || !V || !out || !lse) return HA_ERR_NULL;
   AttnArgs a{};

@@ -27,6 +27,8 @@
 //     are issued before the current tile's MFMAs.
 //   * softmax runs in the exp2 domain in fp32; P is rounded to bf16 only as the
 //     MFMA operand, the row sum uses the unrounded fp32 values.
+#include <type_traits>
+
 #include "attn_common.h"
 
 namespace ha {
@@ -58,6 +60,8 @@ __host__ __device__ inline size_t mfma_lds_bytes(int b, int m, int mode) {
   if (mode == kModeNode) s += (size_t)list_capacity(b, m) * 4;
   return s;
 }
+
+__device__ inline float max3f(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 
 template <int D>
 struct TileRegs {
@@ -125,31 +129,40 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
   }
 
   // ---- tile movers ----
-  auto key_row = [&](int kt, int j) -> int {
-    if (MODE == kModeNode) return list[kt * kKT + j];
-    const int r = w.k0 + kt * kKT + j;
-    return r < w.k1 ? r : w.k1 - 1;
-  };
+  // K and V rows are fetched with buffer loads: a 32-bit per-lane byte offset
+  // (row * row_bytes + column, from the key list in node mode, fixed in exact
+  // mode) plus a scalar offset that advances with the tile.  Offsets past the
+  // end of the head's tensor return zeros (such keys are masked by position).
+  const uint32_t head_bytes = (uint32_t)((MODE == kModeNode ? a.g.n : a.exact_rows_k) * (D * 2));
+  const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc((void*)Kh, 0, (int)head_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t vrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)Vh, 0, (int)head_bytes, 0x00020000);
   u32x4 kreg[TR::NKC], vreg[TR::NKC];
-  auto load_tile = [&](int kt) {
+  auto load_rows = [&](int kt, const __amdgpu_buffer_rsrc_t& rsrc, u32x4 (&reg)[TR::NKC]) {
 #pragma unroll
     for (int i = 0; i < TR::NKC; ++i) {
       const int c = tid + i * kNT;
       const int key = c / TR::CPR, col = c % TR::CPR;
-      const int64_t off = (int64_t)key_row(kt, key) * D + col * 8;
-      kreg[i] = *reinterpret_cast<const u32x4*>(Kh + off);
-      vreg[i] = *reinterpret_cast<const u32x4*>(Vh + off);
+      int voff, soff;
+      if (MODE == kModeNode) {
+        voff = list[kt * kKT + key] * (D * 2) + col * 16;
+        soff = 0;
+      } else {
+        voff = key * (D * 2) + col * 16;
+        soff = (w.k0 + kt * kKT) * (D * 2);
+      }
+      reg[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 0);
     }
   };
-  auto store_tile = [&](unsigned char* buf) {
+  auto store_rows = [&](unsigned char* dst, int stride, const u32x4 (&reg)[TR::NKC]) {
 #pragma unroll
     for (int i = 0; i < TR::NKC; ++i) {
       const int c = tid + i * kNT;
       const int key = c / TR::CPR, col = c % TR::CPR;
-      *reinterpret_cast<u32x4*>(buf + key * L::KSTR + col * 16) = kreg[i];
-      *reinterpret_cast<u32x4*>(buf + L::K_BYTES + key * L::VSTR + col * 16) = vreg[i];
+      *reinterpret_cast<u32x4*>(dst + key * stride + col * 16) = reg[i];
     }
   };
+  auto kbuf_at = [&](int t) -> unsigned char* { return bufs + (t & 1) * L::BUF; };
+  auto vbuf_at = [&](int t) -> unsigned char* { return bufs + (t & 1) * L::BUF + L::K_BYTES; };
   // V^T fragments come from the row-major V tile through the transposing LDS
   // read: the 16 lanes of a group fetch a 4-key x 16-d patch (lane i: key i/4,
   // d 4*(i%4)..+3) and lane n receives the 4 keys of column n.
@@ -161,90 +174,127 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
-  float m_run = -INFINITY;  // running max, log2 domain
-  float l_run = 0.f;        // this lane's share of the row sum
+  // m_run is a reference for the exponentials, not necessarily the running
+  // maximum: it is only moved (and the accumulators rescaled) when a row's tile
+  // maximum exceeds it by more than 2^8, so after the first tiles the rescale is
+  // skipped.  Log2 domain.
+  float m_run = -INFINITY;
+  float l_run = 0.f;  // this lane's share of the row sum
 
-  if (ntiles > 0) {
-    load_tile(0);
-    store_tile(bufs);
-  }
-  __syncthreads();
-
-  const int wave_q_last = w.q0 + wave * 32 + 31;  // exact mode
-
-  for (int kt = 0; kt < ntiles; ++kt) {
-    unsigned char* buf = bufs + (kt & 1) * L::BUF;
-    if (kt + 1 < ntiles) load_tile(kt + 1);
-
-    const int key_base = kt * kKT;  // position in the key list / offset from k0
-    const bool skip = (MODE == kModeExact) && a.exact_causal && (w.k0 + key_base > wave_q_last);
-    if (!skip) {
-      // ---- S^T tile: 64 keys x 32 queries; the two 32-key halves are
-      // independent accumulators, interleaved so no MFMA waits on the previous one ----
-      f32x16 c[2];
+  // Masks of a score tile (rare tiles only): tail of the key list, causal
+  // diagonal, and a tile that straddles the block / sampled boundary.  `bias` is
+  // the tile-uniform log2-domain bias (log2(s/m) on sampled tiles).
+  auto mask_tile = [&](f32x16 (&c)[2], int t, float& bias) {
+    const int key_base = t * kKT;
+    const bool tail = key_base + kKT > nkeys;
+    const bool mixed = (key_base < nb) && (key_base + kKT > nb);
+    const bool diag = (MODE == kModeExact) && a.exact_causal && (w.k0 + key_base + kKT - 1 > w.q0 + wave * 32);
+    bias = (key_base >= nb) ? bias2 : 0.f;
+    if (tail || mixed || diag) {
+      int lim = nkeys;
+      if (MODE == kModeExact && a.exact_causal) lim = min(lim, q_global - w.k0 + 1);
+      const int lim2 = lim - key_base - 4 * h;  // element i is masked iff koff_i >= lim2
+      const int nb2 = mixed ? nb - key_base - 4 * h : 0x7fffffff;
+      const float nat_bias = bias2 * kLn2;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) c[sub][i] = 0.f;
-      {
-        const unsigned char* kp0 = buf + lq * L::KSTR + 16 * h;
-        const unsigned char* kp1 = kp0 + 32 * L::KSTR;
-#pragma unroll
-        for (int kh = 0; kh < KS; kh += 4) {
-          bf16x8 kf0[4], kf1[4];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            kf0[j] = *reinterpret_cast<const bf16x8*>(kp0 + 32 * (kh + j));
-            kf1[j] = *reinterpret_cast<const bf16x8*>(kp1 + 32 * (kh + j));
-          }
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            c[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0[j], qreg[kh + j], c[0], 0, 0, 0);
-            c[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1[j], qreg[kh + j], c[1], 0, 0, 0);
-          }
+        for (int i = 0; i < 16; ++i) {
+          const int koff = 32 * sub + 8 * (i / 4) + (i % 4);
+          float v = c[sub][i];
+          if (koff >= nb2) v += nat_bias;
+          c[sub][i] = (koff >= lim2) ? -INFINITY : v;
         }
-      }
-      // ---- masks (rare tiles only): tail of the key list, causal diagonal, and a
-      // tile that straddles the block / sampled boundary ----
-      const bool tail = key_base + kKT > nkeys;
-      const bool mixed = (key_base < nb) && (key_base + kKT > nb);
-      const bool diag = (MODE == kModeExact) && a.exact_causal && (w.k0 + key_base + kKT - 1 > w.q0 + wave * 32);
-      float bias = (key_base >= nb) ? bias2 : 0.f;  // log2 domain, uniform over the tile
-      if (tail || mixed || diag) {
-        int lim = nkeys;
-        if (MODE == kModeExact && a.exact_causal) lim = min(lim, q_global - w.k0 + 1);
-        const int lim2 = lim - key_base - 4 * h;           // element i is masked iff koff_i >= lim2
-        const int nb2 = mixed ? nb - key_base - 4 * h : 0x7fffffff;
-        const float nat_bias = bias2 * kLn2;
+      if (mixed) bias = 0.f;
+    }
+  };
+  // row maximum of a score tile in the log2 domain (in-lane, then lane ^ 32)
+  auto tile_max = [&](const f32x16 (&c)[2], float bias) -> float {
+    float mx = max3f(c[0][0], c[1][0], c[0][1]);
+#pragma unroll
+    for (int i = 1; i < 16; ++i) {
+      if (i + 1 < 16) mx = max3f(mx, c[1][i], c[0][i + 1]);
+      else mx = fmaxf(mx, c[1][i]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    return __builtin_fmaf(mx, kLog2e, bias);
+  };
+
+  // Software pipeline over key tiles: while the matrix cores compute the scores
+  // of tile kt+1, the vector ALU turns the scores of tile kt into bf16 weights;
+  // while they accumulate P V of tile kt, the vector ALU reduces the row maximum
+  // of tile kt+1.  K tile t and V tile t live in buffer (t & 1) of their kind;
+  // K runs one tile ahead of V.
+  f32x16 c[2];
+  float bias = 0.f, t_max = -INFINITY;
+  if (ntiles > 0) {
+    load_rows(0, krsrc, kreg);
+    load_rows(0, vrsrc, vreg);
+    store_rows(kbuf_at(0), L::KSTR, kreg);
+    store_rows(vbuf_at(0), L::VSTR, vreg);
+    if (ntiles > 1) {
+      load_rows(1, krsrc, kreg);
+      store_rows(kbuf_at(1), L::KSTR, kreg);
+    }
+  }
+  __syncthreads();
+  if (ntiles > 0) {
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) c[sub][i] = 0.f;
+    const unsigned char* kp0 = kbuf_at(0) + lq * L::KSTR + 16 * h;
+    const unsigned char* kp1 = kp0 + 32 * L::KSTR;
+#pragma unroll
+    for (int j = 0; j < KS; ++j) {
+      c[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(kp0 + 32 * j), qreg[j], c[0], 0, 0, 0);
+      c[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(kp1 + 32 * j), qreg[j], c[1], 0, 0, 0);
+    }
+    mask_tile(c, 0, bias);
+    t_max = tile_max(c, bias);
+  }
+
+  auto body = [&](int kt, f32x16 (&c)[2], float& bias, f32x16 (&cn)[2], float& bias_n, auto has_next) {
+    constexpr bool HN = decltype(has_next)::value;
+    const bool more_k = kt + 2 < ntiles;
+    if (more_k) load_rows(kt + 2, krsrc, kreg);
+    if (HN) load_rows(kt + 1, vrsrc, vreg);
+
+    if (__any(t_max > m_run + 8.0f)) {
+      const float m_new = fmaxf(m_run, t_max);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[dt][i] *= alpha;
+      l_run *= alpha;
+      m_run = m_new;
+    }
+    const float shift = bias - ((m_run == -INFINITY) ? 0.f : m_run);
+
+    // ---- scores of tile kt+1 (matrix cores)  ||  weights of tile kt (vector ALU) ----
+    bf16x8 pf[4];
+    {
+      if (HN) {
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int koff = 32 * sub + 8 * (i / 4) + (i % 4);
-            float v = c[sub][i];
-            if (koff >= nb2) v += nat_bias;
-            c[sub][i] = (koff >= lim2) ? -INFINITY : v;
-          }
-        if (mixed) bias = 0.f;
+          for (int i = 0; i < 16; ++i) cn[sub][i] = 0.f;
+        const unsigned char* kp0 = kbuf_at(kt + 1) + lq * L::KSTR + 16 * h;
+        const unsigned char* kp1 = kp0 + 32 * L::KSTR;
+        bf16x8 kf[2 * KS];
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+          kf[2 * j] = *reinterpret_cast<const bf16x8*>(kp0 + 32 * j);
+          kf[2 * j + 1] = *reinterpret_cast<const bf16x8*>(kp1 + 32 * j);
+        }
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+          cn[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[2 * j], qreg[j], cn[0], 0, 0, 0);
+          cn[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[2 * j + 1], qreg[j], cn[1], 0, 0, 0);
+        }
       }
-      // ---- online softmax (exp2 domain) ----
-      float mx = fmaxf(c[0][0], c[1][0]);
-#pragma unroll
-      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(c[0][i], c[1][i]));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, __builtin_fmaf(mx, kLog2e, bias));
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      if (__any(m_new > m_run)) {
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) o[dt][i] *= alpha;
-        l_run *= alpha;
-      }
-      m_run = m_new;
-      const float shift = bias - m_use;
-      bf16x8 pf[4];
+      float ls[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -254,33 +304,77 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
           for (int e = 0; e < 4; ++e) {
             const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(c[sub][8 * jj + 2 * e], kLog2e, shift));
             const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(c[sub][8 * jj + 2 * e + 1], kLog2e, shift));
-            l_run += p0 + p1;
+            ls[e] += p0 + p1;
             pk[e] = pack_bf16x2(p0, p1);
           }
           pf[2 * sub + jj] = __builtin_bit_cast(bf16x8, pk);
         }
-      // ---- O^T += V^T P^T ----
-      // slot e of a lane's P registers holds key 8*(e/4) + 4*h + e%4 of the 16-key step
-      {
-        typedef short s16x4 __attribute__((ext_vector_type(4)));
-        typedef short s16x8 __attribute__((ext_vector_type(8)));
-        typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
-        const unsigned char* vb = buf + L::K_BYTES + vtr_off;
+      l_run += (ls[0] + ls[1]) + (ls[2] + ls[3]);
+      // keep the weights' computation in this block, next to the MFMAs it hides behind
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(pf[j]));
+      asm volatile("" : "+v"(l_run));
+      if (HN) {
+        // issue order: a few fragment reads ahead, then per MFMA one more read and
+        // a slice of the vector work, which fits inside the MFMA's 32 cycles
+        constexpr int kPre = 4;
+        constexpr int kValu = (KS == 8) ? 7 : 14;
+        __builtin_amdgcn_sched_group_barrier(0x100, kPre, 0);
 #pragma unroll
-          for (int dt = 0; dt < DT; ++dt) {
-            const unsigned char* vp = vb + (16 * j) * L::VSTR + (32 * dt) * 2;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * L::VSTR));
-            const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[j], o[dt], 0, 0, 0);
-          }
+        for (int j = 0; j < 2 * KS; ++j) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (j < 2 * KS - kPre) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, kValu, 0);
         }
       }
     }
-    if (kt + 1 < ntiles) store_tile(bufs + ((kt + 1) & 1) * L::BUF);
+    if (HN) mask_tile(cn, kt + 1, bias_n);
+
+    // ---- O^T += V^T P^T of tile kt (matrix cores)  ||  row maximum of tile kt+1 ----
+    // slot e of a lane's P registers holds key 8*(e/4) + 4*h + e%4 of the 16-key step
+    {
+      typedef short s16x4 __attribute__((ext_vector_type(4)));
+      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+      const unsigned char* vb = vbuf_at(kt) + vtr_off;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          const unsigned char* vp = vb + (16 * j) * L::VSTR + (32 * dt) * 2;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * L::VSTR));
+          const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[j], o[dt], 0, 0, 0);
+        }
+      }
+      if (HN) t_max = tile_max(cn, bias_n);
+      constexpr int kPreV = 8;
+      __builtin_amdgcn_sched_group_barrier(0x100, kPreV, 0);
+#pragma unroll
+      for (int j = 0; j < 4 * DT; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (2 * j < 8 * DT - kPreV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        if (HN) __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+      }
+    }
+    if (more_k) store_rows(kbuf_at(kt + 2), L::KSTR, kreg);
+    if (HN) store_rows(vbuf_at(kt + 1), L::VSTR, vreg);
     __syncthreads();
+  };
+  // two tiles per trip so the score registers swap roles without copies
+  f32x16 c2[2];
+  float bias_b = 0.f;
+  int kt = 0;
+  for (; kt + 2 < ntiles; kt += 2) {
+    body(kt, c, bias, c2, bias_b, std::true_type{});
+    body(kt + 1, c2, bias_b, c, bias, std::true_type{});
+  }
+  if (kt + 2 == ntiles) {
+    body(kt, c, bias, c2, bias_b, std::true_type{});
+    body(kt + 1, c2, bias_b, c, bias, std::false_type{});
+  } else if (kt + 1 == ntiles) {
+    body(kt, c, bias, c2, bias_b, std::false_type{});
   }
 
   // ---- epilogue ----
