@@ -82,13 +82,14 @@ typedef struct {
  *   perm_q, perm_k    int32  [levels][B*H][n_cov]     row (index within the head) at each sorted position
  *   pos_k             int32  [levels][B*H][n_cov]     sorted position (within the node) of each key
  *   samples           int32  [total_nodes][m]         l_1..l_m of each node, heap order (level l node j -> 2^l - 1 + j)
+ *   samp_blk          int32  [B*H][total_nodes][m]    floor(pos_k[l_j] / b): the sorted block each sampled key falls in
  *   proj              float  [d][r]                   hyperplane matrix R
  *   part_o, part_l    float  [levels][B*H][n_cov][d] / [levels][B*H][n_cov]   causal only: per-level partial outputs and log row sums
  */
 typedef struct {
   int32_t levels, total_nodes;
   int64_t n_cov;
-  size_t codes_q, codes_k, perm_q, perm_k, pos_k, samples, proj, part_o, part_l;
+  size_t codes_q, codes_k, perm_q, perm_k, pos_k, samples, samp_blk, proj, part_o, part_l;
   size_t total_bytes;
 } ha_ws_layout;
 

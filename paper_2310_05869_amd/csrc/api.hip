@@ -92,6 +92,7 @@ static void fill_layout(const Geometry& g, ha_ws_layout* l) {
   l->perm_k = take(cov * 4);
   l->pos_k = take(cov * 4);
   l->samples = take((size_t)g.total_nodes * g.m * 4);
+  l->samp_blk = take((size_t)g.BH * g.total_nodes * g.m * 4);
   l->proj = take((size_t)g.d * g.r * 4);
   const bool partials = g.causal && g.levels > 0;
   l->part_o = take(partials ? cov * g.d * 4 : 0);
@@ -141,6 +142,7 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
   int32_t* perm_k = (int32_t*)(base + lay.perm_k);
   int32_t* pos_k = (int32_t*)(base + lay.pos_k);
   int32_t* samples = (int32_t*)(base + lay.samples);
+  int32_t* samp_blk = (int32_t*)(base + lay.samp_blk);
   float* proj = (float*)(base + lay.proj);
   float* part_o = (float*)(base + lay.part_o);
   float* part_l = (float*)(base + lay.part_l);
@@ -163,7 +165,7 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
     rc = launch_lsh_hash(K, codes_k, (int64_t)g.BH * g.n, g.d, g.dtype, proj, g.r, st);
     if (rc != HA_OK) return rc;
     mark(2);
-    rc = launch_seg_sort_nodes(codes_q, codes_k, perm_q, perm_k, pos_k, g, st);
+    rc = launch_seg_sort_nodes(codes_q, codes_k, perm_q, perm_k, pos_k, g.m > 0 ? samples : nullptr, samp_blk, g, st);
     if (rc != HA_OK) return rc;
     mark(3);
 
@@ -176,6 +178,7 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
     a.perm_k = perm_k;
     a.pos_k = pos_k;
     a.samples = g.m > 0 ? samples : nullptr;
+    a.samp_blk = g.m > 0 ? samp_blk : nullptr;
     a.use_block = 1;
     a.out_bh_stride = head_stride;
     a.scatter_out = 1;

@@ -104,22 +104,32 @@ __device__ inline int build_key_list(const AttnArgs& a, const TileWork& w, int32
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   constexpr int NW = NT / 64;
-  int nb = 0;
-  if (a.use_block) {
-    nb = g.b;
-    for (int i = tid; i < nb; i += NT)
-      list[i] = a.perm_k ? a.perm_k[w.seg_off + w.t * g.b + i] : w.nr.k_start + w.t * g.b + i;
-  }
-  int base = nb;
+  const int nb = a.use_block ? g.b : 0;
   const int m = (a.samples != nullptr) ? g.m : 0;
+  auto block_key = [&](int i) -> int {
+    return a.perm_k ? a.perm_k[w.seg_off + w.t * g.b + i] : w.nr.k_start + w.t * g.b + i;
+  };
+  auto sample_of = [&](int j, int* blk) -> int {
+    const int l = a.samples[(int64_t)w.nr.heap * g.m + j];
+    if (a.samp_blk) *blk = a.samp_blk[((int64_t)w.bh * g.total_nodes + w.nr.heap) * g.m + j];
+    else *blk = (a.pos_k ? a.pos_k[w.seg_off + l] : l) / g.b;
+    return l;
+  };
+  // the first chunk of both sources is fetched before anything is consumed, so
+  // the two global round trips overlap (b, m <= NT is the common case)
+  int pk0 = 0, l0 = 0, blk0 = 0;
+  if (tid < nb) pk0 = block_key(tid);
+  if (tid < m) l0 = sample_of(tid, &blk0);
+  if (tid < nb) list[tid] = pk0;
+  for (int i = tid + NT; i < nb; i += NT) list[i] = block_key(i);
+  int base = nb;
   for (int j0 = 0; j0 < m; j0 += NT) {
     const int j = j0 + tid;
-    int l = 0;
+    int l = l0, blk = blk0;
     bool keep = false;
     if (j < m) {
-      l = a.samples[(int64_t)w.nr.heap * g.m + j];
-      const int pk = a.pos_k ? a.pos_k[w.seg_off + l] : l;
-      keep = (pk / g.b) != w.t;  // 1 - M_{i, l_j}: same for every row of the block
+      if (j0 > 0) l = sample_of(j, &blk);
+      keep = blk != w.t;  // 1 - M_{i, l_j}: same for every row of the block
     }
     const unsigned long long bal = __ballot(keep);
     if (lane == 0) scratch[wave] = __popcll(bal);

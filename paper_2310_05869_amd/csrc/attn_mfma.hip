@@ -87,23 +87,15 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
 
   const int bid = logical_block(blockIdx.x, gridDim.x);
   TileWork w;
-  int nb, nkeys;
-  if (MODE == kModeNode) {
-    w = decode_node_tile<kQT>(a, bid);
-    nkeys = build_key_list<kNT>(a, w, list, scratch, &nb);
-  } else {
-    w = decode_exact_tile<kQT>(a, bid);
-    nkeys = max(0, w.k1 - w.k0);
-    nb = 0x7fffffff;
-  }
-  const int ntiles = (nkeys + kKT - 1) / kKT;
-  const float bias2 = (MODE == kModeNode && a.g.m > 0) ? log2f((float)w.nr.s / (float)a.g.m) : 0.f;
+  if (MODE == kModeNode) w = decode_node_tile<kQT>(a, bid);
+  else w = decode_exact_tile<kQT>(a, bid);
 
   const uint16_t* Qh = reinterpret_cast<const uint16_t*>(a.Q) + (int64_t)w.bh * a.q_bh_stride;
   const uint16_t* Kh = reinterpret_cast<const uint16_t*>(a.K) + (int64_t)w.bh * a.k_bh_stride;
   const uint16_t* Vh = reinterpret_cast<const uint16_t*>(a.V) + (int64_t)w.bh * a.k_bh_stride;
 
-  // ---- this lane's query row: B operand of S^T = K Q^T, kept in registers ----
+  // ---- this lane's query row: B operand of S^T = K Q^T, kept in registers.
+  // Issued first so the (gathered) row is in flight while the key list is built.
   const int r_in_tile = wave * 32 + lq;
   RowDest dest;
   int qrow_load;   // row to load (always a valid row)
@@ -127,6 +119,16 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qreg[ks] = __builtin_bit_cast(bf16x8, qp[2 * ks]);
   }
+
+  int nb, nkeys;
+  if (MODE == kModeNode) {
+    nkeys = build_key_list<kNT>(a, w, list, scratch, &nb);
+  } else {
+    nkeys = max(0, w.k1 - w.k0);
+    nb = 0x7fffffff;
+  }
+  const int ntiles = (nkeys + kKT - 1) / kKT;
+  const float bias2 = (MODE == kModeNode && a.g.m > 0) ? log2f((float)w.nr.s / (float)a.g.m) : 0.f;
 
   // ---- tile movers ----
   // K and V rows are fetched with buffer loads: a 32-bit per-lane byte offset
@@ -228,14 +230,14 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
   f32x16 c[2];
   float bias = 0.f, t_max = -INFINITY;
   if (ntiles > 0) {
+    // all three tiles are requested before any is stored: one global round trip
+    u32x4 kreg1[TR::NKC];
     load_rows(0, krsrc, kreg);
     load_rows(0, vrsrc, vreg);
+    if (ntiles > 1) load_rows(1, krsrc, kreg1);
     store_rows(kbuf_at(0), L::KSTR, kreg);
     store_rows(vbuf_at(0), L::VSTR, vreg);
-    if (ntiles > 1) {
-      load_rows(1, krsrc, kreg);
-      store_rows(kbuf_at(1), L::KSTR, kreg);
-    }
+    if (ntiles > 1) store_rows(kbuf_at(1), L::KSTR, kreg1);
   }
   __syncthreads();
   if (ntiles > 0) {

@@ -88,6 +88,7 @@ struct AttnArgs {
   const int32_t* perm_k;   // same, or null
   const int32_t* pos_k;    // [levels][BH][n_cov]; null => pos == row
   const int32_t* samples;  // [total_nodes][m] node-local key indices; null or m == 0 => none
+  const int32_t* samp_blk; // [BH][total_nodes][m] sorted block of each sampled key; null => look up pos_k
   int32_t use_block;       // 0: residual part alone
   // outputs
   void* out;        // final output in dtype (may be null)
@@ -107,8 +108,11 @@ struct AttnArgs {
 // launchers (defined in the .hip files)
 int launch_lsh_hash(const void* X, uint8_t* codes, int64_t rows, int d, int dtype, const float* R_dev,
                     int r, hipStream_t st);
+int launch_lsh_hash_mfma(const void* X, uint8_t* codes, int64_t rows, int d, const float* R_dev, int r,
+                         hipStream_t st);
 int launch_seg_sort_nodes(const uint8_t* codes_q, const uint8_t* codes_k, int32_t* perm_q, int32_t* perm_k,
-                          int32_t* pos_k, const Geometry& g, hipStream_t st);
+                          int32_t* pos_k, const int32_t* samples, int32_t* samp_blk, const Geometry& g,
+                          hipStream_t st);
 int launch_seg_sort_flat(const uint8_t* codes, int32_t* perm, int32_t* pos, int n_seg, int seg_len,
                          hipStream_t st);
 int launch_prep(float* R_ws, const float* R_dev, const uint16_t* R_bf16_host, int32_t* samples_ws,

@@ -141,6 +141,7 @@ __global__ __launch_bounds__(256) void lsh_hash_kernel(const T* __restrict__ X, 
 int launch_lsh_hash(const void* X, uint8_t* codes, int64_t rows, int d, int dtype, const float* R_dev, int r,
                     hipStream_t st) {
   if (rows <= 0) return HA_OK;
+  if (dtype == HA_BF16) return launch_lsh_hash_mfma(X, codes, rows, d, R_dev, r, st);  // matrix-core path
   const int esz = dtype == HA_BF16 ? 2 : 4;
   const int rpw = 64 / (d * esz / 16);
   const int64_t ngroups = (rows + rpw - 1) / rpw;

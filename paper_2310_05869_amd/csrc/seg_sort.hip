@@ -23,6 +23,8 @@ struct SortArgs {
   int32_t* perm_q;
   int32_t* perm_k;
   int32_t* pos_k;
+  const int32_t* samples;  // node mode: [total_nodes][m] sample indices ...
+  int32_t* samp_blk;       // ... and where to put the sorted block of each: [BH][total_nodes][m]
   Geometry g;
   int32_t flat;  // 1: n_seg consecutive segments of seg_len keys in codes_q -> perm_q / pos_k, local indices
   int32_t seg_len;
@@ -38,6 +40,8 @@ __global__ __launch_bounds__(kSortWaves * 64) void seg_sort_kernel(SortArgs a) {
   int32_t* perm;
   int32_t* pos;
   int s, value_base;
+  const int32_t* smp = nullptr;
+  int32_t* sblk = nullptr;
   if (a.flat) {
     const int64_t off = (int64_t)blockIdx.x * a.seg_len;
     codes = a.codes_q + off;
@@ -59,6 +63,10 @@ __global__ __launch_bounds__(kSortWaves * 64) void seg_sort_kernel(SortArgs a) {
     const int64_t off = ((int64_t)level * a.g.BH + bh) * a.g.n_cov + (int64_t)node * nr.s;
     perm = (which ? a.perm_k : a.perm_q) + off;
     pos = which ? a.pos_k + off : nullptr;
+    if (which && a.samples && a.samp_blk && a.g.m > 0) {
+      smp = a.samples + (int64_t)heap * a.g.m;
+      sblk = a.samp_blk + ((int64_t)bh * a.g.total_nodes + heap) * a.g.m;
+    }
   }
 
   const int tid = threadIdx.x;
@@ -130,12 +138,21 @@ __global__ __launch_bounds__(kSortWaves * 64) void seg_sort_kernel(SortArgs a) {
     }
     __builtin_amdgcn_wave_barrier();
   }
+
+  // Algorithm 2's factor (1 - M_{i,l_j}) only needs the sorted block of each
+  // sampled key; record it here, where the key segment's positions are at hand.
+  if (sblk) {
+    __threadfence_block();
+    __syncthreads();
+    for (int j = tid; j < a.g.m; j += kSortWaves * 64) sblk[j] = pos[smp[j]] / a.g.b;
+  }
 }
 
 int launch_seg_sort_nodes(const uint8_t* codes_q, const uint8_t* codes_k, int32_t* perm_q, int32_t* perm_k,
-                          int32_t* pos_k, const Geometry& g, hipStream_t st) {
+                          int32_t* pos_k, const int32_t* samples, int32_t* samp_blk, const Geometry& g,
+                          hipStream_t st) {
   if (g.levels <= 0 || g.total_nodes <= 0) return HA_OK;
-  SortArgs a{codes_q, codes_k, perm_q, perm_k, pos_k, g, 0, 0};
+  SortArgs a{codes_q, codes_k, perm_q, perm_k, pos_k, samples, samp_blk, g, 0, 0};
   dim3 grid((unsigned)(2 * g.BH * g.total_nodes)), block(kSortWaves * 64);
   hipLaunchKernelGGL(seg_sort_kernel, grid, block, 0, st, a);
   return check_launch();
