@@ -84,7 +84,8 @@ typedef struct {
  *   samples           int32  [total_nodes][m]         l_1..l_m of each node, heap order (level l node j -> 2^l - 1 + j)
  *   samp_blk          int32  [B*H][total_nodes][m]    floor(pos_k[l_j] / b): the sorted block each sampled key falls in
  *   proj              float  [d][r]                   hyperplane matrix R
- *   part_o, part_l    float  [levels][B*H][n_cov][d] / [levels][B*H][n_cov]   causal only: per-level partial outputs and log row sums
+ *   part_o            dtype  [levels][B*H][n_cov][d]   causal only: per-level partial outputs (normalised), in the tensors' dtype
+ *   part_l            float  [levels][B*H][n_cov]      causal only: log of the per-level partial row sums
  */
 typedef struct {
   int32_t levels, total_nodes;

@@ -251,7 +251,8 @@ def workspace_views(workspace, shape: HaShape, params: HaParams):
         if params.m and lay.total_nodes:
             v["samples"] = view(lay.samples, lay.total_nodes * params.m, torch.int32, (lay.total_nodes, params.m))
         if params.causal:
-            v["part_o"] = view(lay.part_o, cov * d, torch.float32, (lay.levels, BH, lay.n_cov, d))
+            pdt = torch.bfloat16 if shape.dtype == HA_BF16 else torch.float32
+            v["part_o"] = view(lay.part_o, cov * d, pdt, (lay.levels, BH, lay.n_cov, d))
             v["part_l"] = view(lay.part_l, cov, torch.float32, (lay.levels, BH, lay.n_cov))
     return v
 

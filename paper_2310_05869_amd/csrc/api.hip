@@ -95,7 +95,7 @@ static void fill_layout(const Geometry& g, ha_ws_layout* l) {
   l->samp_blk = take((size_t)g.BH * g.total_nodes * g.m * 4);
   l->proj = take((size_t)g.d * g.r * 4);
   const bool partials = g.causal && g.levels > 0;
-  l->part_o = take(partials ? cov * g.d * 4 : 0);
+  l->part_o = take(partials ? cov * g.d * (g.dtype == HA_BF16 ? 2 : 4) : 0);
   l->part_l = take(partials ? cov * 4 : 0);
   l->total_bytes = off < 256 ? 256 : off;
 }
@@ -144,7 +144,7 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
   int32_t* samples = (int32_t*)(base + lay.samples);
   int32_t* samp_blk = (int32_t*)(base + lay.samp_blk);
   float* proj = (float*)(base + lay.proj);
-  float* part_o = (float*)(base + lay.part_o);
+  void* part_o = (void*)(base + lay.part_o);
   float* part_l = (float*)(base + lay.part_l);
   const int64_t head_stride = (int64_t)g.n * g.d;
   auto mark = [&](int i) {
@@ -186,6 +186,7 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
     if (g.causal) {
       a.part_o = part_o;
       a.part_l = part_l;
+      a.part_bf16 = g.dtype == HA_BF16;
     } else {
       a.out = out;
       a.lse = lse;
@@ -209,6 +210,7 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
     a.out_bh_stride = head_stride;
     a.part_o = part_o;
     a.part_l = part_l;
+    a.part_bf16 = g.dtype == HA_BF16;
     a.g = g;
     a.exact_rows_q = a.exact_rows_k = g.n;
     a.exact_block = g.base_len;

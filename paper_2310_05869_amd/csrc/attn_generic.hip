@@ -129,7 +129,7 @@ __global__ __launch_bounds__(kGQT) void attn_generic_kernel(AttnArgs a) {
   if (!dest.valid) return;
 
   if (MODE == kModeNode && a.part_o != nullptr) {
-    float* po = a.part_o + dest.part_row * D;
+    float* po = reinterpret_cast<float*>(a.part_o) + dest.part_row * D;
 #pragma unroll
     for (int c = 0; c < D; c += 4)
       *reinterpret_cast<float4*>(po + c) = make_float4(o[c], o[c + 1], o[c + 2], o[c + 3]);
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(kGQT) void attn_generic_kernel(AttnArgs a) {
       const float lp = a.part_l[pr];
       if (lp == -INFINITY) continue;
       const float wl = expf(lp - mx) / den;
-      const float* po = a.part_o + pr * D;
+      const float* po = reinterpret_cast<const float*>(a.part_o) + pr * D;
 #pragma unroll
       for (int c = 0; c < D; c += 4) {
         const float4 v = *reinterpret_cast<const float4*>(po + c);

@@ -389,22 +389,11 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[dt][i] *= inv;
 
-  if (!dest.valid) return;
-
-  if (MODE == kModeNode && a.part_o != nullptr) {
-    float* po = a.part_o + dest.part_row * D;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const f32x4 v = {o[dt][4 * g4], o[dt][4 * g4 + 1], o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]};
-        *reinterpret_cast<f32x4*>(po + 32 * dt + 8 * g4 + 4 * h) = v;
-      }
-    if (h == 0) a.part_l[dest.part_row] = lse_own;
-    return;
-  }
-
-  if (MODE == kModeExact && a.merge_levels > 0) {
+  // Where the row goes: a partial result of the causal recursion (node mode) or
+  // the final output; in exact mode the partial results of every level of
+  // Algorithm 4 are folded in first (row sum = D_21 + D_C22 at every split).
+  const bool to_partial = (MODE == kModeNode) && a.part_o != nullptr;
+  if (MODE == kModeExact && a.merge_levels > 0 && dest.valid) {
     float mx, den;
     const float Lm = merged_lse(a, w.bh, dest.row_in_head, lse_own, &mx, &den);
     const float w_own = (lse_own == -INFINITY) ? 0.f : expf(lse_own - mx) / den;
@@ -418,12 +407,19 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
       const float lp = a.part_l[pr];
       if (lp == -INFINITY) continue;
       const float wl = expf(lp - mx) / den;
-      const float* po = a.part_o + pr * D;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
-          const f32x4 v = *reinterpret_cast<const f32x4*>(po + 32 * dt + 8 * g4 + 4 * h);
+          const int64_t at = pr * D + 32 * dt + 8 * g4 + 4 * h;
+          f32x4 v;
+          if (a.part_bf16) {
+            const u32x2 raw = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint16_t*>(a.part_o) + at);
+            v = (f32x4){__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xFFFF0000u),
+                        __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xFFFF0000u)};
+          } else {
+            v = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(a.part_o) + at);
+          }
           o[dt][4 * g4] += wl * v.x;
           o[dt][4 * g4 + 1] += wl * v.y;
           o[dt][4 * g4 + 2] += wl * v.z;
@@ -432,20 +428,46 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
     }
     lse_own = Lm;
   }
+  float* lse_dst = to_partial ? a.part_l : a.lse;
+  const int64_t row_dst = to_partial ? dest.part_row : dest.out_row;
+  if (lse_dst != nullptr && dest.valid && h == 0) lse_dst[row_dst] = lse_own;
 
-  if (a.out != nullptr) {
-    uint16_t* op = reinterpret_cast<uint16_t*>(a.out) + dest.out_row * D;
+  // The wave's 32 rows are transposed through LDS (free now: the last barrier of
+  // the loop is behind every wave) so that whole rows leave in 16-byte pieces, 16
+  // (or 32) consecutive lanes per row, instead of 8-byte pieces scattered over 32 rows.
+  unsigned char* dst_base = to_partial ? reinterpret_cast<unsigned char*>(a.part_o) : reinterpret_cast<unsigned char*>(a.out);
+  if (dst_base == nullptr) return;
+  const bool out_fp32 = to_partial && !a.part_bf16;
+  const int row_bytes = D * (out_fp32 ? 4 : 2);
+  const int rs = row_bytes + 16;  // padded LDS row
+  unsigned char* ep = smem + wave * (32 * (D * 4 + 16) + 256);
+  int64_t* ep_rows = reinterpret_cast<int64_t*>(ep + 32 * (D * 4 + 16));
+  if (h == 0) ep_rows[lq] = dest.valid ? row_dst : (int64_t)-1;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+  for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int col = 32 * dt + 8 * g4 + 4 * h;
+      if (out_fp32) {
+        const f32x4 v = {o[dt][4 * g4], o[dt][4 * g4 + 1], o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]};
+        *reinterpret_cast<f32x4*>(ep + lq * rs + col * 4) = v;
+      } else {
         u32x2 v;
         v.x = pack_bf16x2(o[dt][4 * g4], o[dt][4 * g4 + 1]);
         v.y = pack_bf16x2(o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]);
-        *reinterpret_cast<u32x2*>(op + 32 * dt + 8 * g4 + 4 * h) = v;
+        *reinterpret_cast<u32x2*>(ep + lq * rs + col * 2) = v;
       }
+    }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  const int chunks = row_bytes / 16;  // 16-byte pieces per row
+  for (int idx = lane; idx < 32 * chunks; idx += 64) {
+    const int row = idx / chunks, ch = idx % chunks;
+    const int64_t r64 = ep_rows[row];
+    if (r64 >= 0)
+      *reinterpret_cast<u32x4*>(dst_base + r64 * row_bytes + ch * 16) = *reinterpret_cast<const u32x4*>(ep + row * rs + ch * 16);
   }
-  if (a.lse != nullptr && h == 0) a.lse[dest.out_row] = lse_own;
 }
 
 template <int D, int MODE>

@@ -93,8 +93,10 @@ struct AttnArgs {
   // outputs
   void* out;        // final output in dtype (may be null)
   float* lse;       // final log row sum (may be null)
-  float* part_o;    // fp32 outputs [levels][BH][n_cov][d] (node mode when non-null; merged in by the base case)
+  void* part_o;     // outputs [levels][BH][n_cov][d] (node mode when non-null; merged in by the base case):
+                    // bf16 if part_bf16, else fp32
   float* part_l;
+  int32_t part_bf16;
   int64_t out_bh_stride;  // elements between heads of `out` ; lse stride = out_bh_stride / d
   int32_t scatter_out;    // node mode: 1 => write row perm_q[p], 0 => write sorted position p
   Geometry g;

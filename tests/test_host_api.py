@@ -65,7 +65,7 @@ def test_workspace_layout(ha):
     offs = [lay.codes_q, lay.codes_k, lay.perm_q, lay.perm_k, lay.pos_k, lay.samples, lay.proj, lay.part_o,
             lay.part_l, lay.total_bytes]
     assert all(o % 256 == 0 for o in offs) and offs == sorted(offs)
-    assert lay.part_l - lay.part_o == 5 * 32 * 65536 * 128 * 4
+    assert lay.part_l - lay.part_o == 5 * 32 * 65536 * 128 * 2     # bf16 tensors: bf16 partial outputs
     assert ha.ha_workspace_bytes(sh, p) == lay.total_bytes
     # unmasked: one level covering all n rows, no partial buffers
     p2 = ha.make_params(256, 256, 7, False, 4096, 0)
