@@ -286,3 +286,86 @@ def test_empty_and_error_paths(ha, torch):
     with pytest.raises(ha.HyperAttnError) as e:
         ha.hyperattn_forward(q, q, q, 64, 8, 4, workspace=small)
     assert e.value.status == -4
+
+
+# ------------------------------------------------------------------ hash: the uncertified-sign path
+def test_lsh_hash_bf16_rows_with_vanishing_projections(ha, torch):
+    """bf16 rows hashed on the matrix cores: rows whose projection is exactly
+    zero (or all zero) cannot be certified there and must come out of the fp64
+    redo with the oracle's bit (0 for p == 0)."""
+    d, r, rows = 128, 7, 200
+    R = orc.make_projection(11, d, r)                       # bf16-representable
+    X = synth_inputs.iid_qkv(1, 1, rows, d, "bf16", seed=5)[0].reshape(rows, d).copy()
+    X[3] = 0.0
+    for i, (a, b_) in enumerate([(0, 1), (5, 90), (17, 127)]):
+        x = np.zeros(d, dtype=np.float32)
+        x[a], x[b_] = R[b_, 0], -R[a, 0]                    # <x, R[:,0]> == 0 exactly
+        X[10 + i] = x
+    p = orc.lsh_project(X, R)
+    assert p[10, 0] == 0.0 and p[11, 0] == 0.0
+    ref = orc.lsh_codes(p, r)
+    got = ha.ha_lsh_hash(to_device(X, "bf16"), torch.from_numpy(R.astype(np.float32)).cuda()).cpu().numpy()
+    np.testing.assert_array_equal(got, ref)
+
+
+def test_lsh_hash_bf16_rows_with_unrepresentable_R(ha, torch):
+    """Caller-supplied hyperplanes that are not bf16 values: every row takes the fp64 path."""
+    rng = np.random.default_rng(2)
+    d, r, rows = 64, 8, 333
+    X = synth_inputs.iid_qkv(1, 1, rows, d, "bf16", seed=6)[0].reshape(rows, d)
+    R = rng.standard_normal((d, r)).astype(np.float32)
+    ref = orc.lsh_codes(orc.lsh_project(X, R), r)
+    got = ha.ha_lsh_hash(to_device(X, "bf16"), torch.from_numpy(R).cuda()).cpu().numpy()
+    np.testing.assert_array_equal(got, ref)
+
+
+# ------------------------------------------------------------------ full benchmark sizes, sampled heads
+def _full_size_inputs(torch, cfg, host_heads):
+    """All heads drawn on the device from the configuration's law; the checked
+    heads (batch 0, heads < host_heads) come from the seeded host generator."""
+    B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
+    g = torch.Generator(device="cuda")
+    g.manual_seed(99)
+    host = synth_inputs.make_qkv(cfg, B=1, H=host_heads)
+    dev = []
+    for i in range(3):
+        t = torch.randn((B, H, n, d), generator=g, device="cuda", dtype=torch.float32)
+        if cfg["law"] == "iid" or i == 2:
+            t.mul_(d ** -0.25 if cfg["law"] == "iid" else 1.0)
+        t = t.to(torch.bfloat16)
+        t[0, :host_heads] = to_device(host[i][0], "bf16")
+        dev.append(t.contiguous())
+    return dev, host
+
+
+@pytest.mark.parametrize("name,host_heads", [("cfg2_n32k", 2), ("cfg3_n32k_causal", 1), ("cfg4_n131k_causal", 1),
+                                             ("cfg5_n65k_mixture", 1)])
+def test_full_size_configuration_sampled_heads(ha, torch, name, host_heads):
+    """The benchmark configurations at full size, in the launch configuration
+    bench.py times; the heads fed from the host generator are compared with the
+    oracle element by element (codes first, then outputs)."""
+    cfg = synth_inputs.CONFIGS[name]
+    print(f"full size {name}: checking {host_heads} head(s) against the oracle", flush=True)
+    (Q, K, V), host = _full_size_inputs(torch, cfg, host_heads)
+    B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
+    shape = ha.make_shape(B, H, n, d, ha.HA_BF16)
+    params = ha.make_params(cfg["b"], cfg["m"], cfg["r"], cfg["causal"], cfg["n_min"], cfg["seed"])
+    ws = ha.alloc_workspace(shape, params)
+    out, lse = ha.hyperattn_forward(Q, K, V, cfg["b"], cfg["m"], cfg["r"], causal=cfg["causal"], n_min=cfg["n_min"],
+                                    seed=cfg["seed"], workspace=ws)
+    torch.cuda.synchronize()
+    views = ha.workspace_views(ws, shape, params)
+    stages = {}
+    ref_out, ref_lse, absv = run_oracle(*host, cfg, stages=stages, with_absv=True)
+    gpu_codes = np.stack([views["codes_q"][:host_heads].cpu().numpy(), views["codes_k"][:host_heads].cpu().numpy()])
+    flips = compare_codes(gpu_codes, stages, cfg["r"])
+    if flips:
+        print(f"  replaying {len(flips)} near-zero sign bits in the oracle", flush=True)
+        ref_out, ref_lse, absv = run_oracle(*host, cfg, flip=flips, with_absv=True)
+    got = to_host(out[0, :host_heads])[None]
+    err = assert_close(got, ref_out, "bf16", "out", absv if cfg["law"] == "mixture" else None)
+    assert_lse_close(to_host(lse[0, :host_heads])[None], ref_lse, "bf16", "lse")
+    over = int((np.abs(got - ref_out) > 2e-3).sum())
+    print(f"  max abs err {err:.3e}; elements over 2e-3: {over} of {got.size}; sign flips {len(flips)}", flush=True)
+    # the unchecked heads: rows are normalised and finite
+    assert torch.isfinite(out).all() and torch.isfinite(lse).all()
