@@ -27,6 +27,13 @@ import synth_inputs  # noqa: E402
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 
+# HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc runs summarised in
+# profiles/bench_cfg4_n131k_causal_hbm_traffic.txt (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB).
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg4_n131k_causal", "base"): int((3134603.9 * 2.0 + 1064960.0) * 1024),
+    ("cfg4_n131k_causal", "node"): int((3981874.3 * 2.0 + 2800454.3) * 1024),
+}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -138,11 +145,14 @@ def main():
     hash_gbs = work["hash_bytes"] / (stage["lsh_hash"] * 1e-3) / 1e9 if stage["lsh_hash"] > 0 else 0.0
     # the dominant kernel: the causal base case when there is one, else the node attention
     if stage["causal_base"] >= stage["node_attn"]:
-        dom, dom_tf, dom_flop, dom_ms = "attn_mfma_kernel<exact> (causal base case)", base_tf, work["base_flop"], stage["causal_base"]
+        dom, dom_tf, dom_flop, dom_ms, key = ("attn_mfma_kernel<exact> (causal base case)", base_tf, work["base_flop"],
+                                              stage["causal_base"], "base")
     else:
-        dom, dom_tf, dom_flop, dom_ms = "attn_mfma_kernel<node> (block + sampled)", node_tf, work["node_flop"], stage["node_attn"]
+        dom, dom_tf, dom_flop, dom_ms, key = ("attn_mfma_kernel<node> (block + sampled)", node_tf, work["node_flop"],
+                                              stage["node_attn"], "node")
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(dom_tf, 2), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(dom_tf / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(dom_tf / PEAK_BF16_TFLOPS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, key)),
                 "flop_per_launch": dom_flop, "ms_per_launch": round(dom_ms, 4)}
 
     result = {
