@@ -39,8 +39,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kQT = 128;      // queries per workgroup
-constexpr int kNT = 256;      // threads
 constexpr int kKT = 64;       // keys per step
 
 template <int D>
@@ -63,17 +61,20 @@ __host__ __device__ inline size_t mfma_lds_bytes(int b, int m, int mode) {
 
 __device__ inline float max3f(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 
-template <int D>
+template <int D, int NT>
 struct TileRegs {
   static constexpr int CPR = D / 8;              // 16-byte chunks per K row
-  static constexpr int NKC = kKT * CPR / kNT;    // K (and V) chunks per thread
+  static constexpr int NKC = kKT * CPR / NT;     // K (and V) chunks per thread
 };
 
-template <int D, int MODE>
-__global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
+// NW waves per workgroup (32 queries each); two waves per SIMD in either case.
+template <int D, int MODE, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int kQT = 32 * NW;  // queries per workgroup
+  constexpr int kNT = 64 * NW;  // threads
   using L = Lds<D>;
-  using TR = TileRegs<D>;
+  using TR = TileRegs<D, kNT>;
   constexpr int KS = D / 16;  // MFMA k-steps of the score product
   constexpr int DT = D / 32;  // 32-wide d tiles of the output
 
@@ -440,8 +441,9 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
   const bool out_fp32 = to_partial && !a.part_bf16;
   const int row_bytes = D * (out_fp32 ? 4 : 2);
   const int rs = row_bytes + 16;  // padded LDS row
-  unsigned char* ep = smem + wave * (32 * (D * 4 + 16) + 256);
-  int64_t* ep_rows = reinterpret_cast<int64_t*>(ep + 32 * (D * 4 + 16));
+  constexpr int kEpRow = D * (MODE == kModeNode ? 4 : 2) + 16;  // widest padded row this mode stores
+  unsigned char* ep = smem + wave * (32 * kEpRow + 256);
+  int64_t* ep_rows = reinterpret_cast<int64_t*>(ep + 32 * kEpRow);
   if (h == 0) ep_rows[lq] = dest.valid ? row_dst : (int64_t)-1;
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
@@ -470,28 +472,40 @@ __global__ __launch_bounds__(kNT, 2) void attn_mfma_kernel(AttnArgs a) {
   }
 }
 
-template <int D, int MODE>
-static int launch_one(const AttnArgs& a, int grid, hipStream_t st) {
+template <int D, int MODE, int NW>
+static int launch_one(const AttnArgs& a, hipStream_t st) {
+  const int grid = MODE == kModeNode ? node_grid<32 * NW>(a.g) : exact_grid<32 * NW>(a);
+  if (grid <= 0) return HA_OK;
   const size_t lds = mfma_lds_bytes<D>(a.g.b, a.g.m, MODE);
   static bool configured = false;  // per instantiation
   if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<D, MODE>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<D, MODE, NW>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
       (void)hipGetLastError();
       return HA_ERR_LAUNCH;
     }
     configured = true;
   }
-  hipLaunchKernelGGL((attn_mfma_kernel<D, MODE>), dim3((unsigned)grid), dim3(kNT), lds, st, a);
+  hipLaunchKernelGGL((attn_mfma_kernel<D, MODE, NW>), dim3((unsigned)grid), dim3(64 * NW), lds, st, a);
   return check_launch();
 }
 
+// Waves per workgroup: node tiles (short key loops) use 4, two workgroups per
+// CU, so one workgroup's gathers overlap the other's MFMAs; exact attention and
+// the causal base case (long key loops) can share each K / V tile among 8 waves.
+#ifndef HA_NW_NODE
+#define HA_NW_NODE 4
+#endif
+#ifndef HA_NW_EXACT
+#define HA_NW_EXACT 4
+#endif
+
 int launch_attn_mfma(const AttnArgs& a, int mode, hipStream_t st) {
   if (a.g.dtype != HA_BF16) return HA_ERR_DTYPE;
-  const int grid = mode == kModeNode ? node_grid<kQT>(a.g) : exact_grid<kQT>(a);
-  if (grid <= 0) return HA_OK;
-  if (a.g.d == 128) return mode == kModeNode ? launch_one<128, kModeNode>(a, grid, st) : launch_one<128, kModeExact>(a, grid, st);
-  if (a.g.d == 64) return mode == kModeNode ? launch_one<64, kModeNode>(a, grid, st) : launch_one<64, kModeExact>(a, grid, st);
+  if (a.g.d == 128)
+    return mode == kModeNode ? launch_one<128, kModeNode, HA_NW_NODE>(a, st) : launch_one<128, kModeExact, HA_NW_EXACT>(a, st);
+  if (a.g.d == 64)
+    return mode == kModeNode ? launch_one<64, kModeNode, HA_NW_NODE>(a, st) : launch_one<64, kModeExact, HA_NW_EXACT>(a, st);
   return HA_ERR_SHAPE;
 }
 
