@@ -6,9 +6,10 @@
 //   P   = X R          32 rows x 32 columns (r of them real) per wave and trip
 //   P'  = |X| |R|      same shape: sum_c |x_c R_ck|, the scale of the rounding error
 //
-// A wave reads 32 rows straight from global memory in the MFMA's A layout
+// A wave reads 32 rows straight from global memory in the MFMA's operand layout
 // (lane l: row l%32, 8 consecutive elements starting at 16*ks + 8*(l/32)); R
-// and |R| sit in registers as B operands.  bf16 x bf16 products are exact; the
+// and |R| sit in registers as the other operand.  The products are formed as
+// R^T X^T so that a lane ends up with the projections of ONE row.  bf16 x bf16 products are exact; the
 // fp32 accumulation of the d products deviates from the exact sum by far less
 // than 2^-14 * P' (d <= 128 terms, fp32 unit roundoff 2^-24 per add, with a 4x
 // margin for the matrix core's internal order).  So sign(P) is certified
@@ -27,6 +28,7 @@ namespace ha {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Two packed non-negative bf16 values times 2^-14 (exact: exponent minus 14);
 // values below 2^-112 become zero.
@@ -47,7 +49,7 @@ __global__ __launch_bounds__(256) void lsh_hash_mfma_kernel(const uint16_t* __re
   const int lane = threadIdx.x & 63;
   const int n = lane & 31, h = lane >> 5;
 
-  // B operands: R and |R| as bf16, column n (zero for n >= r)
+  // matrix operands R^T and |R|^T as bf16: projection n (zero for n >= r)
   u32x4 rb[KS], rabs[KS];
   bool exact = true;
 #pragma unroll
@@ -74,6 +76,14 @@ __global__ __launch_bounds__(256) void lsh_hash_mfma_kernel(const uint16_t* __re
     for (int e = 0; e < 4; ++e) rabs[ks][e] = scale_bf16x2_down14(rabs[ks][e]);
   const bool all_exact = __all(exact);
 
+  // for the fp64 path: R in fp32, eight columns per row (zero beyond r), and one
+  // row of X per wave
+  __shared__ __attribute__((aligned(16))) float Rs[D * 8];
+  __shared__ __attribute__((aligned(16))) uint16_t xrow[4][D];
+  const int wv = threadIdx.x >> 6;
+  for (int i = threadIdx.x; i < D * 8; i += blockDim.x) Rs[i] = (i % 8) < r ? R[(i / 8) * r + (i % 8)] : 0.f;
+  __syncthreads();
+
   const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
   const int64_t ngroups = (rows + 31) / 32;
@@ -88,7 +98,10 @@ __global__ __launch_bounds__(256) void lsh_hash_mfma_kernel(const uint16_t* __re
   const uint32_t mask_r = (1u << r) - 1u;
   auto trip = [&](int64_t g, u32x4 (&xa)[KS], u32x4 (&xn)[KS]) {
     const int64_t row0 = g * 32;
-    if (g + nwaves < ngroups) load_group(g + nwaves, xn);
+    // unconditional (past the end: this trip's own rows again, a cache hit), so
+    // the count of loads in flight is the same on every path and the waits
+    // before the MFMAs below leave the two younger groups in flight
+    load_group(g + 2 * nwaves < ngroups ? g + 2 * nwaves : g, xn);
 
     f32x16 p, pa;
 #pragma unroll
@@ -98,48 +111,59 @@ __global__ __launch_bounds__(256) void lsh_hash_mfma_kernel(const uint16_t* __re
     }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      p = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[ks]), __builtin_bit_cast(bf16x8, rb[ks]),
+      p = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, rb[ks]), __builtin_bit_cast(bf16x8, xa[ks]),
                                                   p, 0, 0, 0);
       const u32x4 ax = xa[ks] & 0x7FFF7FFFu;
-      pa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ax), __builtin_bit_cast(bf16x8, rabs[ks]),
+      pa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, rabs[ks]), __builtin_bit_cast(bf16x8, ax),
                                                    pa, 0, 0, 0);
     }
 
-    // Accumulator element i of lane (n, h) is row 8*(i/4) + 4*h + i%4, column n:
-    // a ballot over the wave yields the sign word of row j_lo = 8*(i/4) + i%4 in
-    // its low half and of row j_lo + 4 in its high half.  The words are uniform
-    // values, dropped into lane j of my_word; doubt is collected as a row mask.
-    uint32_t my_word = 0;
-    uint32_t doubt_rows = all_exact ? 0u : 0xFFFFFFFFu;
+    // The product is taken transposed (R^T X^T), so accumulator element i < 4 of
+    // lane (n, h) is projection 4 h + i of row n: every lane forms one nibble of
+    // its row's sign word, and the two halves of the wave swap nibbles.
+    uint32_t nib = 0;
+    bool lane_doubt = !all_exact;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const unsigned long long sign = __ballot(p[i] > 0.f);
-      const unsigned long long doubt = __ballot(!(fabsf(p[i]) > pa[i]));
-      const int j_lo = 8 * (i / 4) + (i % 4);
-      asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(my_word) : "s"((uint32_t)sign & mask_r), "n"(j_lo));
-      asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(my_word) : "s"((uint32_t)(sign >> 32) & mask_r), "n"(j_lo + 4));
-      if ((uint32_t)doubt & mask_r) doubt_rows |= 1u << j_lo;
-      if ((uint32_t)(doubt >> 32) & mask_r) doubt_rows |= 1u << (j_lo + 4);
+    for (int i = 0; i < 4; ++i) {
+      const bool real = 4 * h + i < r;
+      nib |= (p[i] > 0.f ? 1u : 0u) << i;
+      lane_doubt = lane_doubt || (real && !(fabsf(p[i]) > pa[i]));
     }
+    nib <<= 4 * h;
+    uint32_t my_word = (nib | (uint32_t)__shfl_xor((int)nib, 32)) & mask_r;
+    const unsigned long long dbal = __ballot(lane_doubt);
+    const uint32_t doubt_rows = (uint32_t)dbal | (uint32_t)(dbal >> 32);
     const int64_t left = rows - row0;
-    unsigned long long redo = doubt_rows;
-    if (left < 32) redo &= (1ull << left) - 1ull;
+    // a wave-uniform row mask, held in scalar registers
+    uint32_t redo = __builtin_amdgcn_readfirstlane(doubt_rows);
+    if (left < 32) redo &= (1u << left) - 1u;
 
-    // exact fp64 evaluation of the doubtful rows, one row at a time by the whole wave
+    // Exact fp64 evaluation of the doubtful rows, one row at a time by the whole
+    // wave: the two lanes that hold row j hand it over through LDS, then lane l
+    // multiplies elements EL*l .. EL*l + EL - 1 with their rows of R.
     while (redo) {
-      const int j = __ffsll((long long)redo) - 1;
+      const int j = __builtin_ctz(redo);
       redo &= redo - 1;
-      const uint16_t* xr = X + (row0 + j) * D + lane * EL;
+      if (n == j) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) *reinterpret_cast<u32x4*>(&xrow[wv][16 * ks + 8 * h]) = xa[ks];
+      }
+      __builtin_amdgcn_wave_barrier();  // LDS serves one wave's requests in order
       double acc[8];
 #pragma unroll
       for (int k = 0; k < 8; ++k) acc[k] = 0.0;
 #pragma unroll
       for (int e = 0; e < EL; ++e) {
-        const double x = (double)__uint_as_float((uint32_t)xr[e] << 16);
+        const double x = (double)__uint_as_float((uint32_t)xrow[wv][lane * EL + e] << 16);
+        const f32x4 r0 = *reinterpret_cast<const f32x4*>(&Rs[(lane * EL + e) * 8]);
+        const f32x4 r1 = *reinterpret_cast<const f32x4*>(&Rs[(lane * EL + e) * 8 + 4]);
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
-          if (k < r) acc[k] = __builtin_fma(x, (double)R[(lane * EL + e) * r + k], acc[k]);
+        for (int k = 0; k < 4; ++k) {
+          acc[k] = __builtin_fma(x, (double)r0[k], acc[k]);
+          acc[4 + k] = __builtin_fma(x, (double)r1[k], acc[4 + k]);
+        }
       }
+      __builtin_amdgcn_wave_barrier();
       // transposing butterfly over the 64 lanes: 8 -> 4 -> 2 -> 1 values, then plain
       const bool u1 = (lane & 32) != 0;
       double w4[4];
@@ -165,8 +189,9 @@ __global__ __launch_bounds__(256) void lsh_hash_mfma_kernel(const uint16_t* __re
       // lane l now holds projection (l >> 3) & 7
       const unsigned long long bal = __ballot(ws > 0.0);
       uint32_t word = 0;
-      for (int k = 0; k < r; ++k) word |= (uint32_t)((bal >> (8 * k)) & 1ull) << k;
-      if (lane == j) my_word = word;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) word |= (uint32_t)((bal >> (8 * k)) & 1ull) << k;
+      if (lane == j) my_word = word & mask_r;
     }
 
     if (lane < 32 && row0 + lane < rows) {
@@ -178,24 +203,37 @@ __global__ __launch_bounds__(256) void lsh_hash_mfma_kernel(const uint16_t* __re
       codes[row0 + lane] = (uint8_t)idx;
     }
   };
-  // rows of the next trip are requested before the current trip is processed;
-  // two trips per loop pass so the two register sets swap roles without copies
-  u32x4 xa[KS], xb[KS];
+  // the rows of the next two trips are in flight while the current one is
+  // processed; three register sets rotate so nothing is copied
+  u32x4 xa[KS], xb[KS], xc[KS];
   int64_t g = wave;
-  if (g < ngroups) load_group(g, xa);
-  for (; g + nwaves < ngroups; g += 2 * nwaves) {
-    trip(g, xa, xb);
-    trip(g + nwaves, xb, xa);
+  if (g >= ngroups) return;
+  load_group(g, xa);
+  load_group(g + nwaves < ngroups ? g + nwaves : g, xb);
+  while (g < ngroups) {
+    trip(g, xa, xc);
+    g += nwaves;
+    if (g >= ngroups) break;
+    trip(g, xb, xa);
+    g += nwaves;
+    if (g >= ngroups) break;
+    trip(g, xc, xb);
+    g += nwaves;
   }
-  if (g < ngroups) trip(g, xa, xb);
 }
+
+#ifndef HA_HASH_BLOCKS
+#define HA_HASH_BLOCKS 512
+#endif
+// resident-sized grid (two 4-wave blocks per CU): every wave streams many 32-row groups
+constexpr int kHashBlocks = HA_HASH_BLOCKS;
 
 int launch_lsh_hash_mfma(const void* X, uint8_t* codes, int64_t rows, int d, const float* R_dev, int r,
                          hipStream_t st) {
   if (rows <= 0) return HA_OK;
   const int64_t ngroups = (rows + 31) / 32;
   int64_t blocks = (ngroups + 3) / 4;
-  if (blocks > 2048) blocks = 2048;
+  if (blocks > kHashBlocks) blocks = kHashBlocks;
   dim3 grid((unsigned)blocks), block(256);
   if (d == 128)
     hipLaunchKernelGGL((lsh_hash_mfma_kernel<128>), grid, block, 0, st, (const uint16_t*)X, codes, rows, R_dev, r);
