@@ -50,6 +50,15 @@ struct Lds {
   static constexpr int BUF = K_BYTES + V_BYTES;
 };
 
+// Epilogue staging per wave: 32 fp32 rows (padded), 32 x kMaxFold merge weights, 32 row ids,
+// kMaxFold partial-row bases.
+constexpr int kMaxFold = 8;
+template <int D>
+struct EpLds {
+  static constexpr int ROW = D * 4 + 16;
+  static constexpr int WAVE = 32 * ROW + 32 * kMaxFold * 4 + 32 * 8 + kMaxFold * 8;
+};
+
 __host__ __device__ inline int list_capacity(int b, int m) { return ((b + m + 63) & ~63) + 64; }
 
 template <int D>
@@ -385,16 +394,80 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
   const bool empty = !(l_tot > 0.f);
   const float inv = empty ? 0.f : 1.f / l_tot;
   float lse_own = empty ? -INFINITY : (m_run + log2f(l_tot)) * kLn2;
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) o[dt][i] *= inv;
-
   // Where the row goes: a partial result of the causal recursion (node mode) or
   // the final output; in exact mode the partial results of every level of
   // Algorithm 4 are folded in first (row sum = D_21 + D_C22 at every split).
+  //
+  // The wave's 32 rows are transposed through LDS in fp32 (free now: the last
+  // barrier of the loop is behind every wave), so that rows leave, and partial
+  // rows arrive, as whole 16-byte pieces on consecutive lanes.
   const bool to_partial = (MODE == kModeNode) && a.part_o != nullptr;
-  if (MODE == kModeExact && a.merge_levels > 0 && dest.valid) {
+  unsigned char* ep = smem + wave * EpLds<D>::WAVE;
+  float* ep_w = reinterpret_cast<float*>(ep + 32 * EpLds<D>::ROW);
+  int64_t* ep_rows = reinterpret_cast<int64_t*>(ep + 32 * EpLds<D>::ROW + 32 * kMaxFold * 4);
+  int64_t* ep_pr = ep_rows + 32;
+
+  // Levels folded row-major below (up to kMaxFold of them).  The 32 rows of a wave
+  // lie in one n_min block, so every level treats them alike: either none of
+  // them belongs to its off-diagonal node, or they are 32 consecutive partial rows.
+  const bool fold = MODE == kModeExact && a.merge_levels > 0;
+  const bool fold_rows = fold && a.merge_levels <= kMaxFold;
+  uint32_t touched = 0;
+  int nfold = 0;  // number of touched levels
+  int64_t pr0[kMaxFold];
+  float scale_own = inv;
+  if (fold_rows) {
+    const int i0 = w.q0 + 32 * __builtin_amdgcn_readfirstlane(wave);
+    float lp[kMaxFold];
+#pragma unroll
+    for (int u = 0; u < kMaxFold; ++u) {
+      lp[u] = -INFINITY;
+      pr0[u] = 0;
+      int64_t pr;
+      if (u < a.merge_levels && level_touches(a.g, w.bh, i0, u, &pr)) {
+        touched |= 1u << u;
+        pr0[u] = pr;
+        if (dest.valid) lp[u] = a.part_l[pr + lq];
+      }
+    }
+    float mx = lse_own;
+#pragma unroll
+    for (int u = 0; u < kMaxFold; ++u) mx = fmaxf(mx, lp[u]);
+    float w_own = 0.f, wl[kMaxFold];
+#pragma unroll
+    for (int u = 0; u < kMaxFold; ++u) wl[u] = 0.f;
+    if (mx != -INFINITY) {
+      const float e_own = expf(lse_own - mx);
+      float den = e_own;
+#pragma unroll
+      for (int u = 0; u < kMaxFold; ++u) {
+        wl[u] = expf(lp[u] - mx);
+        den += wl[u];
+      }
+      const float rden = 1.f / den;
+      w_own = e_own * rden;
+#pragma unroll
+      for (int u = 0; u < kMaxFold; ++u) wl[u] *= rden;
+      lse_own = mx + logf(den);
+    }
+    scale_own = inv * w_own;
+    // weights and partial-row bases of the touched levels, compacted (the set
+    // of touched levels is the same for the whole wave)
+#pragma unroll
+    for (int u = 0; u < kMaxFold; ++u)
+      if ((touched >> u) & 1u) {
+        if (h == 0) ep_w[lq * kMaxFold + nfold] = wl[u];
+        if (lane == 0) ep_pr[nfold] = pr0[u];
+        ++nfold;
+      }
+  }
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[dt][i] *= scale_own;
+
+  if (fold && !fold_rows && dest.valid) {
+    // deeper recursions than kMaxFold levels: fold in the accumulator layout
     float mx, den;
     const float Lm = merged_lse(a, w.bh, dest.row_in_head, lse_own, &mx, &den);
     const float w_own = (lse_own == -INFINITY) ? 0.f : expf(lse_own - mx) / den;
@@ -433,42 +506,91 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
   const int64_t row_dst = to_partial ? dest.part_row : dest.out_row;
   if (lse_dst != nullptr && dest.valid && h == 0) lse_dst[row_dst] = lse_own;
 
-  // The wave's 32 rows are transposed through LDS (free now: the last barrier of
-  // the loop is behind every wave) so that whole rows leave in 16-byte pieces, 16
-  // (or 32) consecutive lanes per row, instead of 8-byte pieces scattered over 32 rows.
   unsigned char* dst_base = to_partial ? reinterpret_cast<unsigned char*>(a.part_o) : reinterpret_cast<unsigned char*>(a.out);
   if (dst_base == nullptr) return;
   const bool out_fp32 = to_partial && !a.part_bf16;
-  const int row_bytes = D * (out_fp32 ? 4 : 2);
-  const int rs = row_bytes + 16;  // padded LDS row
-  constexpr int kEpRow = D * (MODE == kModeNode ? 4 : 2) + 16;  // widest padded row this mode stores
-  unsigned char* ep = smem + wave * (32 * kEpRow + 256);
-  int64_t* ep_rows = reinterpret_cast<int64_t*>(ep + 32 * kEpRow);
+  constexpr int rs = EpLds<D>::ROW;
   if (h == 0) ep_rows[lq] = dest.valid ? row_dst : (int64_t)-1;
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
     for (int g4 = 0; g4 < 4; ++g4) {
       const int col = 32 * dt + 8 * g4 + 4 * h;
-      if (out_fp32) {
-        const f32x4 v = {o[dt][4 * g4], o[dt][4 * g4 + 1], o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]};
-        *reinterpret_cast<f32x4*>(ep + lq * rs + col * 4) = v;
-      } else {
-        u32x2 v;
-        v.x = pack_bf16x2(o[dt][4 * g4], o[dt][4 * g4 + 1]);
-        v.y = pack_bf16x2(o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]);
-        *reinterpret_cast<u32x2*>(ep + lq * rs + col * 2) = v;
-      }
+      const f32x4 v = {o[dt][4 * g4], o[dt][4 * g4 + 1], o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]};
+      *reinterpret_cast<f32x4*>(ep + lq * rs + col * 4) = v;
     }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  const int chunks = row_bytes / 16;  // 16-byte pieces per row
-  for (int idx = lane; idx < 32 * chunks; idx += 64) {
-    const int row = idx / chunks, ch = idx % chunks;
-    const int64_t r64 = ep_rows[row];
-    if (r64 >= 0)
-      *reinterpret_cast<u32x4*>(dst_base + r64 * row_bytes + ch * 16) = *reinterpret_cast<const u32x4*>(ep + row * rs + ch * 16);
+  constexpr int CH = D / 8;  // 8-element pieces per row
+  // NF = number of partial rows folded into every row; a compile-time count so
+  // that all their loads are issued before the first is consumed
+  auto drain = [&](auto nf_tag) {
+    constexpr int NF = decltype(nf_tag)::value;
+    int64_t prc[NF > 0 ? NF : 1];
+#pragma unroll
+    for (int c = 0; c < NF; ++c) prc[c] = ep_pr[c];
+#pragma unroll 2
+    for (int idx = lane; idx < 32 * CH; idx += 64) {
+      const int row = idx / CH, ch = idx % CH;
+      const int64_t r64 = ep_rows[row];
+      if (r64 < 0) continue;
+      u32x4 raw[NF > 0 ? NF : 1][2];
+#pragma unroll
+      for (int c = 0; c < NF; ++c) {
+        const int64_t at = (prc[c] + row) * D + ch * 8;
+        if (a.part_bf16) {
+          raw[c][0] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(a.part_o) + at);
+        } else {
+          raw[c][0] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const float*>(a.part_o) + at);
+          raw[c][1] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const float*>(a.part_o) + at + 4);
+        }
+      }
+      f32x4 v0 = *reinterpret_cast<const f32x4*>(ep + row * rs + ch * 32);
+      f32x4 v1 = *reinterpret_cast<const f32x4*>(ep + row * rs + ch * 32 + 16);
+#pragma unroll
+      for (int c = 0; c < NF; ++c) {
+        const float wl = ep_w[row * kMaxFold + c];
+        f32x4 p0, p1;
+        if (a.part_bf16) {
+          const u32x4 q = raw[c][0];
+          p0 = (f32x4){__uint_as_float(q.x << 16), __uint_as_float(q.x & 0xFFFF0000u),
+                       __uint_as_float(q.y << 16), __uint_as_float(q.y & 0xFFFF0000u)};
+          p1 = (f32x4){__uint_as_float(q.z << 16), __uint_as_float(q.z & 0xFFFF0000u),
+                       __uint_as_float(q.w << 16), __uint_as_float(q.w & 0xFFFF0000u)};
+        } else {
+          p0 = __builtin_bit_cast(f32x4, raw[c][0]);
+          p1 = __builtin_bit_cast(f32x4, raw[c][1]);
+        }
+        if (wl != 0.f) {  // a partial with an empty row sum carries no defined values
+          v0 += wl * p0;
+          v1 += wl * p1;
+        }
+      }
+      if (out_fp32) {
+        f32x4* dp = reinterpret_cast<f32x4*>(dst_base + (r64 * D + ch * 8) * 4);
+        dp[0] = v0;
+        dp[1] = v1;
+      } else {
+        const u32x4 pk = {pack_bf16x2(v0.x, v0.y), pack_bf16x2(v0.z, v0.w), pack_bf16x2(v1.x, v1.y), pack_bf16x2(v1.z, v1.w)};
+        *reinterpret_cast<u32x4*>(dst_base + (r64 * D + ch * 8) * 2) = pk;
+      }
+    }
+  };
+  if (MODE == kModeExact) {
+    switch (nfold) {
+      case 0: drain(std::integral_constant<int, 0>{}); break;
+      case 1: drain(std::integral_constant<int, 1>{}); break;
+      case 2: drain(std::integral_constant<int, 2>{}); break;
+      case 3: drain(std::integral_constant<int, 3>{}); break;
+      case 4: drain(std::integral_constant<int, 4>{}); break;
+      case 5: drain(std::integral_constant<int, 5>{}); break;
+      case 6: drain(std::integral_constant<int, 6>{}); break;
+      case 7: drain(std::integral_constant<int, 7>{}); break;
+      default: drain(std::integral_constant<int, 8>{}); break;
+    }
+  } else {
+    drain(std::integral_constant<int, 0>{});
   }
 }
 
@@ -476,7 +598,8 @@ template <int D, int MODE, int NW>
 static int launch_one(const AttnArgs& a, hipStream_t st) {
   const int grid = MODE == kModeNode ? node_grid<32 * NW>(a.g) : exact_grid<32 * NW>(a);
   if (grid <= 0) return HA_OK;
-  const size_t lds = mfma_lds_bytes<D>(a.g.b, a.g.m, MODE);
+  size_t lds = mfma_lds_bytes<D>(a.g.b, a.g.m, MODE);
+  if (lds < (size_t)NW * EpLds<D>::WAVE) lds = (size_t)NW * EpLds<D>::WAVE;
   static bool configured = false;  // per instantiation
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<D, MODE, NW>),
