@@ -213,7 +213,11 @@ def test_forward_unmasked_bf16(ha, torch, d, n, b, m, law):
 
 @pytest.mark.parametrize("dtype,d,n,n_min,b,m", [("bf16", 128, 2048, 256, 128, 64), ("bf16", 64, 4096, 1024, 256, 256),
                                                  ("fp32", 64, 512, 64, 32, 16), ("bf16", 128, 1024, 4096, 256, 256),
-                                                 ("bf16", 128, 1024, 512, 512, 0)])
+                                                 ("bf16", 128, 1024, 512, 512, 0),
+                                                 # nine levels of recursion (more than the epilogue folds row-major)
+                                                 ("bf16", 64, 8192, 16, 16, 8),
+                                                 # eight levels, base blocks smaller than a query tile
+                                                 ("bf16", 128, 8192, 32, 32, 16)])
 def test_forward_causal(ha, torch, dtype, d, n, n_min, b, m):
     print(f"forward causal {dtype} d={d} n={n} n_min={n_min} b={b} m={m}", flush=True)
     cfg = dict(B=2, H=1, n=n, d=d, dtype=dtype, law="iid", b=b, m=m, r=7, causal=1, n_min=n_min, seed=3)
