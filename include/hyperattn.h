@@ -194,6 +194,21 @@ int ha_merge_unpermute(const float* o_b, const float* lse_b, const float* o_r, c
                        const int32_t* perm_q, void* out, float* lse, int32_t groups, int32_t n,
                        int32_t d, int32_t dtype, void* stream);
 
+/* Measurement aids (no passage of the paper: they serve the roofline report).
+ * Both run on `stream`, time themselves with events and WAIT for the stream;
+ * `buf` is caller-owned device memory that they overwrite.
+ *
+ * ha_measure_mfma_rate: bf16 matrix-core rate of register-resident chains of the
+ * 32x32x16 MFMA the attention kernels use, `iters` loop trips per wave
+ * (1..2^20; 2000 takes a few ms), in TFLOP/s.  buf >= 512 KiB.
+ * ha_measure_hbm_rate: GB/s of a streaming read of the first half of buf, and of
+ * a copy of the first half onto the second (read + written bytes counted).
+ * buf 16-byte aligned, bytes >= 1 MiB; use a buffer well beyond the caches.
+ * Errors: HA_ERR_NULL, HA_ERR_WORKSPACE (buf too small / misaligned),
+ * HA_ERR_SHAPE (iters), HA_ERR_LAUNCH. */
+int ha_measure_mfma_rate(void* buf, size_t bytes, int32_t iters, float* tflops, void* stream);
+int ha_measure_hbm_rate(void* buf, size_t bytes, float* read_gbs, float* copy_gbs, void* stream);
+
 /* Text for an ha_status value. */
 const char* ha_strerror(int status);
 

@@ -58,6 +58,8 @@ _SIGNATURES = {
     "ha_block_attn": (c_int, [c_void_p] * 5 + [c_int32] * 5 + [c_void_p]),
     "ha_sampled_attn": (c_int, [c_void_p] * 7 + [c_int32] * 6 + [c_void_p]),
     "ha_merge_unpermute": (c_int, [c_void_p] * 7 + [c_int32] * 4 + [c_void_p]),
+    "ha_measure_mfma_rate": (c_int, [c_void_p, c_size_t, c_int32, POINTER(c_float), c_void_p]),
+    "ha_measure_hbm_rate": (c_int, [c_void_p, c_size_t, POINTER(c_float), POINTER(c_float), c_void_p]),
     "ha_strerror": (c_char_p, [c_int]),
 }
 
@@ -320,3 +322,19 @@ def ha_merge_unpermute(o_b, lse_b, o_r, lse_r, perm_q, dtype, stream=None):
                                     _dev(perm_q, "perm_q"), out.data_ptr(), lse.data_ptr(), groups, n, d,
                                     _dtype_code(out), _stream(stream)), "ha_merge_unpermute")
     return out, lse
+
+
+def ha_measure_mfma_rate(buf, iters=2000, stream=None) -> float:
+    """bf16 matrix-core TFLOP/s of register-resident MFMA chains; buf: device tensor >= 512 KiB."""
+    val = c_float(0.0)
+    _check(lib().ha_measure_mfma_rate(_dev(buf, "buf"), buf.numel() * buf.element_size(), int(iters),
+                                      ctypes.byref(val), _stream(stream)), "ha_measure_mfma_rate")
+    return float(val.value)
+
+
+def ha_measure_hbm_rate(buf, stream=None):
+    """(read GB/s, copy GB/s) of streaming kernels over buf, a device tensor well beyond the caches."""
+    rd, cp = c_float(0.0), c_float(0.0)
+    _check(lib().ha_measure_hbm_rate(_dev(buf, "buf"), buf.numel() * buf.element_size(), ctypes.byref(rd),
+                                     ctypes.byref(cp), _stream(stream)), "ha_measure_hbm_rate")
+    return float(rd.value), float(cp.value)

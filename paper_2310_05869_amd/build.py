@@ -18,7 +18,8 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libhyperattn.so")
 
-SOURCES = ["api.hip", "lsh_hash.hip", "lsh_hash_mfma.hip", "seg_sort.hip", "stage_kernels.hip", "attn_mfma.hip", "attn_generic.hip"]
+SOURCES = ["api.hip", "lsh_hash.hip", "lsh_hash_mfma.hip", "seg_sort.hip", "stage_kernels.hip", "attn_mfma.hip", "attn_generic.hip",
+           "calib.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

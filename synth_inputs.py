@@ -93,6 +93,15 @@ CONFIGS = {
 }
 
 
+# The single-layer sweep shape of the paper's speed-up curves (Section 4.2): 12 heads
+# of dimension 64, b = m = 256, sequence lengths 4k .. 131k, with and without the causal mask.
+SWEEP_LENGTHS = (4096, 8192, 16384, 32768, 65536, 131072)
+for _n in SWEEP_LENGTHS:
+    for _c in (0, 1):
+        CONFIGS[f"sweep_h12_d64_n{_n}" + ("_causal" if _c else "")] = dict(
+            B=1, H=12, n=_n, d=64, dtype="bf16", law="iid", b=256, m=256, r=7, causal=_c, n_min=4096, seed=0)
+
+
 def make_qkv(cfg: dict, seed=DATA_SEED, B=None, H=None, n=None):
     """Inputs for a CONFIGS entry (optionally with B, H or n overridden)."""
     B = cfg["B"] if B is None else B
