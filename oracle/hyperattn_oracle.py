@@ -326,3 +326,137 @@ def hyperattn_forward(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0,
         stages["codes"] = all_codes
         stages["proj"] = all_proj
     return out, lse
+
+
+# --------------------------------------------------------------------------
+# Backward pass: the vector-Jacobian product of the forward map above, with the
+# random draws (hyperplanes, index sets) and hence the permutations held fixed
+# (they are piecewise constant in Q and K).  The paper times forward + backward
+# (Section 4.2) and obtains the backward by differentiating its forward; this is
+# that derivative written out part by part, in the forward's own structure.
+# Every part is "O = A V / den, L = log den" for some non-negative A = w . exp(S);
+# with cotangents (dO, dL):  P = A / den,  dV = P^T dO,
+#   dS = P . (dO V^T - <dO, O>) + P dL,  dQ = dS K,  dK = dS^T Q.
+# --------------------------------------------------------------------------
+def _softmax_part_backward(Qs, Ks, Vs, S_mask, O, L, dO, dL):
+    """Cotangents of one part.  Qs [a,d], Ks, Vs [c,*]; S_mask [a,c] boolean
+    (True = entry present); O, L the part's outputs (L without additive
+    constants matters only through P, which is recomputed here); returns
+    (dQs, dKs, dVs)."""
+    S = Qs @ Ks.T
+    S = np.where(S_mask, S, -np.inf)
+    mx = S.max(axis=1, keepdims=True)
+    live = np.isfinite(mx[:, 0])
+    mx = np.where(np.isfinite(mx), mx, 0.0)
+    A = np.exp(S - mx)
+    den = A.sum(axis=1, keepdims=True)
+    P = np.where(live[:, None], A / np.where(den > 0, den, 1.0), 0.0)
+    dP = dO @ Vs.T
+    delta = (dO * O).sum(axis=1, keepdims=True)
+    dLc = np.where(live, dL, 0.0)[:, None]
+    dS = P * (dP - delta + dLc)
+    return dS @ Ks, dS.T @ Qs, P.T @ dO
+
+
+def _merge_backward(O1, L1, O2, L2, O, L, dO, dL):
+    """Cotangents of merge_parts: returns (dO1, dL1, dO2, dL2)."""
+    with np.errstate(invalid="ignore"):
+        w1 = np.where(np.isfinite(L1), np.exp(L1 - L), 0.0)
+        w2 = np.where(np.isfinite(L2), np.exp(L2 - L), 0.0)
+    g = (dO * O).sum(axis=1)
+    dL1 = w1 * (dL + (dO * O1).sum(axis=1) - g)
+    dL2 = w2 * (dL + (dO * O2).sum(axis=1) - g)
+    return w1[:, None] * dO, dL1, w2[:, None] * dO, dL2
+
+
+def node_backward(Qn, Kn, Vn, codes_q, codes_k, b, samples, dO, dL):
+    """Backward of node_forward; returns (dQn, dKn, dVn)."""
+    s = Qn.shape[0]
+    parts = {}
+    O, L = node_forward(Qn, Kn, Vn, codes_q, codes_k, b, samples, parts)
+    dO_b, dL_b, dO_r, dL_r = _merge_backward(parts["O_b"], parts["L_b"], parts["O_r"], parts["L_r"], O, L, dO, dL)
+    dQ = np.zeros_like(Qn)
+    dK = np.zeros_like(Kn)
+    dV = np.zeros_like(Vn)
+    perm_q, perm_k, pos_q, pos_k = parts["perm_q"], parts["perm_k"], parts["pos_q"], parts["pos_k"]
+    for t in range(s // b):                       # masked part, block by block
+        I = perm_q[t * b:(t + 1) * b]
+        J = perm_k[t * b:(t + 1) * b]
+        full = np.ones((len(I), len(J)), dtype=bool)
+        gq, gk, gv = _softmax_part_backward(Qn[I], Kn[J], Vn[J], full, parts["O_b"][I], parts["L_b"][I], dO_b[I], dL_b[I])
+        dQ[I] += gq
+        dK[J] += gk
+        dV[J] += gv
+    samples = np.asarray(samples, dtype=np.int64)
+    if len(samples) > 0:                          # estimate: the same index set for every row
+        keep = (pos_q[:, None] // b) != (pos_k[samples][None, :] // b)
+        gq, gk, gv = _softmax_part_backward(Qn, Kn[samples], Vn[samples], keep, parts["O_r"], parts["L_r"], dO_r, dL_r)
+        dQ += gq
+        np.add.at(dK, samples, gk)                # an index may be drawn more than once
+        np.add.at(dV, samples, gv)
+    return dQ, dK, dV
+
+
+def causal_backward(Q, K, V, codes_q, codes_k, b, n_min, sample_fn, dO, dL, level=0, node=0):
+    """Backward of causal_forward; returns (dQ, dK, dV)."""
+    n = Q.shape[0]
+    if n <= n_min:
+        O, L = exact_attention(Q, K, V, causal=True)
+        i = np.arange(n)[:, None]
+        j = np.arange(n)[None, :]
+        return _softmax_part_backward(Q, K, V, i >= j, O, L, dO, dL)
+    h = n // 2
+    O22, L22 = causal_forward(Q[h:], K[h:], V[h:], codes_q[h:], codes_k[h:], b, n_min, sample_fn, level + 1, 2 * node + 1)
+    samples = sample_fn(level, node, h)
+    O21, L21 = node_forward(Q[h:], K[:h], V[:h], codes_q[h:], codes_k[:h], b, samples)
+    O2, L2 = merge_parts(O21, L21, O22, L22)
+    dO21, dL21, dO22, dL22 = _merge_backward(O21, L21, O22, L22, O2, L2, dO[h:], dL[h:])
+    dQ = np.zeros_like(Q)
+    dK = np.zeros_like(K)
+    dV = np.zeros_like(V)
+    g = causal_backward(Q[:h], K[:h], V[:h], codes_q[:h], codes_k[:h], b, n_min, sample_fn, dO[:h], dL[:h], level + 1, 2 * node)
+    dQ[:h] += g[0]
+    dK[:h] += g[1]
+    dV[:h] += g[2]
+    g = causal_backward(Q[h:], K[h:], V[h:], codes_q[h:], codes_k[h:], b, n_min, sample_fn, dO22, dL22, level + 1, 2 * node + 1)
+    dQ[h:] += g[0]
+    dK[h:] += g[1]
+    dV[h:] += g[2]
+    g = node_backward(Q[h:], K[:h], V[:h], codes_q[h:], codes_k[:h], b, samples, dO21, dL21)
+    dQ[h:] += g[0]
+    dK[:h] += g[1]
+    dV[:h] += g[2]
+    return dQ, dK, dV
+
+
+def hyperattn_backward(Q, K, V, dO, b, m, r, causal=False, n_min=4096, seed=0, R=None, sample_fn=None, flip=None):
+    """Gradients (dQ, dK, dV) of sum(out * dO) for out = hyperattn_forward(Q, K, V, ...)[0],
+    all [B, H, n, d] in fp64; arguments as in hyperattn_forward."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    dO = np.asarray(dO, dtype=np.float64)
+    B, H, n, d = Q.shape
+    if R is None:
+        R = make_projection(seed, d, r)
+    if sample_fn is None:
+        def sample_fn(level, node, n_keys):
+            return make_samples(seed, level, node, n_keys, m)
+    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
+    for bh in range(B * H):
+        q, k, v, g = (x.reshape(B * H, n, -1)[bh] for x in (Q, K, V, dO))
+        bits = [lsh_bits(lsh_project(q, R)), lsh_bits(lsh_project(k, R))]
+        if flip:
+            for (t, fbh, row, kk) in flip:
+                if fbh == bh:
+                    bits[t][row, kk] = ~bits[t][row, kk]
+        cq, ck = (codes_from_bits(bits[t], r) for t in range(2))
+        zero = np.zeros(n)
+        if causal:
+            gq, gk, gv = causal_backward(q, k, v, cq, ck, b, n_min, sample_fn, g, zero)
+        else:
+            gq, gk, gv = node_backward(q, k, v, cq, ck, b, sample_fn(0, 0, n), g, zero)
+        dQ.reshape(B * H, n, -1)[bh] = gq
+        dK.reshape(B * H, n, -1)[bh] = gk
+        dV.reshape(B * H, n, -1)[bh] = gv
+    return dQ, dK, dV
