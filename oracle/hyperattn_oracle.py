@@ -32,13 +32,18 @@ algorithm's steps in the paper's order and notation:
   causal_forward       Algorithm 4 with the outputs combined by the same
                        row-sum weights (D_21 + D_C22)
   hyperattn_forward    Algorithm 3 in its Section 4 form over [B, H, n, d]
+  hyperattn_backward   the forward's vector-Jacobian product (Section 4.2 times
+                       forward + backward), random draws held fixed, written
+                       out part by part in the forward's structure
 
 Pins (tests/test_oracle_pins.py): brute-force equivalence in the degenerate
 cases (one block and no samples; causal base case; every key sampled exactly
 once), the closed-form collision and adjacent-bucket probabilities of
 Definition 1, unbiasedness of the estimator, row-stochasticity (V = 1 gives
 out = 1), permutation/stability invariants of the sort, and additivity of the
-causal row sums.  At the full benchmark configurations the randomised output
+causal row sums; for the backward pass central finite differences of the
+forward, the dense softmax-attention gradient where the method is exact, and
+the identities row-stochasticity implies.  At the full benchmark configurations the randomised output
 itself has no independent pin beyond these (no worked example is printed in
 the paper): there the oracle is trusted as the same code that passed them.
 """

@@ -327,3 +327,79 @@ def test_approximation_error_shrinks_with_more_samples():
             e += np.linalg.norm(out[0, 0] - ref) / np.linalg.norm(ref)
         errs.append(e / 4)
     assert errs[1] < 0.6 * errs[0]
+
+
+# --------------------------------------------------------------------------
+# Backward pass of the oracle: pinned to central finite differences of the
+# forward oracle (a different code path: no derivative formula is involved), to
+# the dense textbook gradient of softmax attention where the method is exact,
+# and to what row-stochasticity fixes.
+# --------------------------------------------------------------------------
+def _central_difference(f, X, idx, eps=1e-6):
+    Xp, Xm = X.copy(), X.copy()
+    Xp[idx] += eps
+    Xm[idx] -= eps
+    return (f(Xp) - f(Xm)) / (2 * eps)
+
+
+@pytest.mark.parametrize("causal,n,n_min", [(False, 64, 16), (True, 64, 16), (True, 96, 24)])
+def test_backward_matches_finite_differences_of_forward(causal, n, n_min):
+    rng = np.random.default_rng(11 + n)
+    d, b, m = 8, 8, 6
+    Q, K, V, G = (rng.standard_normal((1, 2, n, d)) * 0.7 for _ in range(4))
+    kw = dict(b=b, m=m, r=3, causal=causal, n_min=n_min, seed=5)
+    dQ, dK, dV = orc.hyperattn_backward(Q, K, V, G, **kw)
+    loss = lambda q, k, v: float((orc.hyperattn_forward(q, k, v, **kw)[0] * G).sum())
+    for name, X, dX in (("Q", Q, dQ), ("K", K, dK), ("V", V, dV)):
+        for _ in range(16):
+            idx = tuple(int(rng.integers(0, s)) for s in X.shape)
+            f = {"Q": lambda x: loss(x, K, V), "K": lambda x: loss(Q, x, V), "V": lambda x: loss(Q, K, x)}[name]
+            num = _central_difference(f, X, idx)
+            assert abs(num - dX[idx]) <= 1e-6 * (1.0 + abs(num)), (name, idx, num, dX[idx])
+
+
+def _dense_attention_gradients(Q, K, V, G, causal):
+    """Softmax-attention gradients from the dense matrices (textbook form)."""
+    S = Q @ K.T
+    if causal:
+        S = np.where(np.tril(np.ones_like(S, dtype=bool)), S, -np.inf)
+    P = np.exp(S - S.max(axis=1, keepdims=True))
+    P /= P.sum(axis=1, keepdims=True)
+    dP = G @ V.T
+    dS = P * (dP - (P * dP).sum(axis=1, keepdims=True))
+    return dS @ K, dS.T @ Q, P.T @ G
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_backward_with_identity_sampling_is_exact_attention_gradient(causal):
+    """Every key of every node sampled exactly once and one block per node... the
+    forward is then exact attention, so its gradient must be the dense one."""
+    rng = np.random.default_rng(3)
+    n, d = 64, 8
+    Q, K, V, G = (rng.standard_normal((1, 1, n, d)) * 0.6 for _ in range(4))
+    ident = lambda level, node, n_keys: np.arange(n_keys)
+    if causal:
+        got = orc.hyperattn_backward(Q, K, V, G, b=8, m=0, r=3, causal=True, n_min=16, sample_fn=ident)
+    else:
+        got = orc.hyperattn_backward(Q, K, V, G, b=8, m=n, r=3, causal=False, sample_fn=ident)
+    ref = _dense_attention_gradients(Q[0, 0], K[0, 0], V[0, 0], G[0, 0], causal)
+    for g, r_ in zip(got, ref):
+        np.testing.assert_allclose(g[0, 0], r_, rtol=1e-9, atol=1e-11)
+
+
+def test_backward_invariants_from_row_stochasticity():
+    rng = np.random.default_rng(8)
+    n, d = 128, 8
+    Q, K, V, G = (rng.standard_normal((1, 2, n, d)) for _ in range(4))
+    kw = dict(b=16, m=12, r=4, causal=True, n_min=32, seed=2)
+    dQ, dK, dV = orc.hyperattn_backward(Q, K, V, G, **kw)
+    # the weights of every output row sum to one: the columns of dV add up to those of dO
+    np.testing.assert_allclose(dV.sum(axis=2), G.sum(axis=2), rtol=1e-10, atol=1e-10)
+    # identical value rows make the output constant in Q and K
+    Vc = np.broadcast_to(V[:, :, :1], V.shape).copy()
+    dQc, dKc, _ = orc.hyperattn_backward(Q, K, Vc, G, **kw)
+    assert np.abs(dQc).max() < 1e-12 and np.abs(dKc).max() < 1e-12
+    # linear in the cotangent
+    dQ2, dK2, dV2 = orc.hyperattn_backward(Q, K, V, -2.0 * G, **kw)
+    np.testing.assert_allclose(dQ2, -2.0 * dQ, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(dK2, -2.0 * dK, rtol=1e-12, atol=1e-12)
