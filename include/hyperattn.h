@@ -194,6 +194,60 @@ int ha_merge_unpermute(const float* o_b, const float* lse_b, const float* o_r, c
                        const int32_t* perm_q, void* out, float* lse, int32_t groups, int32_t n,
                        int32_t d, int32_t dtype, void* stream);
 
+/* ------------------------------------------------------------------------
+ * Backward pass (Section 4.2 times forward + backward; the backward is the
+ * derivative of the forward above with the random draws, and so the
+ * permutations, held fixed).  bf16 tensors only (HA_ERR_DTYPE otherwise).
+ *
+ * Because every output row is one softmax over the union of its parts (block
+ * keys, kept samples weighted s/m, base-case keys; Algorithms 1, 2, 4), with
+ * L = lse and delta_i = <d_out_i, out_i>:
+ *   P_ij = w_ij exp(<q_i,k_j> - L_i),  dV_j = sum_i P_ij d_out_i,
+ *   dS_ij = P_ij (<d_out_i, v_j> - delta_i),  dQ_i = sum_j dS_ij k_j,  dK_j = sum_i dS_ij q_i.
+ *
+ * hyperattn_backward: Q, K, V, out, d_out, dQ, dK, dV are device pointers to
+ * contiguous [B][H][n][d] bf16; lse device fp32 [B][H][n].  out and lse are the
+ * results of hyperattn_forward on the same Q, K, V, shape and params, and
+ * fwd_workspace is that call's workspace, unmodified since (it holds the sort
+ * permutations and sample indices; only read here).  bwd_workspace: device,
+ * 256-byte aligned, >= ha_backward_workspace_bytes(); overwritten.  All
+ * caller-owned; nothing is allocated; kernels are enqueued on `stream` and the
+ * call returns without waiting.  Sums over parts are taken in a fixed order:
+ * same inputs give bit-identical gradients.
+ * Errors: HA_ERR_NULL, HA_ERR_DTYPE, HA_ERR_SHAPE (as hyperattn_forward; more
+ * than 24 recursion levels), HA_ERR_WORKSPACE, HA_ERR_LAUNCH.
+ *
+ * hyperattn_backward_timed: the same, and WAITS for the stream; stage_ms_host
+ * (host, 8 floats) receives the times between events on the stream: delta, dQ
+ * of the nodes, dQ of the base case, dK/dV of the block keys, dK/dV of the
+ * sampled keys with their reduction, dK/dV of the base case, final sums, total.
+ *
+ * exact_attn_backward: gradients of exact_attn_forward (Section 1.1; causal:
+ * Section 3.1), the denominator of the forward + backward speed-up.  workspace
+ * >= exact_attn_backward_workspace_bytes(shape). */
+typedef struct {
+  size_t delta;                      /* fp32 [B*H][n] */
+  size_t dq_base, dk_base, dv_base;  /* fp32 [B*H][n][d], causal only */
+  size_t dq_part, dk_part, dv_part;  /* fp32 [levels][B*H][n_cov][d] */
+  size_t samp_k, samp_v;             /* fp32 rows of the sampled keys per (level, head, node, query chunk, sample) */
+  size_t total_bytes;
+} ha_bwd_ws_layout;
+
+int ha_backward_workspace_layout(const ha_shape* shape, const ha_params* params, ha_bwd_ws_layout* layout);
+size_t ha_backward_workspace_bytes(const ha_shape* shape, const ha_params* params);
+int hyperattn_backward(const void* Q, const void* K, const void* V, const void* out, const float* lse,
+                       const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape,
+                       const ha_params* params, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                       void* bwd_workspace, size_t bwd_workspace_bytes, void* stream);
+int hyperattn_backward_timed(const void* Q, const void* K, const void* V, const void* out, const float* lse,
+                             const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape,
+                             const ha_params* params, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                             void* bwd_workspace, size_t bwd_workspace_bytes, void* stream, float* stage_ms_host);
+int exact_attn_backward(const void* Q, const void* K, const void* V, const void* out, const float* lse,
+                        const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape, int causal,
+                        void* workspace, size_t workspace_bytes, void* stream);
+size_t exact_attn_backward_workspace_bytes(const ha_shape* shape);
+
 /* Measurement aids (no passage of the paper: they serve the roofline report).
  * Both run on `stream`, time themselves with events and WAIT for the stream;
  * `buf` is caller-owned device memory that they overwrite.

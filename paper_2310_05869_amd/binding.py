@@ -35,6 +35,11 @@ class HaWsLayout(ctypes.Structure):
                 ("part_l", c_size_t), ("total_bytes", c_size_t)]
 
 
+class HaBwdWsLayout(ctypes.Structure):
+    _fields_ = [(k, c_size_t) for k in ("delta", "dq_base", "dk_base", "dv_base", "dq_part", "dk_part", "dv_part",
+                                        "samp_k", "samp_v", "total_bytes")]
+
+
 class HyperAttnError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -58,6 +63,14 @@ _SIGNATURES = {
     "ha_block_attn": (c_int, [c_void_p] * 5 + [c_int32] * 5 + [c_void_p]),
     "ha_sampled_attn": (c_int, [c_void_p] * 7 + [c_int32] * 6 + [c_void_p]),
     "ha_merge_unpermute": (c_int, [c_void_p] * 7 + [c_int32] * 4 + [c_void_p]),
+    "ha_backward_workspace_layout": (c_int, [POINTER(HaShape), POINTER(HaParams), POINTER(HaBwdWsLayout)]),
+    "ha_backward_workspace_bytes": (c_size_t, [POINTER(HaShape), POINTER(HaParams)]),
+    "hyperattn_backward": (c_int, [c_void_p] * 9 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_size_t, c_void_p,
+                                                   c_size_t, c_void_p]),
+    "hyperattn_backward_timed": (c_int, [c_void_p] * 9 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_size_t,
+                                                         c_void_p, c_size_t, c_void_p, POINTER(c_float)]),
+    "exact_attn_backward": (c_int, [c_void_p] * 9 + [POINTER(HaShape), c_int, c_void_p, c_size_t, c_void_p]),
+    "exact_attn_backward_workspace_bytes": (c_size_t, [POINTER(HaShape)]),
     "ha_measure_mfma_rate": (c_int, [c_void_p, c_size_t, c_int32, POINTER(c_float), c_void_p]),
     "ha_measure_hbm_rate": (c_int, [c_void_p, c_size_t, POINTER(c_float), POINTER(c_float), c_void_p]),
     "ha_strerror": (c_char_p, [c_int]),
@@ -338,3 +351,73 @@ def ha_measure_hbm_rate(buf, stream=None):
     _check(lib().ha_measure_hbm_rate(_dev(buf, "buf"), buf.numel() * buf.element_size(), ctypes.byref(rd),
                                      ctypes.byref(cp), _stream(stream)), "ha_measure_hbm_rate")
     return float(rd.value), float(cp.value)
+
+
+# ---------------------------------------------------------------- backward pass
+BWD_STAGE_NAMES = ("delta", "dq_nodes", "dq_base", "dkv_block", "dkv_sampled", "dkv_base", "sums", "total")
+
+
+def ha_backward_workspace_bytes(shape: HaShape, params: HaParams) -> int:
+    lay = HaBwdWsLayout()
+    _check(lib().ha_backward_workspace_layout(ctypes.byref(shape), ctypes.byref(params), ctypes.byref(lay)),
+           "ha_backward_workspace_layout")
+    return int(lay.total_bytes)
+
+
+def alloc_backward_workspace(shape: HaShape, params: HaParams, device="cuda"):
+    return _torch().empty(ha_backward_workspace_bytes(shape, params), dtype=_torch().uint8, device=device)
+
+
+def _backward_call(timed, Q, K, V, out, lse, d_out, b, m, r, causal, n_min, seed, fwd_workspace, bwd_workspace,
+                   grads, stream):
+    torch = _torch()
+    B, H, n, d = Q.shape
+    shape = make_shape(B, H, n, d, _dtype_code(Q))
+    params = make_params(b, m, r, causal, n_min, seed)
+    if bwd_workspace is None:
+        bwd_workspace = alloc_backward_workspace(shape, params, Q.device)
+    dQ, dK, dV = grads if grads is not None else (torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V))
+    args = [_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"), _dev(lse, "lse"), _dev(d_out, "d_out"),
+            _dev(dQ, "dQ"), _dev(dK, "dK"), _dev(dV, "dV"), ctypes.byref(shape), ctypes.byref(params),
+            fwd_workspace.data_ptr(), fwd_workspace.numel(), bwd_workspace.data_ptr(), bwd_workspace.numel(),
+            _stream(stream)]
+    if not timed:
+        _check(lib().hyperattn_backward(*args), "hyperattn_backward")
+        return dQ, dK, dV
+    ms = (c_float * 8)()
+    _check(lib().hyperattn_backward_timed(*args, ms), "hyperattn_backward_timed")
+    return dQ, dK, dV, dict(zip(BWD_STAGE_NAMES, [float(x) for x in ms]))
+
+
+def hyperattn_backward(Q, K, V, out, lse, d_out, b, m, r, causal=False, n_min=4096, seed=0, fwd_workspace=None,
+                       bwd_workspace=None, grads=None, stream=None):
+    """dQ, dK, dV of sum(out * d_out).  out, lse and fwd_workspace are what
+    hyperattn_forward produced / used for the same arguments (bf16 tensors)."""
+    if fwd_workspace is None:
+        raise ValueError("hyperattn_backward needs the workspace of the forward call")
+    return _backward_call(False, Q, K, V, out, lse, d_out, b, m, r, causal, n_min, seed, fwd_workspace, bwd_workspace,
+                          grads, stream)
+
+
+def hyperattn_backward_timed(Q, K, V, out, lse, d_out, b, m, r, causal=False, n_min=4096, seed=0, fwd_workspace=None,
+                             bwd_workspace=None, grads=None, stream=None):
+    """As hyperattn_backward, but waits and also returns per-stage milliseconds (BWD_STAGE_NAMES)."""
+    if fwd_workspace is None:
+        raise ValueError("hyperattn_backward_timed needs the workspace of the forward call")
+    return _backward_call(True, Q, K, V, out, lse, d_out, b, m, r, causal, n_min, seed, fwd_workspace, bwd_workspace,
+                          grads, stream)
+
+
+def exact_attn_backward(Q, K, V, out, lse, d_out, causal=False, workspace=None, grads=None, stream=None):
+    torch = _torch()
+    B, H, n, d = Q.shape
+    shape = make_shape(B, H, n, d, _dtype_code(Q))
+    if workspace is None:
+        workspace = torch.empty(int(lib().exact_attn_backward_workspace_bytes(ctypes.byref(shape))), dtype=torch.uint8,
+                                device=Q.device)
+    dQ, dK, dV = grads if grads is not None else (torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V))
+    _check(lib().exact_attn_backward(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"), _dev(lse, "lse"),
+                                     _dev(d_out, "d_out"), _dev(dQ, "dQ"), _dev(dK, "dK"), _dev(dV, "dV"),
+                                     ctypes.byref(shape), int(bool(causal)), workspace.data_ptr(), workspace.numel(),
+                                     _stream(stream)), "exact_attn_backward")
+    return dQ, dK, dV

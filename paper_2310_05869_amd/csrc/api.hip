@@ -17,6 +17,7 @@
 #include <cstring>
 
 #include "ha_common.h"
+#include "bwd_common.h"
 
 namespace ha {
 
@@ -242,6 +243,162 @@ static int stage_geometry(Geometry* g, int groups, int n, int d, int dtype, int 
   return HA_OK;
 }
 
+// ---------------------------------------------------------------------------
+// Backward pass
+// ---------------------------------------------------------------------------
+static int64_t bwd_sample_rows(const Geometry& g) {
+  int64_t rows = 0;
+  if (g.m <= 0) return 0;
+  for (int l = 0; l < g.levels; ++l) {
+    const int nodes = g.causal ? (1 << l) : 1;
+    rows += (int64_t)g.BH * nodes * bwd_chunks_per_node(g, l) * g.m;
+  }
+  return rows;
+}
+
+static void fill_bwd_layout(const Geometry& g, ha_bwd_ws_layout* l) {
+  std::memset(l, 0, sizeof(*l));
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off = align256(off + bytes);
+    return at;
+  };
+  const size_t rows = (size_t)g.BH * g.n;
+  const size_t cov = (size_t)g.levels * g.BH * g.n_cov;
+  const size_t rowb = (size_t)g.d * 4;
+  const bool base = g.causal != 0;
+  l->delta = take(rows * 4);
+  l->dq_base = take(base ? rows * rowb : 0);
+  l->dk_base = take(base ? rows * rowb : 0);
+  l->dv_base = take(base ? rows * rowb : 0);
+  l->dq_part = take(cov * rowb);
+  l->dk_part = take(cov * rowb);
+  l->dv_part = take(cov * rowb);
+  const size_t srows = (size_t)bwd_sample_rows(g);
+  l->samp_k = take(srows * rowb);
+  l->samp_v = take(srows * rowb);
+  l->total_bytes = off < 256 ? 256 : off;
+}
+
+// ev, when non-null, receives 9 events: start, after delta, dQ of the nodes, dQ of the base case,
+// dK/dV of the block keys, of the sampled keys (with their reduction), of the base case, after the final sums.
+static int backward_impl(const void* Q, const void* K, const void* V, const void* out, const float* lse,
+                         const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* sh, const ha_params* p,
+                         const void* fws, size_t fws_bytes, void* bws, size_t bws_bytes, void* stream,
+                         hipEvent_t* ev = nullptr) {
+  Geometry g;
+  int rc = make_geometry(sh, p, &g);
+  if (rc != HA_OK) return rc;
+  if (g.dtype != HA_BF16) return HA_ERR_DTYPE;
+  if (g.levels > kBwdMaxLevels) return HA_ERR_SHAPE;
+  if (g.BH == 0 || g.n == 0) return HA_OK;
+  if (!Q || !K || !V || !out || !lse || !d_out || !dQ || !dK || !dV || !fws || !bws) return HA_ERR_NULL;
+  ha_ws_layout lay;
+  fill_layout(g, &lay);
+  ha_bwd_ws_layout bl;
+  fill_bwd_layout(g, &bl);
+  if (fws_bytes < lay.total_bytes || ((uintptr_t)fws & 255) != 0) return HA_ERR_WORKSPACE;
+  if (bws_bytes < bl.total_bytes || ((uintptr_t)bws & 255) != 0) return HA_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const unsigned char* fb = (const unsigned char*)fws;
+  unsigned char* bb = (unsigned char*)bws;
+  float* delta = (float*)(bb + bl.delta);
+  float* dq_base = (float*)(bb + bl.dq_base);
+  float* dk_base = (float*)(bb + bl.dk_base);
+  float* dv_base = (float*)(bb + bl.dv_base);
+  float* dq_part = (float*)(bb + bl.dq_part);
+  float* dk_part = (float*)(bb + bl.dk_part);
+  float* dv_part = (float*)(bb + bl.dv_part);
+  float* samp_k = (float*)(bb + bl.samp_k);
+  float* samp_v = (float*)(bb + bl.samp_v);
+  auto mark = [&](int i) {
+    if (ev) (void)hipEventRecord(ev[i], st);
+  };
+
+  BwdArgs a{};
+  a.f.Q = Q;
+  a.f.K = K;
+  a.f.V = V;
+  a.f.q_bh_stride = a.f.k_bh_stride = a.f.out_bh_stride = (int64_t)g.n * g.d;
+  a.f.perm_q = (const int32_t*)(fb + lay.perm_q);
+  a.f.perm_k = (const int32_t*)(fb + lay.perm_k);
+  a.f.pos_k = (const int32_t*)(fb + lay.pos_k);
+  a.f.samples = g.m > 0 ? (const int32_t*)(fb + lay.samples) : nullptr;
+  a.f.samp_blk = g.m > 0 ? (const int32_t*)(fb + lay.samp_blk) : nullptr;
+  a.f.use_block = 1;
+  a.f.g = g;
+  a.f.exact_rows_q = a.f.exact_rows_k = g.n;
+  a.f.exact_block = g.causal ? g.base_len : g.n;
+  a.f.exact_causal = g.causal;
+  a.dO = d_out;
+  a.lse = lse;
+  a.delta = delta;
+  {
+    int wg = 0;
+    int64_t row = 0;
+    const int spn = (g.m + 127) / 128;
+    for (int l = 0; l < g.levels; ++l) {
+      const int nodes = g.causal ? (1 << l) : 1;
+      const int cpn = bwd_chunks_per_node(g, l);
+      a.samp_wg_off[l] = wg;
+      a.samp_row_off[l] = row;
+      wg += g.BH * nodes * cpn * spn;
+      row += (int64_t)g.BH * nodes * cpn * g.m;
+    }
+    a.samp_wg_off[g.levels] = wg;
+  }
+
+  mark(0);
+  rc = launch_bwd_delta(out, d_out, delta, (int64_t)g.BH * g.n, g.d, st);
+  if (rc != HA_OK) return rc;
+  mark(1);
+  if (g.levels > 0) {
+    a.out1 = dq_part;
+    a.out2 = nullptr;
+    rc = launch_attn_bwd_mfma(a, kBwdDqNode, st);
+    if (rc != HA_OK) return rc;
+  }
+  mark(2);
+  if (g.causal) {
+    a.out1 = dq_base;
+    rc = launch_attn_bwd_mfma(a, kBwdDqExact, st);
+    if (rc != HA_OK) return rc;
+  }
+  mark(3);
+  if (g.levels > 0) {
+    a.out1 = dk_part;
+    a.out2 = dv_part;
+    rc = launch_attn_bwd_mfma(a, kBwdDkvBlock, st);
+    if (rc != HA_OK) return rc;
+  }
+  mark(4);
+  if (g.levels > 0 && g.m > 0) {
+    a.out1 = samp_k;
+    a.out2 = samp_v;
+    rc = launch_attn_bwd_mfma(a, kBwdDkvSamp, st);
+    if (rc != HA_OK) return rc;
+    rc = launch_bwd_sample_scatter(a, samp_k, samp_v, dk_part, dv_part, st);
+    if (rc != HA_OK) return rc;
+  }
+  mark(5);
+  if (g.causal) {
+    a.out1 = dk_base;
+    a.out2 = dv_base;
+    rc = launch_attn_bwd_mfma(a, kBwdDkvExact, st);
+    if (rc != HA_OK) return rc;
+  }
+  mark(6);
+  rc = launch_bwd_combine(g.causal ? dq_base : nullptr, dq_part, dQ, g, 1, st);
+  if (rc != HA_OK) return rc;
+  rc = launch_bwd_combine(g.causal ? dk_base : nullptr, dk_part, dK, g, 0, st);
+  if (rc != HA_OK) return rc;
+  rc = launch_bwd_combine(g.causal ? dv_base : nullptr, dv_part, dV, g, 0, st);
+  if (rc != HA_OK) return rc;
+  mark(7);
+  return HA_OK;
+}
+
 }  // namespace ha
 
 using namespace ha;
@@ -418,6 +575,118 @@ int ha_merge_unpermute(const float* o_b, const float* lse_b, const float* o_r, c
   if (!o_b || !lse_b || !o_r || !lse_r || !perm_q || !out || !lse) return HA_ERR_NULL;
   return launch_merge_unpermute(o_b, lse_b, o_r, lse_r, perm_q, out, lse, groups, n, d, dtype,
                                 (hipStream_t)stream);
+}
+
+int ha_backward_workspace_layout(const ha_shape* shape, const ha_params* params, ha_bwd_ws_layout* layout) {
+  if (!layout) return HA_ERR_NULL;
+  Geometry g;
+  const int rc = make_geometry(shape, params, &g);
+  if (rc != HA_OK) return rc;
+  if (g.dtype != HA_BF16) return HA_ERR_DTYPE;
+  fill_bwd_layout(g, layout);
+  return HA_OK;
+}
+
+size_t ha_backward_workspace_bytes(const ha_shape* shape, const ha_params* params) {
+  ha_bwd_ws_layout l;
+  return ha_backward_workspace_layout(shape, params, &l) == HA_OK ? l.total_bytes : 0;
+}
+
+int hyperattn_backward(const void* Q, const void* K, const void* V, const void* out, const float* lse,
+                       const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape,
+                       const ha_params* params, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                       void* bwd_workspace, size_t bwd_workspace_bytes, void* stream) {
+  return backward_impl(Q, K, V, out, lse, d_out, dQ, dK, dV, shape, params, fwd_workspace, fwd_workspace_bytes,
+                       bwd_workspace, bwd_workspace_bytes, stream);
+}
+
+int hyperattn_backward_timed(const void* Q, const void* K, const void* V, const void* out, const float* lse,
+                             const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape,
+                             const ha_params* params, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                             void* bwd_workspace, size_t bwd_workspace_bytes, void* stream, float* stage_ms_host) {
+  if (!stage_ms_host) return HA_ERR_NULL;
+  constexpr int NE = 8;
+  hipEvent_t ev[NE];
+  for (int i = 0; i < NE; ++i)
+    if (hipEventCreate(&ev[i]) != hipSuccess) {
+      for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
+      return HA_ERR_LAUNCH;
+    }
+  int rc = backward_impl(Q, K, V, out, lse, d_out, dQ, dK, dV, shape, params, fwd_workspace, fwd_workspace_bytes,
+                         bwd_workspace, bwd_workspace_bytes, stream, ev);
+  for (int i = 0; i < NE; ++i) stage_ms_host[i] = 0.f;
+  Geometry g;
+  const bool ran = rc == HA_OK && make_geometry(shape, params, &g) == HA_OK && g.BH > 0 && g.n > 0;
+  if (ran) {
+    if (hipEventSynchronize(ev[NE - 1]) != hipSuccess) rc = HA_ERR_LAUNCH;
+    for (int i = 0; i < NE - 1 && rc == HA_OK; ++i)
+      if (hipEventElapsedTime(&stage_ms_host[i], ev[i], ev[i + 1]) != hipSuccess) rc = HA_ERR_LAUNCH;
+    if (rc == HA_OK && hipEventElapsedTime(&stage_ms_host[NE - 1], ev[0], ev[NE - 1]) != hipSuccess) rc = HA_ERR_LAUNCH;
+  }
+  for (int i = 0; i < NE; ++i) (void)hipEventDestroy(ev[i]);
+  return rc;
+}
+
+int exact_attn_backward(const void* Q, const void* K, const void* V, const void* out, const float* lse,
+                        const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* sh, int causal,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  if (!sh) return HA_ERR_NULL;
+  // exact attention is the causal recursion that never splits (n_min = n), or its unmasked twin
+  ha_params p;
+  std::memset(&p, 0, sizeof(p));
+  p.b = 1;
+  p.m = 0;
+  p.r = 1;
+  p.causal = 1;
+  p.n_min = sh->n > 0 ? sh->n : 1;
+  Geometry g;
+  int rc = make_geometry(sh, &p, &g);
+  if (rc != HA_OK) return rc;
+  if (g.dtype != HA_BF16) return HA_ERR_DTYPE;
+  if (g.BH == 0 || g.n == 0) return HA_OK;
+  if (!Q || !K || !V || !out || !lse || !d_out || !dQ || !dK || !dV || !workspace) return HA_ERR_NULL;
+  ha_bwd_ws_layout bl;
+  fill_bwd_layout(g, &bl);
+  if (workspace_bytes < bl.total_bytes || ((uintptr_t)workspace & 255) != 0) return HA_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  unsigned char* bb = (unsigned char*)workspace;
+  BwdArgs a{};
+  a.f.Q = Q;
+  a.f.K = K;
+  a.f.V = V;
+  a.f.q_bh_stride = a.f.k_bh_stride = a.f.out_bh_stride = (int64_t)g.n * g.d;
+  a.f.g = g;
+  a.f.exact_rows_q = a.f.exact_rows_k = g.n;
+  a.f.exact_block = g.n;
+  a.f.exact_causal = causal ? 1 : 0;
+  a.dO = d_out;
+  a.lse = lse;
+  a.delta = (float*)(bb + bl.delta);
+  rc = launch_bwd_delta(out, d_out, (float*)(bb + bl.delta), (int64_t)g.BH * g.n, g.d, st);
+  if (rc != HA_OK) return rc;
+  a.out1 = (float*)(bb + bl.dq_base);
+  rc = launch_attn_bwd_mfma(a, kBwdDqExact, st);
+  if (rc != HA_OK) return rc;
+  a.out1 = (float*)(bb + bl.dk_base);
+  a.out2 = (float*)(bb + bl.dv_base);
+  rc = launch_attn_bwd_mfma(a, kBwdDkvExact, st);
+  if (rc != HA_OK) return rc;
+  rc = launch_bwd_combine((float*)(bb + bl.dq_base), nullptr, dQ, g, 1, st);
+  if (rc != HA_OK) return rc;
+  rc = launch_bwd_combine((float*)(bb + bl.dk_base), nullptr, dK, g, 0, st);
+  if (rc != HA_OK) return rc;
+  return launch_bwd_combine((float*)(bb + bl.dv_base), nullptr, dV, g, 0, st);
+}
+
+size_t exact_attn_backward_workspace_bytes(const ha_shape* sh) {
+  if (!sh) return 0;
+  ha_params p;
+  std::memset(&p, 0, sizeof(p));
+  p.b = 1;
+  p.r = 1;
+  p.causal = 1;
+  p.n_min = sh->n > 0 ? sh->n : 1;
+  return ha_backward_workspace_bytes(sh, &p);
 }
 
 const char* ha_strerror(int status) {

@@ -1,0 +1,142 @@
+// Small kernels around the MFMA backward pass: delta_i = <dO_i, O_i>, the
+// ordered reduction of the sampled keys' gradients into the per-level key
+// buffers, and the final sums over the parts of Algorithm 4 (base case plus
+// every level whose node holds the row), written in the tensors' dtype.
+// Every sum is taken in a fixed order: results are bit-reproducible.
+#include "attn_common.h"
+#include "bwd_common.h"
+
+namespace ha {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// One group of D/8 lanes per row; 16 bytes (8 bf16) per lane.
+template <int D>
+__global__ __launch_bounds__(256) void bwd_delta_kernel(const uint16_t* __restrict__ O, const uint16_t* __restrict__ G,
+                                                        float* __restrict__ delta, int64_t rows) {
+  constexpr int LPR = D / 8;  // lanes per row
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t row = t / LPR;
+  const int part = (int)(t % LPR);
+  float s = 0.f;
+  if (row < rows) {
+    const u32x4 o = *reinterpret_cast<const u32x4*>(O + row * D + part * 8);
+    const u32x4 g = *reinterpret_cast<const u32x4*>(G + row * D + part * 8);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      s = __builtin_fmaf(__uint_as_float(o[e] << 16), __uint_as_float(g[e] << 16), s);
+      s = __builtin_fmaf(__uint_as_float(o[e] & 0xFFFF0000u), __uint_as_float(g[e] & 0xFFFF0000u), s);
+    }
+  }
+#pragma unroll
+  for (int off = LPR / 2; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+  if (row < rows && part == 0) delta[row] = s;
+}
+
+int launch_bwd_delta(const void* O, const void* dO, float* delta, int64_t rows, int d, hipStream_t st) {
+  if (rows <= 0) return HA_OK;
+  const int lpr = d / 8;
+  const int64_t threads = rows * lpr;
+  const unsigned grid = (unsigned)((threads + 255) / 256);
+  if (d == 128)
+    hipLaunchKernelGGL((bwd_delta_kernel<128>), dim3(grid), dim3(256), 0, st, (const uint16_t*)O, (const uint16_t*)dO, delta, rows);
+  else if (d == 64)
+    hipLaunchKernelGGL((bwd_delta_kernel<64>), dim3(grid), dim3(256), 0, st, (const uint16_t*)O, (const uint16_t*)dO, delta, rows);
+  else
+    return HA_ERR_SHAPE;
+  return check_launch();
+}
+
+// One workgroup per (head, node); thread c owns column c of dK (threads < d) or
+// of dV (threads >= d).  For sample j = 0 .. m-1 in order: the partial sums of
+// the node's query chunks are added up (chunk order) and added to the key's row
+// in the level's buffer.  A key drawn twice receives both terms, one after the
+// other, from the same thread.
+__global__ __launch_bounds__(256) void bwd_sample_scatter_kernel(BwdArgs a, const float* __restrict__ samp_k,
+                                                                 const float* __restrict__ samp_v, float* part_k, float* part_v) {
+  const Geometry& g = a.f.g;
+  const int d = g.d;
+  const int bh = blockIdx.x / g.total_nodes;
+  const int heap = blockIdx.x % g.total_nodes;
+  int level = 0;
+  while ((2 << level) - 1 <= heap) ++level;
+  const int node = heap - ((1 << level) - 1);
+  const NodeRef nr = node_ref(g, level, node);
+  const int nodes = g.causal ? (1 << level) : 1;
+  const int cpn = bwd_chunks_per_node(g, level);
+  const int64_t seg_off = ((int64_t)level * g.BH + bh) * g.n_cov + (int64_t)node * nr.s;
+  const int c = threadIdx.x % d;
+  const float* src = (int)threadIdx.x < d ? samp_k : samp_v;
+  float* dst = (int)threadIdx.x < d ? part_k : part_v;
+  if ((int)threadIdx.x >= 2 * d) return;
+  const int64_t row0 = a.samp_row_off[level] + ((int64_t)bh * nodes + node) * cpn * g.m;
+  for (int j = 0; j < g.m; ++j) {
+    float s = 0.f;
+    for (int qc = 0; qc < cpn; ++qc) s += src[(row0 + (int64_t)qc * g.m + j) * d + c];
+    const int key = a.f.samples[(int64_t)heap * g.m + j];
+    dst[(seg_off + key) * d + c] += s;
+  }
+}
+
+int launch_bwd_sample_scatter(const BwdArgs& a, const float* samp_k, const float* samp_v, float* part_k,
+                              float* part_v, hipStream_t st) {
+  const Geometry& g = a.f.g;
+  if (g.m <= 0 || g.total_nodes <= 0) return HA_OK;
+  hipLaunchKernelGGL(bwd_sample_scatter_kernel, dim3((unsigned)(g.BH * g.total_nodes)), dim3(256), 0, st, a, samp_k,
+                     samp_v, part_k, part_v);
+  return check_launch();
+}
+
+// Row i of the result = base[i] (if any) + sum over levels l, in order, of the
+// level's row for i where i lies on the given side of its level-l node.
+template <int D>
+__global__ __launch_bounds__(256) void bwd_combine_kernel(const float* __restrict__ base, const float* __restrict__ part,
+                                                          uint16_t* __restrict__ dst, Geometry g, int query_side) {
+  constexpr int LPR = D / 8;
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t row = t / LPR;
+  const int piece = (int)(t % LPR);
+  if (row >= (int64_t)g.BH * g.n) return;
+  const int bh = (int)(row / g.n), i = (int)(row % g.n);
+  f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
+  if (base) {
+    v0 = *reinterpret_cast<const f32x4*>(base + row * D + piece * 8);
+    v1 = *reinterpret_cast<const f32x4*>(base + row * D + piece * 8 + 4);
+  }
+  for (int l = 0; l < g.levels; ++l) {
+    int64_t pr;
+    bool on;
+    if (g.causal) {
+      const int s = g.n >> (l + 1);
+      const bool second = ((i / s) & 1) != 0;
+      on = query_side ? second : !second;
+      pr = ((int64_t)l * g.BH + bh) * g.n_cov + (int64_t)(i / (2 * s)) * s + (i % s);
+    } else {
+      on = true;
+      pr = (int64_t)bh * g.n_cov + i;
+    }
+    if (!on) continue;
+    v0 += *reinterpret_cast<const f32x4*>(part + pr * D + piece * 8);
+    v1 += *reinterpret_cast<const f32x4*>(part + pr * D + piece * 8 + 4);
+  }
+  const u32x4 pk = {pack_bf16x2(v0.x, v0.y), pack_bf16x2(v0.z, v0.w), pack_bf16x2(v1.x, v1.y), pack_bf16x2(v1.z, v1.w)};
+  *reinterpret_cast<u32x4*>(dst + row * D + piece * 8) = pk;
+}
+
+int launch_bwd_combine(const float* base, const float* part, void* dst, const Geometry& g, int query_side,
+                       hipStream_t st) {
+  const int64_t rows = (int64_t)g.BH * g.n;
+  if (rows <= 0) return HA_OK;
+  const int lpr = g.d / 8;
+  const unsigned grid = (unsigned)((rows * lpr + 255) / 256);
+  if (g.d == 128)
+    hipLaunchKernelGGL((bwd_combine_kernel<128>), dim3(grid), dim3(256), 0, st, base, part, (uint16_t*)dst, g, query_side);
+  else if (g.d == 64)
+    hipLaunchKernelGGL((bwd_combine_kernel<64>), dim3(grid), dim3(256), 0, st, base, part, (uint16_t*)dst, g, query_side);
+  else
+    return HA_ERR_SHAPE;
+  return check_launch();
+}
+
+}  // namespace ha
