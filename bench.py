@@ -131,6 +131,101 @@ def sweep(args, torch, ha):
         "sweep": points}), flush=True)
 
 
+def backward_bench(args, torch, ha):
+    """Forward + backward of the chosen workload (Section 4.2 quotes its speed-ups on that sum),
+    with exact attention forward + backward beside it.  One JSON line."""
+    cfg = dict(synth_inputs.CONFIGS[args.workload])
+    B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
+    (Q, K, V), host = device_inputs(cfg, torch)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(synth_inputs.DATA_SEED + 7)
+    G = torch.randn(Q.shape, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    shape = ha.make_shape(B, H, n, d, ha.HA_BF16)
+    params = ha.make_params(cfg["b"], cfg["m"], cfg["r"], cfg["causal"], cfg["n_min"], cfg["seed"])
+    ws = ha.alloc_workspace(shape, params)
+    bws = ha.alloc_backward_workspace(shape, params)
+    out = torch.empty_like(Q)
+    lse = torch.empty((B, H, n), dtype=torch.float32, device="cuda")
+    grads = tuple(torch.empty_like(Q) for _ in range(3))
+    kw = dict(causal=cfg["causal"], n_min=cfg["n_min"], seed=cfg["seed"])
+    pa = (cfg["b"], cfg["m"], cfg["r"])
+
+    def fwd():
+        ha.hyperattn_forward(Q, K, V, *pa, workspace=ws, out=out, lse=lse, **kw)
+
+    def bwd():
+        ha.hyperattn_backward(Q, K, V, out, lse, G, *pa, fwd_workspace=ws, bwd_workspace=bws, grads=grads, **kw)
+
+    def both():
+        fwd()
+        bwd()
+
+    fwd_ms = time_call(torch, fwd, args.warmup, args.steps)
+    both_ms = time_call(torch, both, args.warmup, args.steps)
+    stage = {k: 0.0 for k in ha.binding.BWD_STAGE_NAMES}
+    for _ in range(args.steps):
+        ms = ha.hyperattn_backward_timed(Q, K, V, out, lse, G, *pa, fwd_workspace=ws, bwd_workspace=bws, grads=grads,
+                                         **kw)[3]
+        for k, v in ms.items():
+            stage[k] += v / args.steps
+    log(f"[bench] forward {fwd_ms:.3f} ms, forward + backward {both_ms:.3f} ms")
+    log("[bench] backward stage ms: " + ", ".join(f"{k} {v:.3f}" for k, v in stage.items()))
+    work = algorithmic_work(cfg)
+    # five products per (query, key) pair against the forward's two: S, dP, dQ, dK, dV
+    bwd_flop = 2.5 * (work["node_flop"] + work["base_flop"])
+    bwd_ms = both_ms - fwd_ms
+    result = {
+        "metric": "HyperAttention fwd+bwd ms", "value": round(both_ms, 4), "unit": "ms", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(both_ms, 4), "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "B": B, "H": H, "n": n, "d": d, "b": cfg["b"], "m": cfg["m"],
+                   "r": cfg["r"], "causal": bool(cfg["causal"]), "n_min": cfg["n_min"], "law": cfg["law"],
+                   "pass": "forward + backward"},
+        "forward_ms": round(fwd_ms, 4), "backward_ms": round(bwd_ms, 4),
+        "backward_stages_ms": {k: round(v, 4) for k, v in stage.items()},
+        "roofline": {"bound": "mfma", "kernel": "attn_bwd_kernel (all five passes of one backward call)",
+                     "achieved": round(bwd_flop / (bwd_ms * 1e-3) / 1e12, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(bwd_flop / (bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None, "flop_per_launch": bwd_flop, "ms_per_launch": round(bwd_ms, 4),
+                     "note": "algorithmic flops (5 products per pair); the two-pass scheme executes 7"},
+    }
+    if not args.no_exact:
+        eo, el = torch.empty_like(Q), torch.empty_like(lse)
+        ews = torch.empty(int(ha.lib().exact_attn_backward_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
+
+        egrads = tuple(torch.empty_like(Q) for _ in range(3))
+
+        def exact_both():
+            ha.exact_attn_forward(Q, K, V, causal=cfg["causal"], out=eo, lse=el)
+            ha.exact_attn_backward(Q, K, V, eo, el, G, causal=cfg["causal"], workspace=ews, grads=egrads)
+
+        ex_ms = time_call(torch, exact_both, 1, 2)
+        result["exact_fwd_bwd_ms"] = round(ex_ms, 3)
+        result["speedup_vs_exact"] = round(ex_ms / both_ms, 3)
+        log(f"[bench] exact attention forward + backward {ex_ms:.2f} ms -> speed-up {ex_ms / both_ms:.2f}x")
+        del eo, el, ews, egrads
+    if not args.no_cpu_baseline:
+        from oracle import hyperattn_oracle as orc
+        Qh, Kh, Vh = host
+        Gh = G[0, :1].float().cpu().numpy()[None]
+        t0 = time.perf_counter()
+        orc.hyperattn_forward(Qh, Kh, Vh, b=cfg["b"], m=cfg["m"], r=cfg["r"], causal=bool(cfg["causal"]),
+                              n_min=cfg["n_min"], seed=cfg["seed"])
+        ref = orc.hyperattn_backward(Qh, Kh, Vh, Gh, b=cfg["b"], m=cfg["m"], r=cfg["r"], causal=bool(cfg["causal"]),
+                                     n_min=cfg["n_min"], seed=cfg["seed"])
+        cpu_s = time.perf_counter() - t0
+        cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
+        errs = [float(np.linalg.norm(grads[i][0, 0].float().cpu().numpy() - ref[i][0, 0]) / np.linalg.norm(ref[i][0, 0]))
+                for i in range(3)]
+        result["cpu_baseline"] = {"value": round(cpu_s * 1e3 * B * H, 1), "unit": "ms", "cores": int(cores),
+                                  "kind": "oracle",
+                                  "sample": f"forward + backward of head 0 of batch 0 ({cpu_s:.1f} s measured), "
+                                            f"multiplied by B*H = {B * H} heads"}
+        result["parity_sample_rel_fro_err"] = {"dQ": errs[0], "dK": errs[1], "dV": errs[2]}
+        log(f"[bench] oracle fwd+bwd {cpu_s:.1f} s for one head; relative Frobenius errors dQ/dK/dV {errs}")
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -139,6 +234,7 @@ def main():
     ap.add_argument("--workload", default="cfg4_n131k_causal", choices=sorted(synth_inputs.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-exact", action="store_true")
+    ap.add_argument("--backward", action="store_true", help="time forward + backward instead of the forward alone")
     ap.add_argument("--sweep", action="store_true", help="time the 12-head d=64 sweep shape at every length instead")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -153,6 +249,8 @@ def main():
 
     if args.sweep:
         return sweep(args, torch, ha)
+    if args.backward:
+        return backward_bench(args, torch, ha)
 
     cfg = dict(synth_inputs.CONFIGS[args.workload])
     B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]

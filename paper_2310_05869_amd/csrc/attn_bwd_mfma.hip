@@ -24,6 +24,9 @@
 // to bf16 are directly the B operands of the accumulating products, whose A
 // operands (T tile transposed) come from the transposing LDS read.
 //
+// The dK/dV passes run twice, once accumulating dK (scores, dP, dS) and once
+// dV (scores, P): one accumulator set each, so two waves fit per SIMD.
+//
 // Results leave as fp32 rows into per-part buffers; sums over parts are taken by
 // separate kernels in a fixed order (no floating-point atomics anywhere).
 #include <type_traits>
@@ -54,8 +57,6 @@ struct BwdLds {
 
 __host__ __device__ inline int bwd_list_capacity(const Geometry& g, int mode) {
   if (mode == kBwdDqNode) return ((g.b + g.m + 63) & ~63) + 64;
-  if (mode == kBwdDkvBlock) return ((g.b + 63) & ~63) + 64;
-  if (mode == kBwdDkvSamp) return kBwdChunk;
   return 0;
 }
 
@@ -64,17 +65,19 @@ __host__ __device__ inline size_t bwd_lds_bytes(const Geometry& g, int mode) {
   return 2 * (size_t)BwdLds<D>::BUF + 2 * BwdLds<D>::SC + 64 + (size_t)bwd_list_capacity(g, mode) * 4;
 }
 
-// dK/dV passes need two accumulator sets (256 registers with the operands):
-// one wave per SIMD there, two in the dQ passes.
-template <int MODE>
-constexpr int bwd_min_waves() { return (MODE == kBwdDqNode || MODE == kBwdDqExact) ? 2 : 1; }
+// WHAT: which product the pass accumulates.
+enum BwdWhat : int { kAccDs = 0,   // acc += Y^T dS^T : dQ (dQ passes) or dK (dK/dV passes)
+                     kAccP = 1 };  // acc += Bt^T P^T : dV (dK/dV passes only)
 
-template <int D, int MODE>
-__global__ __launch_bounds__(kBNT, bwd_min_waves<MODE>()) void attn_bwd_kernel(BwdArgs a) {
+template <int D, int MODE, int WHAT>
+__global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   using L = BwdLds<D>;
   constexpr bool kDq = (MODE == kBwdDqNode || MODE == kBwdDqExact);
   constexpr bool kExact = (MODE == kBwdDqExact || MODE == kBwdDkvExact);
+  constexpr bool kSorted = (MODE == kBwdDkvBlock || MODE == kBwdDkvSamp);  // T rows = a run of sorted query positions
+  constexpr bool kWantDs = (WHAT == kAccDs);
+  static_assert(kWantDs || !kDq, "the dQ passes accumulate dS only");
   constexpr int KS = D / 16;
   constexpr int DT = D / 32;
   constexpr int CPR = D / 8;                 // 16-byte chunks per row
@@ -94,6 +97,7 @@ __global__ __launch_bounds__(kBNT, bwd_min_waves<MODE>()) void attn_bwd_kernel(B
   // ---- which part of the problem this workgroup owns ----
   TileWork w{};
   int chunk_start = 0, chunk_len = 0, samp0 = 0;  // sampled-key pass
+  int64_t samp_row0 = 0;
   int t0 = 0;                                      // exact dK/dV pass: first query row of the T range
   if (MODE == kBwdDqNode || MODE == kBwdDkvBlock) {
     w = decode_node_tile<kRT>(f, logical_block(blockIdx.x, gridDim.x));
@@ -116,14 +120,22 @@ __global__ __launch_bounds__(kBNT, bwd_min_waves<MODE>()) void attn_bwd_kernel(B
     w.k0 = t0;
     w.k1 = blk * eb + blk_rows;     // queries [t0, k1)
   } else {  // kBwdDkvSamp
-    int level = 0;
-    while (level + 1 < g.levels && (int)blockIdx.x >= a.samp_wg_off[level + 1]) ++level;
+    // (static indices only: a dynamically indexed kernel-argument array would be copied to scratch)
+    int level = 0, wg0 = 0;
+    int64_t srow0 = 0;
+#pragma unroll
+    for (int l = 0; l < kBwdMaxLevels; ++l)
+      if (l < g.levels && (int)blockIdx.x >= a.samp_wg_off[l]) {
+        level = l;
+        wg0 = a.samp_wg_off[l];
+        srow0 = a.samp_row_off[l];
+      }
     const NodeRef probe = node_ref(g, level, 0);
     const int clen = min(probe.s, kBwdChunk);
     const int cpn = (probe.s + clen - 1) / clen;        // chunks per node
     const int spn = (g.m + kRT - 1) / kRT;              // sample slabs per node
     const int nodes = g.causal ? (1 << level) : 1;
-    int idx = (int)blockIdx.x - a.samp_wg_off[level];
+    int idx = (int)blockIdx.x - wg0;
     const int slab = idx % spn;
     idx /= spn;
     const int qc = idx % cpn;
@@ -137,6 +149,7 @@ __global__ __launch_bounds__(kBNT, bwd_min_waves<MODE>()) void attn_bwd_kernel(B
     chunk_len = min(clen, w.nr.s - chunk_start);
     samp0 = slab * kRT;
     w.rows_valid = min(kRT, g.m - samp0);
+    samp_row0 = srow0;
     w.t = qc;  // reused: chunk index
     w.p0 = cpn;
   }
@@ -172,19 +185,19 @@ __global__ __launch_bounds__(kBNT, bwd_min_waves<MODE>()) void attn_bwd_kernel(B
     blk_r = f.samp_blk[((int64_t)w.bh * g.total_nodes + w.nr.heap) * g.m + j];
     const int nodes = g.causal ? (1 << w.level) : 1;
     const int node = w.nr.heap - ((1 << w.level) - 1);
-    out_row = a.samp_row_off[w.level] + ((((int64_t)w.bh * nodes + node) * w.p0 + w.t) * g.m + j);
+    out_row = samp_row0 + ((((int64_t)w.bh * nodes + node) * w.p0 + w.t) * g.m + j);
   } else {
     r_row = w.q0 + r_use;
     out_row = (int64_t)w.bh * g.n + r_row;
   }
-  bf16x8 xreg[KS], areg[KS];
+  bf16x8 xreg[KS], areg[kWantDs ? KS : 1];
   {
     const u32x4* xp = reinterpret_cast<const u32x4*>(Xh + (int64_t)r_row * D + 8 * h);
     const u32x4* ap = reinterpret_cast<const u32x4*>(Ah + (int64_t)r_row * D + 8 * h);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       xreg[ks] = __builtin_bit_cast(bf16x8, xp[2 * ks]);
-      areg[ks] = __builtin_bit_cast(bf16x8, ap[2 * ks]);
+      if constexpr (kWantDs) areg[ks] = __builtin_bit_cast(bf16x8, ap[2 * ks]);
     }
   }
   float nl2_r = 0.f, del_r = 0.f;  // dQ passes: -L log2(e) and delta of the R row
@@ -194,20 +207,18 @@ __global__ __launch_bounds__(kBNT, bwd_min_waves<MODE>()) void attn_bwd_kernel(B
     del_r = del_h[r_row];
   }
 
-  // ---- the T rows: a list in LDS (gathered passes) or a contiguous range ----
+  // ---- the T rows: the key list in LDS (dQ of a node), a run of sorted query
+  // positions read through P_Q (dK/dV of a node), or a contiguous range ----
   int nT, nb = 0x7fffffff;
+  const int32_t* tperm = nullptr;  // sorted passes: P_Q at T position 0
   if (MODE == kBwdDqNode) {
     nT = build_key_list<kBNT>(f, w, list, scratch, &nb);
   } else if (MODE == kBwdDkvBlock) {
     nT = g.b;
-    const int pad = (nT + 63) & ~63;
-    for (int i = tid; i < pad; i += kBNT) list[i] = f.perm_q[w.seg_off + w.t * g.b + min(i, nT - 1)];
-    __syncthreads();
+    tperm = f.perm_q + w.seg_off + (int64_t)w.t * g.b;
   } else if (MODE == kBwdDkvSamp) {
     nT = chunk_len;
-    const int pad = (nT + 63) & ~63;
-    for (int i = tid; i < pad; i += kBNT) list[i] = f.perm_q[w.seg_off + chunk_start + min(i, nT - 1)];
-    __syncthreads();
+    tperm = f.perm_q + w.seg_off + chunk_start;
   } else {
     nT = max(0, w.k1 - w.k0);
   }
@@ -220,9 +231,12 @@ __global__ __launch_bounds__(kBNT, bwd_min_waves<MODE>()) void attn_bwd_kernel(B
   const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc((void*)Bh, 0, (int)head_bytes, 0x00020000);
   u32x4 yreg[NKC], breg[NKC];
   float sc_l = 0.f, sc_d = 0.f;
-  auto trow = [&](int tp) -> int {  // row within the head of T position tp (tp < padded length)
-    if (kExact) return w.k0 + tp;
-    return list[tp];
+  // sorted passes: the rows of the tile to be loaded next, fetched one tile ahead of its loads
+  int tix[NKC], six = 0;
+  auto fetch_rows = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < NKC; ++i) tix[i] = tperm[min(kt * kTT + (tid + i * kBNT) / CPR, nT - 1)];
+    if (tid < kTT) six = tperm[min(kt * kTT + tid, nT - 1)];
   };
   auto load_tile = [&](int kt) {
 #pragma unroll
@@ -233,20 +247,23 @@ __global__ __launch_bounds__(kBNT, bwd_min_waves<MODE>()) void attn_bwd_kernel(B
       if (kExact) {
         voff = row * (D * 2) + col * 16;
         soff = (w.k0 + kt * kTT) * (D * 2);
+      } else if (kSorted) {
+        voff = tix[i] * (D * 2) + col * 16;
+        soff = 0;
       } else {
         voff = list[kt * kTT + row] * (D * 2) + col * 16;
         soff = 0;
       }
       yreg[i] = __builtin_amdgcn_raw_buffer_load_b128(yrsrc, voff, soff, 0);
-      breg[i] = __builtin_amdgcn_raw_buffer_load_b128(brsrc, voff, soff, 0);
+      if (kWantDs || !kDq) breg[i] = __builtin_amdgcn_raw_buffer_load_b128(brsrc, voff, soff, 0);
     }
     if (!kDq && tid < kTT) {
-      int row = trow(kt * kTT + tid);
-      row = min(row, g.n - 1);
+      int row = kSorted ? six : min(w.k0 + kt * kTT + tid, g.n - 1);
       const float lv = lse_h[row];
       sc_l = (lv == -INFINITY) ? -INFINITY : -lv * kLog2e;
       sc_d = del_h[row];
     }
+    if (kSorted && (kt + 1) * kTT < nT) fetch_rows(kt + 1);
   };
   auto store_tile = [&](int kt) {
     unsigned char* yb = bufs + (kt & 1) * L::BUF;
@@ -266,16 +283,14 @@ __global__ __launch_bounds__(kBNT, bwd_min_waves<MODE>()) void attn_bwd_kernel(B
   };
   const int vtr_off = ((lane & 15) >> 2) * L::TSTR + ((lane & 3) * 4 + ((lane >> 4) & 1) * 16) * 2 + (4 * h) * L::TSTR;
 
-  f32x16 acc1[DT], acc2[kDq ? 1 : DT];
+  f32x16 acc[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      acc1[dt][i] = 0.f;
-      if constexpr (!kDq) acc2[dt][i] = 0.f;
-    }
+    for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
 
   if (ntiles > 0) {
+    if (kSorted) fetch_rows(0);
     load_tile(0);
     store_tile(0);
   }
@@ -290,118 +305,110 @@ __global__ __launch_bounds__(kBNT, bwd_min_waves<MODE>()) void attn_bwd_kernel(B
     const unsigned char* bb = yb + L::TILE;
     const float* scb = sc + (kt & 1) * (2 * kTT);
 
-    // ---- S^T = Y X^T and dP^T = Bt A^T ----
-    f32x16 c[2], e[2];
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        c[sub][i] = 0.f;
-        e[sub][i] = 0.f;
-      }
-    {
-      const unsigned char* yp0 = yb + lq * L::TSTR + 16 * h;
-      const unsigned char* bp0 = bb + lq * L::TSTR + 16 * h;
-#pragma unroll
-      for (int j = 0; j < KS; ++j) {
-        c[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(yp0 + 32 * j), xreg[j], c[0], 0, 0, 0);
-        c[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(yp0 + 32 * L::TSTR + 32 * j), xreg[j], c[1], 0, 0, 0);
-        e[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(bp0 + 32 * j), areg[j], e[0], 0, 0, 0);
-        e[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(bp0 + 32 * L::TSTR + 32 * j), areg[j], e[1], 0, 0, 0);
-      }
-    }
-
     // ---- P^T and dS^T ----
+    // Masks as limits on the in-tile row offset ko = koff - 4 h of an accumulator element
+    // (koff = 32 sub + 8 (i / 4) + 4 h + i % 4): masked iff ko >= hi2 (end of the T rows; keys
+    // after the query), ko < lo2 (queries before the key) or mlo2 <= ko < mhi2 (queries of
+    // the sampled key's own block, factor 1 - M of Algorithm 2).
     const int tbase = kt * kTT;
-    const bool tail = tbase + kTT > nT;
-    bool special = tail;
+    int hi2 = nT - tbase - 4 * h;
+    int lo2 = -0x40000000, mlo2 = 0x40000000, mhi2 = 0x40000000, nb2 = 0x40000000;
     float tile_bias = 0.f;
     if (MODE == kBwdDqNode) {
-      special = special || ((tbase < nb) && (tbase + kTT > nb));
       tile_bias = (tbase >= nb) ? bias2 : 0.f;
+      if (tbase < nb) nb2 = nb - tbase - 4 * h;  // tile_bias is 0 on a tile that straddles nb
     }
-    if (MODE == kBwdDkvSamp) tile_bias = bias2;
-    if (MODE == kBwdDqExact && f.exact_causal) special = special || (w.k0 + tbase + kTT - 1 > w.q0 + wave * 32);
-    if (MODE == kBwdDkvExact && f.exact_causal) special = special || (t0 + tbase < w.q0 + wave * 32 + 31);
-    bool col_masked = false;  // sampled-key pass: the whole tile lies in this key's own block
     if (MODE == kBwdDkvSamp) {
-      if (g.b % kTT == 0) col_masked = ((chunk_start + tbase) / g.b) == blk_r;
-      else special = true;
+      tile_bias = bias2;
+      mlo2 = blk_r * g.b - (chunk_start + tbase) - 4 * h;
+      mhi2 = mlo2 + g.b;
     }
+    if (MODE == kBwdDqExact && f.exact_causal) hi2 = min(hi2, r_global - w.k0 - tbase + 1 - 4 * h);
+    if (MODE == kBwdDkvExact && f.exact_causal) lo2 = r_global - t0 - tbase - 4 * h;
+    // highest / lowest ko of a lane: 59 / 0
+    const bool special = __any(hi2 <= 59 || lo2 > 0 || nb2 <= 59 || (mlo2 <= 59 && mhi2 > 0));
 
-    bf16x8 pf[4], dsf[4];
+    bf16x8 bf[2];  // B operand of the accumulating product (per half): dS^T or P^T as bf16
+    // one 32-row half of the tile at a time: S^T = Y X^T and dP^T = Bt A^T, then P^T / dS^T
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
+    for (int sub = 0; sub < 2; ++sub) {
+      f32x16 cs, es;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        cs[i] = 0.f;
+        es[i] = 0.f;
+      }
+      {
+        const unsigned char* yp0 = yb + (32 * sub + lq) * L::TSTR + 16 * h;
+        const unsigned char* bp0 = bb + (32 * sub + lq) * L::TSTR + 16 * h;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+          cs = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(yp0 + 32 * j), xreg[j], cs, 0, 0, 0);
+          if constexpr (kWantDs)
+            es = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(bp0 + 32 * j), areg[j], es, 0, 0, 0);
+        }
+      }
+      f32x4 nlq = {0.f, 0.f, 0.f, 0.f}, dq4 = {0.f, 0.f, 0.f, 0.f};  // -L log2(e), delta of four T rows (dK/dV passes)
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
-        f32x4 nlT[2], dT[2];
-        if (!kDq) {
-#pragma unroll
-          for (int q = 0; q < 2; ++q) {
-            const int at = 32 * sub + 16 * jj + 8 * q + 4 * h;
-            nlT[q] = *reinterpret_cast<const f32x4*>(scb + at);
-            dT[q] = *reinterpret_cast<const f32x4*>(scb + kTT + at);
-          }
-        }
         u32x4 pk, dk;
 #pragma unroll
         for (int ee = 0; ee < 4; ++ee) {
+          // elements 8 jj + 2 ee, + 1: T rows 32 sub + 16 jj + 8 (ee / 2) + 4 h + 2 (ee % 2), + 1
+          f32x4 nlT = {0.f, 0.f, 0.f, 0.f}, dT = {0.f, 0.f, 0.f, 0.f};
+          if (!kDq && (ee % 2 == 0)) {
+            const int at = 32 * sub + 16 * jj + 8 * (ee / 2) + 4 * h;
+            nlq = *reinterpret_cast<const f32x4*>(scb + at);
+            dq4 = *reinterpret_cast<const f32x4*>(scb + kTT + at);
+          }
+          nlT = nlq;
+          dT = dq4;
           float pv[2], dv[2];
 #pragma unroll
           for (int z = 0; z < 2; ++z) {
             const int i = 8 * jj + 2 * ee + z;          // accumulator element
-            const int koff = 32 * sub + 8 * (i / 4) + 4 * h + (i % 4);
-            const int tp = tbase + koff;
-            const int q = (i / 4) & 1;                  // which of the two f32x4 of this (sub, jj)
             float arg;
             float dsub;
             if (kDq) {
-              arg = __builtin_fmaf(c[sub][i], kLog2e, nl2_r + tile_bias);
+              arg = __builtin_fmaf(cs[i], kLog2e, nl2_r + tile_bias);
               dsub = del_r;
             } else {
-              arg = __builtin_fmaf(c[sub][i], kLog2e, nlT[q][i % 4] + tile_bias);
-              dsub = dT[q][i % 4];
+              arg = __builtin_fmaf(cs[i], kLog2e, nlT[i % 4] + tile_bias);
+              dsub = dT[i % 4];
             }
             if (special) {
-              bool msk = tp >= nT;
-              if (MODE == kBwdDqNode && tp >= nb && tbase < nb) arg += bias2;  // mixed tile: tile_bias is 0 there
-              if (MODE == kBwdDqExact && f.exact_causal) msk = msk || (w.k0 + tp > r_global);
-              if (MODE == kBwdDkvExact && f.exact_causal) msk = msk || (t0 + tp < r_global);
-              if (MODE == kBwdDkvSamp && (g.b % kTT != 0)) msk = msk || (((chunk_start + tp) / g.b) == blk_r);
+              const int ko = 32 * sub + 8 * (i / 4) + (i % 4);
+              if (MODE == kBwdDqNode && ko >= nb2) arg += bias2;
+              bool msk = ko >= hi2;
+              if (MODE == kBwdDkvExact) msk = msk || (ko < lo2);
+              if (MODE == kBwdDkvSamp) msk = msk || ((unsigned)(ko - mlo2) < (unsigned)g.b);
               if (msk) arg = -INFINITY;
             }
-            if (MODE == kBwdDkvSamp && col_masked) arg = -INFINITY;
             const float p = __builtin_amdgcn_exp2f(arg);
             pv[z] = p;
-            dv[z] = p * (e[sub][i] - dsub);
+            dv[z] = p * (es[i] - dsub);
           }
           pk[ee] = pack_bf16x2(pv[0], pv[1]);
           dk[ee] = pack_bf16x2(dv[0], dv[1]);
         }
-        pf[2 * sub + jj] = __builtin_bit_cast(bf16x8, pk);
-        dsf[2 * sub + jj] = __builtin_bit_cast(bf16x8, dk);
+        bf[jj] = __builtin_bit_cast(bf16x8, kWantDs ? dk : pk);
       }
-
-    // ---- acc1^T += Y^T dS^T ; acc2^T += Bt^T P^T ----
-    {
-      typedef short s16x4 __attribute__((ext_vector_type(4)));
-      typedef short s16x8 __attribute__((ext_vector_type(8)));
-      typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+      // ---- acc^T += Y^T dS^T  or  acc^T += Bt^T P^T  for the 32 rows of this half ----
+      {
+        typedef short s16x4 __attribute__((ext_vector_type(4)));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+        const unsigned char* tb = (kWantDs ? yb : bb) + vtr_off;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+        for (int jj = 0; jj < 2; ++jj) {
+          const int j = 2 * sub + jj;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          const unsigned char* yp = yb + vtr_off + (16 * j) * L::TSTR + (32 * dt) * 2;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(yp));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(yp + 8 * L::TSTR));
-          const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          acc1[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), dsf[j], acc1[dt], 0, 0, 0);
-          if constexpr (!kDq) {
-            const unsigned char* bp = bb + vtr_off + (16 * j) * L::TSTR + (32 * dt) * 2;
-            const s16x4 lo2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(bp));
-            const s16x4 hi2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(bp + 8 * L::TSTR));
-            const s16x8 both2 = __builtin_shufflevector(lo2, hi2, 0, 1, 2, 3, 4, 5, 6, 7);
-            acc2[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both2), pf[j], acc2[dt], 0, 0, 0);
+          for (int dt = 0; dt < DT; ++dt) {
+            const unsigned char* tp = tb + (16 * j) * L::TSTR + (32 * dt) * 2;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(tp));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(tp + 8 * L::TSTR));
+            const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), bf[jj], acc[dt], 0, 0, 0);
           }
         }
       }
@@ -437,40 +444,45 @@ __global__ __launch_bounds__(kBNT, bwd_min_waves<MODE>()) void attn_bwd_kernel(B
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   };
-  drain(acc1, a.out1);
-  if constexpr (!kDq) drain(acc2, a.out2);
+  drain(acc, kWantDs ? a.out1 : a.out2);
 }
 
-template <int D, int MODE>
+template <int D, int MODE, int WHAT>
 static int launch_bwd_one(const BwdArgs& a, int grid, hipStream_t st) {
   if (grid <= 0) return HA_OK;
   size_t lds = bwd_lds_bytes<D>(a.f.g, MODE);
   if (lds < (size_t)4 * BwdLds<D>::EP_WAVE) lds = (size_t)4 * BwdLds<D>::EP_WAVE;
   static bool configured = false;  // per instantiation
   if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_kernel<D, MODE>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_kernel<D, MODE, WHAT>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
       (void)hipGetLastError();
       return HA_ERR_LAUNCH;
     }
     configured = true;
   }
-  hipLaunchKernelGGL((attn_bwd_kernel<D, MODE>), dim3((unsigned)grid), dim3(kBNT), lds, st, a);
+  hipLaunchKernelGGL((attn_bwd_kernel<D, MODE, WHAT>), dim3((unsigned)grid), dim3(kBNT), lds, st, a);
   return check_launch();
+}
+
+// dK/dV passes: two launches, dK into out1 and dV into out2
+template <int D, int MODE>
+static int launch_bwd_pair(const BwdArgs& a, int grid, hipStream_t st) {
+  const int rc = launch_bwd_one<D, MODE, kAccDs>(a, grid, st);
+  return rc != HA_OK ? rc : launch_bwd_one<D, MODE, kAccP>(a, grid, st);
 }
 
 template <int D>
 static int launch_bwd_d(const BwdArgs& a, int mode, int grid, hipStream_t st) {
   switch (mode) {
-    case kBwdDqNode: return launch_bwd_one<D, kBwdDqNode>(a, grid, st);
-    case kBwdDqExact: return launch_bwd_one<D, kBwdDqExact>(a, grid, st);
-    case kBwdDkvBlock: return launch_bwd_one<D, kBwdDkvBlock>(a, grid, st);
-    case kBwdDkvSamp: return launch_bwd_one<D, kBwdDkvSamp>(a, grid, st);
-    case kBwdDkvExact: return launch_bwd_one<D, kBwdDkvExact>(a, grid, st);
+    case kBwdDqNode: return launch_bwd_one<D, kBwdDqNode, kAccDs>(a, grid, st);
+    case kBwdDqExact: return launch_bwd_one<D, kBwdDqExact, kAccDs>(a, grid, st);
+    case kBwdDkvBlock: return launch_bwd_pair<D, kBwdDkvBlock>(a, grid, st);
+    case kBwdDkvSamp: return launch_bwd_pair<D, kBwdDkvSamp>(a, grid, st);
+    case kBwdDkvExact: return launch_bwd_pair<D, kBwdDkvExact>(a, grid, st);
     default: return HA_ERR_SHAPE;
   }
 }
-
 int bwd_grid(const BwdArgs& a, int mode) {
   const Geometry& g = a.f.g;
   if (mode == kBwdDqNode || mode == kBwdDkvBlock) return node_grid<kRT>(g);

@@ -149,3 +149,42 @@ def test_backward_error_paths(ha, torch):
         ha.hyperattn_backward(qb, qb, qb, out, lse, qb, 64, 16, 7, fwd_workspace=ws, bwd_workspace=small)
     with pytest.raises(ha.HyperAttnError):          # forward workspace too small
         ha.hyperattn_backward(qb, qb, qb, out, lse, qb, 64, 16, 7, fwd_workspace=small)
+
+
+@pytest.mark.parametrize("name", ["cfg2_n32k", "cfg4_n131k_causal", "sweep_h12_d64_n65536_causal"])
+def test_backward_full_size_sampled_head(ha, torch, name):
+    """The benchmark configurations at full size: every head runs, head 0 of
+    batch 0 (fed from the seeded host generator) is compared with the oracle."""
+    cfg = synth_inputs.CONFIGS[name]
+    print(f"backward full size {name}", flush=True)
+    B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    host = synth_inputs.make_qkv(cfg, B=1, H=1)
+    Gh = _cotangent(host[0].shape, 9)
+    dev = []
+    for i in range(4):
+        t = torch.randn((B, H, n, d), generator=gen, device="cuda", dtype=torch.float32)
+        if i < 3:
+            t.mul_(d ** -0.25)
+        t = t.to(torch.bfloat16)
+        t[0, :1] = to_device((host[i] if i < 3 else Gh)[0], "bf16")
+        dev.append(t.contiguous())
+    Q, K, V, G = dev
+    shape = ha.make_shape(B, H, n, d, ha.HA_BF16)
+    params = ha.make_params(cfg["b"], cfg["m"], cfg["r"], cfg["causal"], cfg["n_min"], cfg["seed"])
+    ws = ha.alloc_workspace(shape, params)
+    kw = dict(causal=cfg["causal"], n_min=cfg["n_min"], seed=cfg["seed"])
+    out, lse = ha.hyperattn_forward(Q, K, V, cfg["b"], cfg["m"], cfg["r"], workspace=ws, **kw)
+    grads = ha.hyperattn_backward(Q, K, V, out, lse, G, cfg["b"], cfg["m"], cfg["r"], fwd_workspace=ws, **kw)
+    torch.cuda.synchronize()
+    views = ha.workspace_views(ws, shape, params)
+    stages = {}
+    okw = dict(b=cfg["b"], m=cfg["m"], r=cfg["r"], causal=bool(cfg["causal"]), n_min=cfg["n_min"], seed=cfg["seed"])
+    orc.hyperattn_forward(*host, stages=stages, **okw)
+    gpu_codes = np.stack([views["codes_q"][:1].cpu().numpy(), views["codes_k"][:1].cpu().numpy()])
+    flips = compare_codes(gpu_codes, stages, cfg["r"])
+    ref = orc.hyperattn_backward(*host, Gh, flip=flips or None, **okw)
+    for got, r_, what in zip(grads, ref, ("dQ", "dK", "dV")):
+        _assert_grad_close(to_host(got[0, :1])[None], r_, what)
+        assert torch.isfinite(got.float()).all()
