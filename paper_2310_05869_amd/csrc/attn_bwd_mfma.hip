@@ -121,11 +121,12 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
     w.k1 = blk * eb + blk_rows;     // queries [t0, k1)
   } else {  // kBwdDkvSamp
     // (static indices only: a dynamically indexed kernel-argument array would be copied to scratch)
+    const int sbid = logical_block(blockIdx.x, gridDim.x);  // slabs of one chunk meet in one L2
     int level = 0, wg0 = 0;
     int64_t srow0 = 0;
 #pragma unroll
     for (int l = 0; l < kBwdMaxLevels; ++l)
-      if (l < g.levels && (int)blockIdx.x >= a.samp_wg_off[l]) {
+      if (l < g.levels && sbid >= a.samp_wg_off[l]) {
         level = l;
         wg0 = a.samp_wg_off[l];
         srow0 = a.samp_row_off[l];
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
     const int cpn = (probe.s + clen - 1) / clen;        // chunks per node
     const int spn = (g.m + kRT - 1) / kRT;              // sample slabs per node
     const int nodes = g.causal ? (1 << level) : 1;
-    int idx = (int)blockIdx.x - wg0;
+    int idx = sbid - wg0;
     const int slab = idx % spn;
     idx /= spn;
     const int qc = idx % cpn;

@@ -48,17 +48,26 @@ int launch_bwd_delta(const void* O, const void* dO, float* delta, int64_t rows, 
   return check_launch();
 }
 
-// One workgroup per (head, node); thread c owns column c of dK (threads < d) or
-// of dV (threads >= d).  For sample j = 0 .. m-1 in order: the partial sums of
-// the node's query chunks are added up (chunk order) and added to the key's row
-// in the level's buffer.  A key drawn twice receives both terms, one after the
-// other, from the same thread.
-__global__ __launch_bounds__(256) void bwd_sample_scatter_kernel(BwdArgs a, const float* __restrict__ samp_k,
-                                                                 const float* __restrict__ samp_v, float* part_k, float* part_v) {
+// Sampled keys' gradients into the level's key buffers.  One wave per sample j
+// of a (head, node); a lane owns four columns of dK (lanes < d/4) or of dV (the
+// next d/4 lanes).  A key may be drawn more than once: the FIRST sample that
+// drew a key ("owner") adds, in increasing sample order, the sums of every
+// sample of that key, each taken over the node's query chunks in a fixed order;
+// the other samples of the key do nothing.  One writer per row and a fixed
+// order of additions: reproducible bit for bit.
+constexpr int kScatterWaves = 4;
+
+__global__ __launch_bounds__(64 * kScatterWaves) void bwd_sample_scatter_kernel(BwdArgs a, const float* __restrict__ samp_k,
+                                                                                const float* __restrict__ samp_v,
+                                                                                float* part_k, float* part_v) {
+  __shared__ int32_t keys[4096];
   const Geometry& g = a.f.g;
-  const int d = g.d;
-  const int bh = blockIdx.x / g.total_nodes;
-  const int heap = blockIdx.x % g.total_nodes;
+  const int d = g.d, m = g.m;
+  const int groups = (m + kScatterWaves - 1) / kScatterWaves;
+  const int grp = blockIdx.x % groups;
+  const int rest = blockIdx.x / groups;
+  const int bh = rest / g.total_nodes;
+  const int heap = rest % g.total_nodes;
   int level = 0;
   while ((2 << level) - 1 <= heap) ++level;
   const int node = heap - ((1 << level) - 1);
@@ -66,16 +75,54 @@ __global__ __launch_bounds__(256) void bwd_sample_scatter_kernel(BwdArgs a, cons
   const int nodes = g.causal ? (1 << level) : 1;
   const int cpn = bwd_chunks_per_node(g, level);
   const int64_t seg_off = ((int64_t)level * g.BH + bh) * g.n_cov + (int64_t)node * nr.s;
-  const int c = threadIdx.x % d;
-  const float* src = (int)threadIdx.x < d ? samp_k : samp_v;
-  float* dst = (int)threadIdx.x < d ? part_k : part_v;
-  if ((int)threadIdx.x >= 2 * d) return;
-  const int64_t row0 = a.samp_row_off[level] + ((int64_t)bh * nodes + node) * cpn * g.m;
-  for (int j = 0; j < g.m; ++j) {
-    float s = 0.f;
-    for (int qc = 0; qc < cpn; ++qc) s += src[(row0 + (int64_t)qc * g.m + j) * d + c];
-    const int key = a.f.samples[(int64_t)heap * g.m + j];
-    dst[(seg_off + key) * d + c] += s;
+  int64_t lvl_row0 = 0;
+#pragma unroll
+  for (int l = 0; l < kBwdMaxLevels; ++l)
+    if (l == level) lvl_row0 = a.samp_row_off[l];
+  const int64_t row0 = lvl_row0 + ((int64_t)bh * nodes + node) * cpn * m;
+
+  for (int j = threadIdx.x; j < m; j += blockDim.x) keys[j] = a.f.samples[(int64_t)heap * m + j];
+  __syncthreads();
+  const int lane = threadIdx.x & 63;
+  const int j = grp * kScatterWaves + (threadIdx.x >> 6);
+  if (j >= m) return;
+  const int key = keys[j];
+  // an earlier sample of the same key owns it
+  for (int base = 0; base < j; base += 64) {
+    const int jj = base + lane;
+    if (__any(jj < j && keys[jj] == key)) return;
+  }
+  const int q4 = d / 4;  // column quads per row
+  const bool active = lane < 2 * q4;
+  const float* src = lane < q4 ? samp_k : samp_v;
+  float* dst = lane < q4 ? part_k : part_v;
+  const int c4 = (lane % q4) * 4;
+  f32x4 total = {0.f, 0.f, 0.f, 0.f};
+  for (int base = j; base < m; base += 64) {
+    const int jl = base + lane;
+    unsigned long long same = __ballot(jl < m && keys[jl] == key);
+    while (same) {
+      const int jj = base + __builtin_ctzll(same);
+      same &= same - 1;
+      if (active) {
+        const float* p = src + (row0 + jj) * d + c4;
+        const int64_t step = (int64_t)m * d;
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, s2 = s0, s3 = s0;
+        int qc = 0;
+        for (; qc + 4 <= cpn; qc += 4) {
+          s0 += *reinterpret_cast<const f32x4*>(p + (qc + 0) * step);
+          s1 += *reinterpret_cast<const f32x4*>(p + (qc + 1) * step);
+          s2 += *reinterpret_cast<const f32x4*>(p + (qc + 2) * step);
+          s3 += *reinterpret_cast<const f32x4*>(p + (qc + 3) * step);
+        }
+        for (; qc < cpn; ++qc) s0 += *reinterpret_cast<const f32x4*>(p + qc * step);
+        total += (s0 + s1) + (s2 + s3);
+      }
+    }
+  }
+  if (active) {
+    f32x4* out = reinterpret_cast<f32x4*>(dst + (seg_off + key) * d + c4);
+    *out = *out + total;
   }
 }
 
@@ -83,8 +130,9 @@ int launch_bwd_sample_scatter(const BwdArgs& a, const float* samp_k, const float
                               float* part_v, hipStream_t st) {
   const Geometry& g = a.f.g;
   if (g.m <= 0 || g.total_nodes <= 0) return HA_OK;
-  hipLaunchKernelGGL(bwd_sample_scatter_kernel, dim3((unsigned)(g.BH * g.total_nodes)), dim3(256), 0, st, a, samp_k,
-                     samp_v, part_k, part_v);
+  const int groups = (g.m + kScatterWaves - 1) / kScatterWaves;
+  hipLaunchKernelGGL(bwd_sample_scatter_kernel, dim3((unsigned)(g.BH * g.total_nodes * groups)),
+                     dim3(64 * kScatterWaves), 0, st, a, samp_k, samp_v, part_k, part_v);
   return check_launch();
 }
 
