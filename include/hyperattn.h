@@ -220,14 +220,14 @@ int ha_merge_unpermute(const float* o_b, const float* lse_b, const float* o_r, c
  * hyperattn_backward_timed: the same, and WAITS for the stream; stage_ms_host
  * (host, 8 floats) receives the times between events on the stream: delta, dQ
  * of the nodes, dQ of the base case, dK/dV of the block keys, dK/dV of the
- * sampled keys with their reduction, dK/dV of the base case, final sums, total.
+ * sampled keys with their reduction, dK/dV of the base case, final sums (unmasked
+ * problems only; the causal base-case passes add the levels themselves), total.
  *
  * exact_attn_backward: gradients of exact_attn_forward (Section 1.1; causal:
  * Section 3.1), the denominator of the forward + backward speed-up.  workspace
  * >= exact_attn_backward_workspace_bytes(shape). */
 typedef struct {
   size_t delta;                      /* fp32 [B*H][n] */
-  size_t dq_base, dk_base, dv_base;  /* fp32 [B*H][n][d], causal only */
   size_t dq_part, dk_part, dv_part;  /* fp32 [levels][B*H][n_cov][d] */
   size_t samp_k, samp_v;             /* fp32 rows of the sampled keys per (level, head, node, query chunk, sample) */
   size_t total_bytes;

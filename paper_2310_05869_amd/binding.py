@@ -36,8 +36,7 @@ class HaWsLayout(ctypes.Structure):
 
 
 class HaBwdWsLayout(ctypes.Structure):
-    _fields_ = [(k, c_size_t) for k in ("delta", "dq_base", "dk_base", "dv_base", "dq_part", "dk_part", "dv_part",
-                                        "samp_k", "samp_v", "total_bytes")]
+    _fields_ = [(k, c_size_t) for k in ("delta", "dq_part", "dk_part", "dv_part", "samp_k", "samp_v", "total_bytes")]
 
 
 class HyperAttnError(RuntimeError):

@@ -267,11 +267,7 @@ static void fill_bwd_layout(const Geometry& g, ha_bwd_ws_layout* l) {
   const size_t rows = (size_t)g.BH * g.n;
   const size_t cov = (size_t)g.levels * g.BH * g.n_cov;
   const size_t rowb = (size_t)g.d * 4;
-  const bool base = g.causal != 0;
   l->delta = take(rows * 4);
-  l->dq_base = take(base ? rows * rowb : 0);
-  l->dk_base = take(base ? rows * rowb : 0);
-  l->dv_base = take(base ? rows * rowb : 0);
   l->dq_part = take(cov * rowb);
   l->dk_part = take(cov * rowb);
   l->dv_part = take(cov * rowb);
@@ -304,9 +300,6 @@ static int backward_impl(const void* Q, const void* K, const void* V, const void
   const unsigned char* fb = (const unsigned char*)fws;
   unsigned char* bb = (unsigned char*)bws;
   float* delta = (float*)(bb + bl.delta);
-  float* dq_base = (float*)(bb + bl.dq_base);
-  float* dk_base = (float*)(bb + bl.dk_base);
-  float* dv_base = (float*)(bb + bl.dv_base);
   float* dq_part = (float*)(bb + bl.dq_part);
   float* dk_part = (float*)(bb + bl.dk_part);
   float* dv_part = (float*)(bb + bl.dv_part);
@@ -361,7 +354,8 @@ static int backward_impl(const void* Q, const void* K, const void* V, const void
   }
   mark(2);
   if (g.causal) {
-    a.out1 = dq_base;
+    a.fin1 = dQ;
+    a.lvl1 = g.levels > 0 ? dq_part : nullptr;
     rc = launch_attn_bwd_mfma(a, kBwdDqExact, st);
     if (rc != HA_OK) return rc;
   }
@@ -383,18 +377,22 @@ static int backward_impl(const void* Q, const void* K, const void* V, const void
   }
   mark(5);
   if (g.causal) {
-    a.out1 = dk_base;
-    a.out2 = dv_base;
+    a.fin1 = dK;
+    a.fin2 = dV;
+    a.lvl1 = g.levels > 0 ? dk_part : nullptr;
+    a.lvl2 = g.levels > 0 ? dv_part : nullptr;
     rc = launch_attn_bwd_mfma(a, kBwdDkvExact, st);
     if (rc != HA_OK) return rc;
   }
   mark(6);
-  rc = launch_bwd_combine(g.causal ? dq_base : nullptr, dq_part, dQ, g, 1, st);
-  if (rc != HA_OK) return rc;
-  rc = launch_bwd_combine(g.causal ? dk_base : nullptr, dk_part, dK, g, 0, st);
-  if (rc != HA_OK) return rc;
-  rc = launch_bwd_combine(g.causal ? dv_base : nullptr, dv_part, dV, g, 0, st);
-  if (rc != HA_OK) return rc;
+  if (!g.causal) {  // one node, no base case: the level-0 rows are the result
+    rc = launch_bwd_combine(nullptr, dq_part, dQ, g, 1, st);
+    if (rc != HA_OK) return rc;
+    rc = launch_bwd_combine(nullptr, dk_part, dK, g, 0, st);
+    if (rc != HA_OK) return rc;
+    rc = launch_bwd_combine(nullptr, dv_part, dV, g, 0, st);
+    if (rc != HA_OK) return rc;
+  }
   mark(7);
   return HA_OK;
 }
@@ -664,18 +662,12 @@ int exact_attn_backward(const void* Q, const void* K, const void* V, const void*
   a.delta = (float*)(bb + bl.delta);
   rc = launch_bwd_delta(out, d_out, (float*)(bb + bl.delta), (int64_t)g.BH * g.n, g.d, st);
   if (rc != HA_OK) return rc;
-  a.out1 = (float*)(bb + bl.dq_base);
+  a.fin1 = dQ;
   rc = launch_attn_bwd_mfma(a, kBwdDqExact, st);
   if (rc != HA_OK) return rc;
-  a.out1 = (float*)(bb + bl.dk_base);
-  a.out2 = (float*)(bb + bl.dv_base);
-  rc = launch_attn_bwd_mfma(a, kBwdDkvExact, st);
-  if (rc != HA_OK) return rc;
-  rc = launch_bwd_combine((float*)(bb + bl.dq_base), nullptr, dQ, g, 1, st);
-  if (rc != HA_OK) return rc;
-  rc = launch_bwd_combine((float*)(bb + bl.dk_base), nullptr, dK, g, 0, st);
-  if (rc != HA_OK) return rc;
-  return launch_bwd_combine((float*)(bb + bl.dv_base), nullptr, dV, g, 0, st);
+  a.fin1 = dK;
+  a.fin2 = dV;
+  return launch_attn_bwd_mfma(a, kBwdDkvExact, st);
 }
 
 size_t exact_attn_backward_workspace_bytes(const ha_shape* sh) {

@@ -52,7 +52,7 @@ struct BwdLds {
   static constexpr int BUF = 2 * TILE;          // y tile + bt tile
   static constexpr int SC = 2 * kTT * 4;        // per buffer: -L log2(e) and delta of the T rows
   static constexpr int EP_ROW = D * 4 + 16;
-  static constexpr int EP_WAVE = 32 * EP_ROW + 256;
+  static constexpr int EP_WAVE = 32 * EP_ROW + 256 + kBwdMaxLevels * 8;  // rows, row ids, level row bases
 };
 
 __host__ __device__ inline int bwd_list_capacity(const Geometry& g, int mode) {
@@ -418,19 +418,27 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
     __syncthreads();
   }
 
-  // ---- epilogue: the wave's 32 rows leave through an LDS transpose as whole fp32 rows ----
+  // ---- epilogue: the wave's 32 rows leave through an LDS transpose as whole rows.
+  // Node passes write fp32 rows into the per-level buffers.  Exact passes (the
+  // base case of Algorithm 4) write the final gradient in the tensors' dtype,
+  // after adding the rows of every level whose node holds these rows on the
+  // pass's side (queries: second half of the node; keys: first half).  The 32
+  // rows of a wave lie in one n_min block, so a level holds all or none of them
+  // and then as 32 consecutive rows.
   unsigned char* ep = smem + wave * L::EP_WAVE;
   int64_t* ep_rows = reinterpret_cast<int64_t*>(ep + 32 * L::EP_ROW);
+  int64_t* ep_pr = ep_rows + 32;
   if (h == 0) ep_rows[lq] = r_valid ? out_row : (int64_t)-1;
-  auto drain = [&](const f32x16 (&acc)[DT], float* dst) {
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+  for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const int col = 32 * dt + 8 * g4 + 4 * h;
-        const f32x4 v = {acc[dt][4 * g4], acc[dt][4 * g4 + 1], acc[dt][4 * g4 + 2], acc[dt][4 * g4 + 3]};
-        *reinterpret_cast<f32x4*>(ep + lq * L::EP_ROW + col * 4) = v;
-      }
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int col = 32 * dt + 8 * g4 + 4 * h;
+      const f32x4 v = {acc[dt][4 * g4], acc[dt][4 * g4 + 1], acc[dt][4 * g4 + 2], acc[dt][4 * g4 + 3]};
+      *reinterpret_cast<f32x4*>(ep + lq * L::EP_ROW + col * 4) = v;
+    }
+  float* dst32 = kWantDs ? a.out1 : a.out2;
+  if (!kExact) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -439,13 +447,71 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
       const int row = idx / CH, ch = idx % CH;
       const int64_t r64 = ep_rows[row];
       if (r64 >= 0)
-        *reinterpret_cast<f32x4*>(dst + r64 * D + ch * 4) = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 16);
+        *reinterpret_cast<f32x4*>(dst32 + r64 * D + ch * 4) = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 16);
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    return;
+  }
+  uint16_t* dst16 = reinterpret_cast<uint16_t*>(kWantDs ? a.fin1 : a.fin2);
+  const float* lvl = kWantDs ? a.lvl1 : a.lvl2;
+  int nfold = 0;
+  if (lvl != nullptr) {
+    const int i0 = w.q0 + 32 * __builtin_amdgcn_readfirstlane(wave);
+    const bool want_second = kDq;
+    for (int l = 0; l < g.levels; ++l) {
+      const int sl = g.n >> (l + 1);
+      const bool second = ((i0 / sl) & 1) != 0;
+      if (second != want_second) continue;
+      if (lane == 0) ep_pr[nfold] = ((int64_t)l * g.BH + w.bh) * g.n_cov + (int64_t)(i0 / (2 * sl)) * sl + (i0 % sl);
+      ++nfold;
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  constexpr int CH8 = D / 8;  // 8-element pieces per row
+  // NF: compile-time count of folded rows so their loads are issued together; 0 = run-time count nfold
+  auto rows_out = [&](auto nf_tag) {
+    constexpr int NF = decltype(nf_tag)::value;
+    const int nf = NF > 0 ? NF : nfold;
+    for (int idx = lane; idx < 32 * CH8; idx += 64) {
+      const int row = idx / CH8, ch = idx % CH8;
+      const int64_t r64 = ep_rows[row];
+      if (r64 < 0) continue;
+      f32x4 v0 = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 32);
+      f32x4 v1 = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 32 + 16);
+      if (NF > 0) {
+        f32x4 p0[NF > 0 ? NF : 1], p1[NF > 0 ? NF : 1];
+#pragma unroll
+        for (int c = 0; c < NF; ++c) {
+          const float* pp = lvl + (ep_pr[c] + row) * D + ch * 8;
+          p0[c] = *reinterpret_cast<const f32x4*>(pp);
+          p1[c] = *reinterpret_cast<const f32x4*>(pp + 4);
+        }
+#pragma unroll
+        for (int c = 0; c < NF; ++c) {
+          v0 += p0[c];
+          v1 += p1[c];
+        }
+      } else {
+        for (int c = 0; c < nf; ++c) {
+          const float* pp = lvl + (ep_pr[c] + row) * D + ch * 8;
+          v0 += *reinterpret_cast<const f32x4*>(pp);
+          v1 += *reinterpret_cast<const f32x4*>(pp + 4);
+        }
+      }
+      const u32x4 pk = {pack_bf16x2(v0.x, v0.y), pack_bf16x2(v0.z, v0.w), pack_bf16x2(v1.x, v1.y), pack_bf16x2(v1.z, v1.w)};
+      *reinterpret_cast<u32x4*>(dst16 + r64 * D + ch * 8) = pk;
+    }
   };
-  drain(acc, kWantDs ? a.out1 : a.out2);
+  switch (nfold) {
+    case 1: rows_out(std::integral_constant<int, 1>{}); break;
+    case 2: rows_out(std::integral_constant<int, 2>{}); break;
+    case 3: rows_out(std::integral_constant<int, 3>{}); break;
+    case 4: rows_out(std::integral_constant<int, 4>{}); break;
+    case 5: rows_out(std::integral_constant<int, 5>{}); break;
+    case 6: rows_out(std::integral_constant<int, 6>{}); break;
+    default: rows_out(std::integral_constant<int, 0>{}); break;  // none, or more than six
+  }
 }
 
 template <int D, int MODE, int WHAT>

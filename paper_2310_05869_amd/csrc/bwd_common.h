@@ -24,6 +24,12 @@ struct BwdArgs {
   const float* delta;  // <dO_i, O_i> [BH][n]
   float* out1;         // fp32 rows: dQ (dQ passes) or dK (dK/dV passes)
   float* out2;         // fp32 rows: dV (dK/dV passes)
+  // exact passes write the final gradients (tensors' dtype) instead: fin1 = dQ or dK, fin2 = dV,
+  // after adding the rows of the per-level buffers lvl1 / lvl2 (null: nothing to add)
+  void* fin1;
+  void* fin2;
+  const float* lvl1;
+  const float* lvl2;
   // sampled-key pass: first workgroup and first output row of every level
   int32_t samp_wg_off[kBwdMaxLevels + 1];
   int64_t samp_row_off[kBwdMaxLevels];

@@ -93,7 +93,8 @@ def test_backward_unmasked(ha, torch, d, n, b, m):
 
 @pytest.mark.parametrize("d,n,n_min,b,m", [(128, 2048, 256, 128, 64), (64, 4096, 1024, 256, 256),
                                            (128, 1024, 4096, 256, 256), (128, 1024, 512, 512, 0),
-                                           (64, 2048, 64, 32, 16), (128, 8192, 1024, 256, 256)])
+                                           (64, 2048, 64, 32, 16), (128, 8192, 1024, 256, 256),
+                                           (64, 8192, 32, 32, 16)])  # eight levels: more than the epilogue unrolls
 def test_backward_causal(ha, torch, d, n, n_min, b, m):
     print(f"backward causal d={d} n={n} n_min={n_min} b={b} m={m}", flush=True)
     cfg = dict(B=2, H=1, n=n, d=d, dtype="bf16", law="iid", b=b, m=m, r=7, causal=1, n_min=n_min, seed=3)
