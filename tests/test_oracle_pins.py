@@ -403,3 +403,25 @@ def test_backward_invariants_from_row_stochasticity():
     dQ2, dK2, dV2 = orc.hyperattn_backward(Q, K, V, -2.0 * G, **kw)
     np.testing.assert_allclose(dQ2, -2.0 * dQ, rtol=1e-12, atol=1e-12)
     np.testing.assert_allclose(dK2, -2.0 * dK, rtol=1e-12, atol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# Frozen record of the oracle on tiny problems (tests/golden/, written by
+# tests/golden/make_golden.py from the oracle alone): guards against an
+# unnoticed change of its arithmetic; not an independent pin.
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("case", ["unmasked_n32_d4", "causal_n32_d4"])
+def test_oracle_matches_its_frozen_record(case):
+    import importlib.util
+    import json
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_golden.py"))
+    mg = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mg)
+    with open(os.path.join(here, f"oracle_{case}.json")) as f:
+        stored = json.load(f)
+    now = mg.compute(case)
+    for key, val in stored.items():
+        np.testing.assert_allclose(np.asarray(now[key], dtype=np.float64), np.asarray(val, dtype=np.float64),
+                                   rtol=1e-12, atol=1e-14, err_msg=f"{case}: {key}")
