@@ -395,3 +395,36 @@ def test_measurement_aids(ha, torch):
         ha.ha_measure_mfma_rate(small)
     with pytest.raises(ha.HyperAttnError):
         ha.ha_measure_hbm_rate(small)
+
+
+def test_diagnostics_against_dense_definitions(ha, torch):
+    """alpha, ||D^-1 A||_op and kappa as diagnostics.py obtains them from the library's entry
+    points, against their definitions evaluated densely in fp64 (Lemma 1) at a small size."""
+    import diagnostics
+    print("diagnostics", flush=True)
+    cfg = dict(B=1, H=2, n=768, d=64, dtype="bf16", law="iid", b=64, m=32, r=5, causal=0, n_min=4096, seed=0)
+    Q, K, V = synth_inputs.make_qkv(cfg, seed=21)
+    tq, tk, tv = (to_device(x, "bf16") for x in (Q, K, V))
+    _, lse_e = ha.exact_attn_forward(tq, tk, tv, causal=False)
+    alpha = diagnostics.alpha_of(torch, ha, tq, tk, lse_e).cpu().numpy()
+    p_op = diagnostics.softmax_op_norm(torch, ha, tq, tk, lse_e, False, 25).cpu().numpy()
+    _, lse_b = ha.hyperattn_forward(tq, tk, tv, cfg["b"], 0, cfg["r"])
+    kappa, _ = diagnostics.kappa_of(torch, lse_e, lse_b)
+    stages = {}
+    orc.hyperattn_forward(Q, K, V, b=cfg["b"], m=0, r=cfg["r"], causal=False, stages=stages)
+    for hd in range(2):
+        S = Q[0, hd].astype(np.float64) @ K[0, hd].astype(np.float64).T
+        P = np.exp(S - S.max(axis=1, keepdims=True))
+        D = P.sum(axis=1, keepdims=True)
+        P /= D
+        a_ref = cfg["n"] * (P ** 2).sum(axis=0).max()
+        s_ref = np.linalg.svd(P, compute_uv=False)[0]
+        parts = stages["parts"][hd]
+        mask = (parts["pos_q"][:, None] // cfg["b"]) == (parts["pos_k"][None, :] // cfg["b"])
+        unmasked = np.where(mask, 0.0, np.exp(S)).sum(axis=1)
+        k_ref = unmasked.max() / unmasked.min()
+        print(f"  head {hd}: alpha {alpha[hd]:.3f} vs {a_ref:.3f}; ||P|| {p_op[hd]:.4f} vs {s_ref:.4f}; "
+              f"kappa {float(kappa[hd]):.3f} vs {k_ref:.3f}", flush=True)
+        assert abs(alpha[hd] - a_ref) <= 0.03 * a_ref          # bf16 weights squared: about 1 %
+        assert abs(p_op[hd] - s_ref) <= 0.02 * s_ref
+        assert abs(float(kappa[hd]) - k_ref) <= 0.05 * k_ref
