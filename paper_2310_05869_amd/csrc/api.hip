@@ -1,5 +1,5 @@
 // extern "C" entry points of libhyperattn: argument validation, workspace
-// layout and the launch sequence of a forward call.  Everything here is host
+// layouts and the launch sequences of a forward and of a backward call.  Everything here is host
 // code; it enqueues kernels on the caller's stream and returns.
 //
 // Launch sequence of hyperattn_forward (Algorithm 3 in its Section 4 form;
@@ -10,9 +10,19 @@
 //   seg_sort    all nodes of all levels, Q and K, in one launch
 //   attention   all nodes of all levels in one launch (block part + sampled
 //               residual, shared normaliser); unmasked problem: final output;
-//               causal: fp32 partial results per level
+//               causal: partial results per level, in the tensors' dtype
 //   base case   causal only: exact causal attention on the n_min diagonal
 //               blocks, merging the partial results of every level per row
+//
+// Launch sequence of hyperattn_backward (gradients of the above with the random
+// draws held fixed; every (query, key) pair that occurs contributes on its own,
+// given the final log row sums and delta = <dO, O>):
+//   delta       row dots of dO and the forward's output
+//   dQ          node pass (query tiles over their key lists), then the base-case
+//               pass, which adds the node rows and writes dQ
+//   dK, dV      block keys of every node; sampled keys of every node (partial
+//               sums per query chunk, reduced in order); then the base-case
+//               pass, which adds the per-level rows and writes dK, dV
 #include <cmath>
 #include <cstring>
 

@@ -519,15 +519,8 @@ static int launch_bwd_one(const BwdArgs& a, int grid, hipStream_t st) {
   if (grid <= 0) return HA_OK;
   size_t lds = bwd_lds_bytes<D>(a.f.g, MODE);
   if (lds < (size_t)4 * BwdLds<D>::EP_WAVE) lds = (size_t)4 * BwdLds<D>::EP_WAVE;
-  static bool configured = false;  // per instantiation
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_kernel<D, MODE, WHAT>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
-      (void)hipGetLastError();
-      return HA_ERR_LAUNCH;
-    }
-    configured = true;
-  }
+  static std::atomic<uint64_t> lds_set{0};  // per instantiation: devices on which the LDS limit is raised
+  if (allow_full_lds(reinterpret_cast<const void*>(&attn_bwd_kernel<D, MODE, WHAT>), lds_set) != HA_OK) return HA_ERR_LAUNCH;
   hipLaunchKernelGGL((attn_bwd_kernel<D, MODE, WHAT>), dim3((unsigned)grid), dim3(kBNT), lds, st, a);
   return check_launch();
 }

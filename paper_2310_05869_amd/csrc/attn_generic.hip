@@ -185,15 +185,8 @@ __global__ __launch_bounds__(kGQT) void attn_generic_kernel(AttnArgs a) {
 template <typename T, int D, int MODE>
 static int launch_generic_one(const AttnArgs& a, int grid, hipStream_t st) {
   const size_t lds = generic_lds_bytes(D, a.g.b, a.g.m, MODE);
-  static bool configured = false;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_generic_kernel<T, D, MODE>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
-      (void)hipGetLastError();
-      return HA_ERR_LAUNCH;
-    }
-    configured = true;
-  }
+  static std::atomic<uint64_t> lds_set{0};  // per instantiation: devices on which the LDS limit is raised
+  if (allow_full_lds(reinterpret_cast<const void*>(&attn_generic_kernel<T, D, MODE>), lds_set) != HA_OK) return HA_ERR_LAUNCH;
   hipLaunchKernelGGL((attn_generic_kernel<T, D, MODE>), dim3((unsigned)grid), dim3(kGQT), lds, st, a);
   return check_launch();
 }

@@ -600,15 +600,8 @@ static int launch_one(const AttnArgs& a, hipStream_t st) {
   if (grid <= 0) return HA_OK;
   size_t lds = mfma_lds_bytes<D>(a.g.b, a.g.m, MODE);
   if (lds < (size_t)NW * EpLds<D>::WAVE) lds = (size_t)NW * EpLds<D>::WAVE;
-  static bool configured = false;  // per instantiation
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<D, MODE, NW>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
-      (void)hipGetLastError();
-      return HA_ERR_LAUNCH;
-    }
-    configured = true;
-  }
+  static std::atomic<uint64_t> lds_set{0};  // per instantiation: devices on which the LDS limit is raised
+  if (allow_full_lds(reinterpret_cast<const void*>(&attn_mfma_kernel<D, MODE, NW>), lds_set) != HA_OK) return HA_ERR_LAUNCH;
   hipLaunchKernelGGL((attn_mfma_kernel<D, MODE, NW>), dim3((unsigned)grid), dim3(64 * NW), lds, st, a);
   return check_launch();
 }

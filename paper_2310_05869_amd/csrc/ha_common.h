@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "hyperattn.h"
 
 namespace ha {
@@ -128,5 +130,21 @@ int launch_merge_unpermute(const float* o_b, const float* lse_b, const float* o_
                            hipStream_t st);
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? HA_OK : HA_ERR_LAUNCH; }
+
+// Lets kernel `fn` use up to 160 KiB of dynamic LDS on the current device.  The
+// attribute is per device; `done` (one per kernel instantiation) remembers the
+// devices already set, so concurrent callers and several devices are both fine.
+inline int allow_full_lds(const void* fn, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return HA_ERR_LAUNCH;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (dev < 64 && (done.load(std::memory_order_acquire) & bit)) return HA_OK;
+  if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
+    (void)hipGetLastError();
+    return HA_ERR_LAUNCH;
+  }
+  if (dev < 64) done.fetch_or(bit, std::memory_order_release);
+  return HA_OK;
+}
 
 }  // namespace ha
