@@ -84,13 +84,14 @@ typedef struct {
  *   samples           int32  [total_nodes][m]         l_1..l_m of each node, heap order (level l node j -> 2^l - 1 + j)
  *   samp_blk          int32  [B*H][total_nodes][m]    floor(pos_k[l_j] / b): the sorted block each sampled key falls in
  *   proj              float  [d][r]                   hyperplane matrix R
+ *   sort_hist         uint32 [chunks][256]            scratch of the sort: bucket counts per 4096-key chunk
  *   part_o            dtype  [levels][B*H][n_cov][d]   causal only: per-level partial outputs (normalised), in the tensors' dtype
  *   part_l            float  [levels][B*H][n_cov]      causal only: log of the per-level partial row sums
  */
 typedef struct {
   int32_t levels, total_nodes;
   int64_t n_cov;
-  size_t codes_q, codes_k, perm_q, perm_k, pos_k, samples, samp_blk, proj, part_o, part_l;
+  size_t codes_q, codes_k, perm_q, perm_k, pos_k, samples, samp_blk, proj, sort_hist, part_o, part_l;
   size_t total_bytes;
 } ha_ws_layout;
 

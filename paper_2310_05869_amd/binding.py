@@ -31,7 +31,8 @@ class HaParams(ctypes.Structure):
 class HaWsLayout(ctypes.Structure):
     _fields_ = [("levels", c_int32), ("total_nodes", c_int32), ("n_cov", c_int64),
                 ("codes_q", c_size_t), ("codes_k", c_size_t), ("perm_q", c_size_t), ("perm_k", c_size_t),
-                ("pos_k", c_size_t), ("samples", c_size_t), ("samp_blk", c_size_t), ("proj", c_size_t), ("part_o", c_size_t),
+                ("pos_k", c_size_t), ("samples", c_size_t), ("samp_blk", c_size_t), ("proj", c_size_t), ("sort_hist", c_size_t),
+                ("part_o", c_size_t),
                 ("part_l", c_size_t), ("total_bytes", c_size_t)]
 
 

@@ -105,6 +105,7 @@ static void fill_layout(const Geometry& g, ha_ws_layout* l) {
   l->samples = take((size_t)g.total_nodes * g.m * 4);
   l->samp_blk = take((size_t)g.BH * g.total_nodes * g.m * 4);
   l->proj = take((size_t)g.d * g.r * 4);
+  l->sort_hist = take((size_t)seg_sort_chunks(g) * 256 * 4);
   const bool partials = g.causal && g.levels > 0;
   l->part_o = take(partials ? cov * g.d * (g.dtype == HA_BF16 ? 2 : 4) : 0);
   l->part_l = take(partials ? cov * 4 : 0);
@@ -176,7 +177,8 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
     rc = launch_lsh_hash(K, codes_k, (int64_t)g.BH * g.n, g.d, g.dtype, proj, g.r, st);
     if (rc != HA_OK) return rc;
     mark(2);
-    rc = launch_seg_sort_nodes(codes_q, codes_k, perm_q, perm_k, pos_k, g.m > 0 ? samples : nullptr, samp_blk, g, st);
+    rc = launch_seg_sort_nodes(codes_q, codes_k, perm_q, perm_k, pos_k, g.m > 0 ? samples : nullptr, samp_blk,
+                               (uint32_t*)(base + lay.sort_hist), g, st);
     if (rc != HA_OK) return rc;
     mark(3);
 

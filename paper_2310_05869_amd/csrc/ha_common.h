@@ -115,8 +115,9 @@ int launch_lsh_hash(const void* X, uint8_t* codes, int64_t rows, int d, int dtyp
 int launch_lsh_hash_mfma(const void* X, uint8_t* codes, int64_t rows, int d, const float* R_dev, int r,
                          hipStream_t st);
 int launch_seg_sort_nodes(const uint8_t* codes_q, const uint8_t* codes_k, int32_t* perm_q, int32_t* perm_k,
-                          int32_t* pos_k, const int32_t* samples, int32_t* samp_blk, const Geometry& g,
-                          hipStream_t st);
+                          int32_t* pos_k, const int32_t* samples, int32_t* samp_blk, uint32_t* chunk_hist,
+                          const Geometry& g, hipStream_t st);
+int64_t seg_sort_chunks(const Geometry& g);  // rows of 256 counters the chunked sort needs
 int launch_seg_sort_flat(const uint8_t* codes, int32_t* perm, int32_t* pos, int n_seg, int seg_len,
                          hipStream_t st);
 int launch_prep(float* R_ws, const float* R_dev, const uint16_t* R_bf16_host, int32_t* samples_ws,
