@@ -428,3 +428,44 @@ def test_diagnostics_against_dense_definitions(ha, torch):
         assert abs(alpha[hd] - a_ref) <= 0.03 * a_ref          # bf16 weights squared: about 1 %
         assert abs(p_op[hd] - s_ref) <= 0.02 * s_ref
         assert abs(float(kappa[hd]) - k_ref) <= 0.05 * k_ref
+
+
+def test_forward_on_a_side_stream_and_under_graph_capture(ha, torch):
+    """The library only enqueues on the caller's stream and allocates nothing, so a
+    forward call can run on any stream and be captured into a HIP graph.  Replays
+    (with eager work and synchronisations between them) must reproduce the eager
+    result bit for bit."""
+    print("side stream / graph capture", flush=True)
+    cfg = dict(B=1, H=2, n=2048, d=128, dtype="bf16", law="iid", b=128, m=64, r=7, causal=1, n_min=512, seed=4)
+    Q, K, V = (to_device(x, "bf16") for x in synth_inputs.make_qkv(cfg, seed=31))
+    shape = ha.make_shape(1, 2, 2048, 128, ha.HA_BF16)
+    params = ha.make_params(128, 64, 7, True, 512, 4)
+    ws = ha.alloc_workspace(shape, params)
+    kw = dict(causal=True, n_min=512, seed=4, workspace=ws)
+    ref_out, ref_lse = ha.hyperattn_forward(Q, K, V, 128, 64, 7, **kw)
+    torch.cuda.synchronize()
+    ref_out, ref_lse = ref_out.clone(), ref_lse.clone()
+
+    side = torch.cuda.Stream()
+    out = torch.zeros_like(Q)
+    lse = torch.zeros_like(ref_lse)
+    with torch.cuda.stream(side):
+        ha.hyperattn_forward(Q, K, V, 128, 64, 7, out=out, lse=lse, **kw)
+    side.synchronize()
+    assert torch.equal(out.view(torch.int16), ref_out.view(torch.int16)) and torch.equal(lse, ref_lse)
+
+    graph = torch.cuda.CUDAGraph()
+    out.zero_()
+    lse.zero_()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        ha.hyperattn_forward(Q, K, V, 128, 64, 7, out=out, lse=lse, **kw)
+    for rep in range(3):
+        out.zero_()
+        lse.zero_()
+        ws.zero_()                       # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), ref_out.view(torch.int16)), f"replay {rep}"
+        assert torch.equal(lse, ref_lse), f"replay {rep}"
