@@ -189,3 +189,24 @@ def test_backward_full_size_sampled_head(ha, torch, name):
     for got, r_, what in zip(grads, ref, ("dQ", "dK", "dV")):
         _assert_grad_close(to_host(got[0, :1])[None], r_, what)
         assert torch.isfinite(got.float()).all()
+
+
+@pytest.mark.parametrize("n,n_min,b,m,causal", [(64, 4096, 1, 4, 0),      # blocks of one key
+                                                (128, 8, 8, 20, 1),       # more samples than keys in the deep nodes
+                                                (192, 4096, 96, 7, 0),    # block not a multiple of 64, odd m
+                                                (96, 4096, 96, 96, 0)])   # a single block
+def test_backward_degenerate_shapes(ha, torch, n, n_min, b, m, causal):
+    print(f"backward degenerate n={n} n_min={n_min} b={b} m={m} causal={causal}", flush=True)
+    cfg = dict(B=1, H=2, n=n, d=64, dtype="bf16", law="iid", b=b, m=m, r=4, causal=causal, n_min=n_min, seed=9)
+    _run_case(ha, torch, cfg)
+
+
+def test_backward_of_nothing(ha, torch):
+    """Empty batches and empty sequences are accepted and touch nothing."""
+    print("backward empty", flush=True)
+    for shp in ((0, 2, 256, 64), (1, 2, 0, 64)):
+        q = torch.zeros(shp, dtype=torch.bfloat16, device="cuda")
+        lse = torch.zeros(shp[:3], dtype=torch.float32, device="cuda")
+        ws = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+        grads = ha.hyperattn_backward(q, q, q, q, lse, q, 64, 16, 7, fwd_workspace=ws, bwd_workspace=ws.clone())
+        assert all(g.shape == q.shape for g in grads)
