@@ -10,8 +10,9 @@ operand: 2^-9; delta_i built from the bf16 output: 2^-9), the terms' errors are
 independent, and the result is rounded to bf16 once more.  So the error of a
 tensor is about 2^-9 .. 2^-8 of its size in the root-mean-square sense and a
 few times that at its worst element:
-    ||got - ref||_F <= 4e-3 ||ref||_F   and   max|got - ref| <= 1e-2 max|ref|
-(measured: 2.3e-3 .. 2.6e-3 and 2e-3 .. 5e-3; rounding the fp64 result to bf16 alone gives 2.3e-3).
+    ||got - ref||_F <= 5e-3 ||ref||_F   and   max|got - ref| <= 1e-2 max|ref|
+(measured: 2.3e-3 .. 2.6e-3 and 2e-3 .. 5e-3 when a row has hundreds of keys, up to 3.3e-3 and 7e-3 when it has
+five and the operand roundings do not average out; rounding the fp64 result to bf16 alone gives 2.3e-3).
 A dropped term, a wrong mask, sign or weight moves both by O(1)."""
 import numpy as np
 import pytest
@@ -22,7 +23,7 @@ from ha_testutil import compare_codes, have_gpu, to_device, to_host
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not have_gpu(), reason="needs a GPU")]
 
-FRO_TOL = 4e-3
+FRO_TOL = 5e-3
 MAX_TOL = 1e-2
 
 
