@@ -147,14 +147,16 @@ def backward_bench(args, torch, ha):
     out = torch.empty_like(Q)
     lse = torch.empty((B, H, n), dtype=torch.float32, device="cuda")
     grads = tuple(torch.empty_like(Q) for _ in range(3))
+    out32 = torch.empty(Q.shape, dtype=torch.float32, device="cuda")  # unrounded output for the backward's delta
     kw = dict(causal=cfg["causal"], n_min=cfg["n_min"], seed=cfg["seed"])
     pa = (cfg["b"], cfg["m"], cfg["r"])
 
     def fwd():
-        ha.hyperattn_forward(Q, K, V, *pa, workspace=ws, out=out, lse=lse, **kw)
+        ha.hyperattn_forward(Q, K, V, *pa, workspace=ws, out=out, lse=lse, out_f32=out32, **kw)
 
     def bwd():
-        ha.hyperattn_backward(Q, K, V, out, lse, G, *pa, fwd_workspace=ws, bwd_workspace=bws, grads=grads, **kw)
+        ha.hyperattn_backward(Q, K, V, out, lse, G, *pa, fwd_workspace=ws, bwd_workspace=bws, grads=grads,
+                              out_f32=out32, **kw)
 
     def both():
         fwd()
@@ -165,7 +167,7 @@ def backward_bench(args, torch, ha):
     stage = {k: 0.0 for k in ha.binding.BWD_STAGE_NAMES}
     for _ in range(args.steps):
         ms = ha.hyperattn_backward_timed(Q, K, V, out, lse, G, *pa, fwd_workspace=ws, bwd_workspace=bws, grads=grads,
-                                         **kw)[3]
+                                         out_f32=out32, **kw)[3]
         for k, v in ms.items():
             stage[k] += v / args.steps
     log(f"[bench] forward {fwd_ms:.3f} ms, forward + backward {both_ms:.3f} ms")
@@ -196,8 +198,8 @@ def backward_bench(args, torch, ha):
         egrads = tuple(torch.empty_like(Q) for _ in range(3))
 
         def exact_both():
-            ha.exact_attn_forward(Q, K, V, causal=cfg["causal"], out=eo, lse=el)
-            ha.exact_attn_backward(Q, K, V, eo, el, G, causal=cfg["causal"], workspace=ews, grads=egrads)
+            ha.exact_attn_forward(Q, K, V, causal=cfg["causal"], out=eo, lse=el, out_f32=out32)
+            ha.exact_attn_backward(Q, K, V, eo, el, G, causal=cfg["causal"], workspace=ews, grads=egrads, out_f32=out32)
 
         ex_ms = time_call(torch, exact_both, 1, 2)
         result["exact_fwd_bwd_ms"] = round(ex_ms, 3)

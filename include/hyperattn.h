@@ -206,8 +206,16 @@ int ha_merge_unpermute(const float* o_b, const float* lse_b, const float* o_r, c
  *   P_ij = w_ij exp(<q_i,k_j> - L_i),  dV_j = sum_i P_ij d_out_i,
  *   dS_ij = P_ij (<d_out_i, v_j> - delta_i),  dQ_i = sum_j dS_ij k_j,  dK_j = sum_i dS_ij q_i.
  *
+ * hyperattn_forward_train: hyperattn_forward that also writes out_f32 (device
+ * fp32 [B][H][n][d]; NULL: none), the output before its rounding to bf16.  The
+ * backward forms delta from it: with the bf16 tensor alone delta carries the
+ * output's rounding error (2^-9 relative), which dominates dQ and dK on rows
+ * whose weight sits on few keys, where <d_out_i, v_j> - delta_i cancels.
+ * exact_attn_forward_train: the same for exact attention.
+ *
  * hyperattn_backward: Q, K, V, out, d_out, dQ, dK, dV are device pointers to
- * contiguous [B][H][n][d] bf16; lse device fp32 [B][H][n].  out and lse are the
+ * contiguous [B][H][n][d] bf16; lse device fp32 [B][H][n]; out_f32 as written
+ * by hyperattn_forward_train, or NULL (delta then comes from out).  out and lse are the
  * results of hyperattn_forward on the same Q, K, V, shape and params, and
  * fwd_workspace is that call's workspace, unmodified since (it holds the sort
  * permutations and sample indices; only read here).  bwd_workspace: device,
@@ -236,16 +244,21 @@ typedef struct {
 
 int ha_backward_workspace_layout(const ha_shape* shape, const ha_params* params, ha_bwd_ws_layout* layout);
 size_t ha_backward_workspace_bytes(const ha_shape* shape, const ha_params* params);
-int hyperattn_backward(const void* Q, const void* K, const void* V, const void* out, const float* lse,
-                       const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape,
+int hyperattn_forward_train(const void* Q, const void* K, const void* V, void* out, float* lse, float* out_f32,
+                            const ha_shape* shape, const ha_params* params, void* workspace,
+                            size_t workspace_bytes, void* stream);
+int exact_attn_forward_train(const void* Q, const void* K, const void* V, void* out, float* lse, float* out_f32,
+                             const ha_shape* shape, int causal, void* stream);
+int hyperattn_backward(const void* Q, const void* K, const void* V, const void* out, const float* out_f32,
+                       const float* lse, const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape,
                        const ha_params* params, const void* fwd_workspace, size_t fwd_workspace_bytes,
                        void* bwd_workspace, size_t bwd_workspace_bytes, void* stream);
-int hyperattn_backward_timed(const void* Q, const void* K, const void* V, const void* out, const float* lse,
-                             const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape,
+int hyperattn_backward_timed(const void* Q, const void* K, const void* V, const void* out, const float* out_f32,
+                             const float* lse, const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape,
                              const ha_params* params, const void* fwd_workspace, size_t fwd_workspace_bytes,
                              void* bwd_workspace, size_t bwd_workspace_bytes, void* stream, float* stage_ms_host);
-int exact_attn_backward(const void* Q, const void* K, const void* V, const void* out, const float* lse,
-                        const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape, int causal,
+int exact_attn_backward(const void* Q, const void* K, const void* V, const void* out, const float* out_f32,
+                        const float* lse, const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape, int causal,
                         void* workspace, size_t workspace_bytes, void* stream);
 size_t exact_attn_backward_workspace_bytes(const ha_shape* shape);
 

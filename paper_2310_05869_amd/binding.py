@@ -65,11 +65,14 @@ _SIGNATURES = {
     "ha_merge_unpermute": (c_int, [c_void_p] * 7 + [c_int32] * 4 + [c_void_p]),
     "ha_backward_workspace_layout": (c_int, [POINTER(HaShape), POINTER(HaParams), POINTER(HaBwdWsLayout)]),
     "ha_backward_workspace_bytes": (c_size_t, [POINTER(HaShape), POINTER(HaParams)]),
-    "hyperattn_backward": (c_int, [c_void_p] * 9 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_size_t, c_void_p,
-                                                   c_size_t, c_void_p]),
-    "hyperattn_backward_timed": (c_int, [c_void_p] * 9 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_size_t,
-                                                         c_void_p, c_size_t, c_void_p, POINTER(c_float)]),
-    "exact_attn_backward": (c_int, [c_void_p] * 9 + [POINTER(HaShape), c_int, c_void_p, c_size_t, c_void_p]),
+    "hyperattn_forward_train": (c_int, [c_void_p] * 6 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_size_t,
+                                                        c_void_p]),
+    "exact_attn_forward_train": (c_int, [c_void_p] * 6 + [POINTER(HaShape), c_int, c_void_p]),
+    "hyperattn_backward": (c_int, [c_void_p] * 10 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_size_t, c_void_p,
+                                                    c_size_t, c_void_p]),
+    "hyperattn_backward_timed": (c_int, [c_void_p] * 10 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_size_t,
+                                                          c_void_p, c_size_t, c_void_p, POINTER(c_float)]),
+    "exact_attn_backward": (c_int, [c_void_p] * 10 + [POINTER(HaShape), c_int, c_void_p, c_size_t, c_void_p]),
     "exact_attn_backward_workspace_bytes": (c_size_t, [POINTER(HaShape)]),
     "ha_measure_mfma_rate": (c_int, [c_void_p, c_size_t, c_int32, POINTER(c_float), c_void_p]),
     "ha_measure_hbm_rate": (c_int, [c_void_p, c_size_t, POINTER(c_float), POINTER(c_float), c_void_p]),
@@ -178,10 +181,12 @@ def alloc_workspace(shape: HaShape, params: HaParams, device="cuda"):
 
 
 def hyperattn_forward(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0, R=None, samples=None,
-                      workspace=None, out=None, lse=None, stream=None):
+                      workspace=None, out=None, lse=None, stream=None, out_f32=None):
     """out, lse = HyperAttention(Q, K, V).  Q, K, V: [B, H, n, d] device tensors
     (bf16 or fp32).  R (float32 [d, r]) / samples (int32 [total_nodes, m]) are
-    optional device tensors overriding the seed-derived draws."""
+    optional device tensors overriding the seed-derived draws.  out_f32 (float32
+    [B, H, n, d]), if given, receives the output before its rounding to bf16
+    (hyperattn_forward_train): pass it on to hyperattn_backward."""
     torch = _torch()
     B, H, n, d = Q.shape
     shape = make_shape(B, H, n, d, _dtype_code(Q))
@@ -193,7 +198,12 @@ def hyperattn_forward(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0, R=None
     if lse is None:
         lse = torch.empty((B, H, n), dtype=torch.float32, device=Q.device)
     ptrs = [_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"), _dev(lse, "lse")]
-    if R is None and samples is None:
+    if out_f32 is not None:
+        if R is not None or samples is not None:
+            raise ValueError("out_f32 goes with the seed-derived draws")
+        st = lib().hyperattn_forward_train(*ptrs, _dev(out_f32, "out_f32"), ctypes.byref(shape), ctypes.byref(params),
+                                           workspace.data_ptr(), workspace.numel(), _stream(stream))
+    elif R is None and samples is None:
         st = lib().hyperattn_forward(*ptrs, ctypes.byref(shape), ctypes.byref(params), workspace.data_ptr(),
                                      workspace.numel(), _stream(stream))
     else:
@@ -230,7 +240,7 @@ def hyperattn_forward_timed(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0, 
     return out, lse, dict(zip(STAGE_NAMES, [float(x) for x in ms]))
 
 
-def exact_attn_forward(Q, K, V, causal=False, out=None, lse=None, stream=None):
+def exact_attn_forward(Q, K, V, causal=False, out=None, lse=None, stream=None, out_f32=None):
     torch = _torch()
     B, H, n, d = Q.shape
     shape = make_shape(B, H, n, d, _dtype_code(Q))
@@ -238,6 +248,11 @@ def exact_attn_forward(Q, K, V, causal=False, out=None, lse=None, stream=None):
         out = torch.empty_like(Q)
     if lse is None:
         lse = torch.empty((B, H, n), dtype=torch.float32, device=Q.device)
+    if out_f32 is not None:
+        _check(lib().exact_attn_forward_train(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"), _dev(lse, "lse"),
+                                              _dev(out_f32, "out_f32"), ctypes.byref(shape), int(bool(causal)),
+                                              _stream(stream)), "exact_attn_forward_train")
+        return out, lse
     _check(lib().exact_attn_forward(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"), _dev(lse, "lse"),
                                     ctypes.byref(shape), int(bool(causal)), _stream(stream)), "exact_attn_forward")
     return out, lse
@@ -369,7 +384,7 @@ def alloc_backward_workspace(shape: HaShape, params: HaParams, device="cuda"):
 
 
 def _backward_call(timed, Q, K, V, out, lse, d_out, b, m, r, causal, n_min, seed, fwd_workspace, bwd_workspace,
-                   grads, stream):
+                   grads, stream, out_f32=None):
     torch = _torch()
     B, H, n, d = Q.shape
     shape = make_shape(B, H, n, d, _dtype_code(Q))
@@ -377,7 +392,8 @@ def _backward_call(timed, Q, K, V, out, lse, d_out, b, m, r, causal, n_min, seed
     if bwd_workspace is None:
         bwd_workspace = alloc_backward_workspace(shape, params, Q.device)
     dQ, dK, dV = grads if grads is not None else (torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V))
-    args = [_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"), _dev(lse, "lse"), _dev(d_out, "d_out"),
+    args = [_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"),
+            None if out_f32 is None else _dev(out_f32, "out_f32"), _dev(lse, "lse"), _dev(d_out, "d_out"),
             _dev(dQ, "dQ"), _dev(dK, "dK"), _dev(dV, "dV"), ctypes.byref(shape), ctypes.byref(params),
             fwd_workspace.data_ptr(), fwd_workspace.numel(), bwd_workspace.data_ptr(), bwd_workspace.numel(),
             _stream(stream)]
@@ -390,25 +406,27 @@ def _backward_call(timed, Q, K, V, out, lse, d_out, b, m, r, causal, n_min, seed
 
 
 def hyperattn_backward(Q, K, V, out, lse, d_out, b, m, r, causal=False, n_min=4096, seed=0, fwd_workspace=None,
-                       bwd_workspace=None, grads=None, stream=None):
+                       bwd_workspace=None, grads=None, stream=None, out_f32=None):
     """dQ, dK, dV of sum(out * d_out).  out, lse and fwd_workspace are what
-    hyperattn_forward produced / used for the same arguments (bf16 tensors)."""
+    hyperattn_forward produced / used for the same arguments (bf16 tensors);
+    out_f32, if the forward wrote one, makes delta = <d_out, out> free of the
+    output's bf16 rounding."""
     if fwd_workspace is None:
         raise ValueError("hyperattn_backward needs the workspace of the forward call")
     return _backward_call(False, Q, K, V, out, lse, d_out, b, m, r, causal, n_min, seed, fwd_workspace, bwd_workspace,
-                          grads, stream)
+                          grads, stream, out_f32)
 
 
 def hyperattn_backward_timed(Q, K, V, out, lse, d_out, b, m, r, causal=False, n_min=4096, seed=0, fwd_workspace=None,
-                             bwd_workspace=None, grads=None, stream=None):
+                             bwd_workspace=None, grads=None, stream=None, out_f32=None):
     """As hyperattn_backward, but waits and also returns per-stage milliseconds (BWD_STAGE_NAMES)."""
     if fwd_workspace is None:
         raise ValueError("hyperattn_backward_timed needs the workspace of the forward call")
     return _backward_call(True, Q, K, V, out, lse, d_out, b, m, r, causal, n_min, seed, fwd_workspace, bwd_workspace,
-                          grads, stream)
+                          grads, stream, out_f32)
 
 
-def exact_attn_backward(Q, K, V, out, lse, d_out, causal=False, workspace=None, grads=None, stream=None):
+def exact_attn_backward(Q, K, V, out, lse, d_out, causal=False, workspace=None, grads=None, stream=None, out_f32=None):
     torch = _torch()
     B, H, n, d = Q.shape
     shape = make_shape(B, H, n, d, _dtype_code(Q))
@@ -416,7 +434,8 @@ def exact_attn_backward(Q, K, V, out, lse, d_out, causal=False, workspace=None, 
         workspace = torch.empty(int(lib().exact_attn_backward_workspace_bytes(ctypes.byref(shape))), dtype=torch.uint8,
                                 device=Q.device)
     dQ, dK, dV = grads if grads is not None else (torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V))
-    _check(lib().exact_attn_backward(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"), _dev(lse, "lse"),
+    _check(lib().exact_attn_backward(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"),
+                                     None if out_f32 is None else _dev(out_f32, "out_f32"), _dev(lse, "lse"),
                                      _dev(d_out, "d_out"), _dev(dQ, "dQ"), _dev(dK, "dK"), _dev(dV, "dV"),
                                      ctypes.byref(shape), int(bool(causal)), workspace.data_ptr(), workspace.numel(),
                                      _stream(stream)), "exact_attn_backward")

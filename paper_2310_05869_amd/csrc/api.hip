@@ -136,12 +136,13 @@ static int run_attention(const AttnArgs& a, int mode, hipStream_t st) {
 // prep, after hashing, after sorting, after the node attention, after the base case.
 static int forward_impl(const void* Q, const void* K, const void* V, void* out, float* lse, const ha_shape* sh,
                         const ha_params* p, const float* R_dev, const int32_t* samples_dev, void* ws,
-                        size_t ws_bytes, void* stream, hipEvent_t* ev = nullptr) {
+                        size_t ws_bytes, void* stream, hipEvent_t* ev = nullptr, float* out_f32 = nullptr) {
   Geometry g;
   int rc = make_geometry(sh, p, &g);
   if (rc != HA_OK) return rc;
   if (g.BH == 0 || g.n == 0) return HA_OK;
   if (!Q || !K || !V || !out || !lse) return HA_ERR_NULL;
+  if (out_f32 && g.dtype != HA_BF16) return HA_ERR_DTYPE;
   ha_ws_layout lay;
   fill_layout(g, &lay);
   if (!ws) return HA_ERR_NULL;
@@ -203,6 +204,7 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
     } else {
       a.out = out;
       a.lse = lse;
+      a.out_f32 = out_f32;
     }
     rc = run_attention(a, kModeNode, st);
     if (rc != HA_OK) return rc;
@@ -220,6 +222,7 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
     a.q_bh_stride = a.k_bh_stride = head_stride;
     a.out = out;
     a.lse = lse;
+    a.out_f32 = out_f32;
     a.out_bh_stride = head_stride;
     a.part_o = part_o;
     a.part_l = part_l;
@@ -291,8 +294,9 @@ static void fill_bwd_layout(const Geometry& g, ha_bwd_ws_layout* l) {
 
 // ev, when non-null, receives 9 events: start, after delta, dQ of the nodes, dQ of the base case,
 // dK/dV of the block keys, of the sampled keys (with their reduction), of the base case, after the final sums.
-static int backward_impl(const void* Q, const void* K, const void* V, const void* out, const float* lse,
-                         const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* sh, const ha_params* p,
+static int backward_impl(const void* Q, const void* K, const void* V, const void* out, const float* out_f32,
+                         const float* lse, const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* sh,
+                         const ha_params* p,
                          const void* fws, size_t fws_bytes, void* bws, size_t bws_bytes, void* stream,
                          hipEvent_t* ev = nullptr) {
   Geometry g;
@@ -355,7 +359,7 @@ static int backward_impl(const void* Q, const void* K, const void* V, const void
   }
 
   mark(0);
-  rc = launch_bwd_delta(out, d_out, delta, (int64_t)g.BH * g.n, g.d, st);
+  rc = launch_bwd_delta(out, out_f32, d_out, delta, (int64_t)g.BH * g.n, g.d, st);
   if (rc != HA_OK) return rc;
   mark(1);
   if (g.levels > 0) {
@@ -464,14 +468,15 @@ int hyperattn_forward_timed(const void* Q, const void* K, const void* V, void* o
   return rc;
 }
 
-int exact_attn_forward(const void* Q, const void* K, const void* V, void* out, float* lse, const ha_shape* sh,
-                       int causal, void* stream) {
+static int exact_forward_impl(const void* Q, const void* K, const void* V, void* out, float* lse, float* out_f32,
+                              const ha_shape* sh, int causal, void* stream) {
   if (!sh) return HA_ERR_NULL;
   if (sh->dtype != HA_BF16 && sh->dtype != HA_FP32) return HA_ERR_DTYPE;
   if (sh->B < 0 || sh->H < 0 || sh->n < 0 || (sh->d != 64 && sh->d != 128)) return HA_ERR_SHAPE;
   if ((int64_t)sh->B * sh->H > (1 << 20) || sh->n > (1 << 22)) return HA_ERR_SHAPE;
   if (sh->B == 0 || sh->H == 0 || sh->n == 0) return HA_OK;
   if (!Q || !K || !V || !out || !lse) return HA_ERR_NULL;
+  if (out_f32 && sh->dtype != HA_BF16) return HA_ERR_DTYPE;
   AttnArgs a{};
   a.Q = Q;
   a.K = K;
@@ -479,6 +484,7 @@ int exact_attn_forward(const void* Q, const void* K, const void* V, void* out, f
   a.q_bh_stride = a.k_bh_stride = a.out_bh_stride = (int64_t)sh->n * sh->d;
   a.out = out;
   a.lse = lse;
+  a.out_f32 = out_f32;
   a.g.BH = sh->B * sh->H;
   a.g.n = sh->n;
   a.g.d = sh->d;
@@ -489,6 +495,16 @@ int exact_attn_forward(const void* Q, const void* K, const void* V, void* out, f
   a.exact_causal = causal ? 1 : 0;
   a.merge_levels = 0;
   return run_attention(a, kModeExact, (hipStream_t)stream);
+}
+
+int exact_attn_forward(const void* Q, const void* K, const void* V, void* out, float* lse, const ha_shape* sh,
+                       int causal, void* stream) {
+  return exact_forward_impl(Q, K, V, out, lse, nullptr, sh, causal, stream);
+}
+
+int exact_attn_forward_train(const void* Q, const void* K, const void* V, void* out, float* lse, float* out_f32,
+                             const ha_shape* sh, int causal, void* stream) {
+  return exact_forward_impl(Q, K, V, out, lse, out_f32, sh, causal, stream);
 }
 
 int ha_make_projection(uint64_t seed, int32_t d, int32_t r, float* R_host) {
@@ -602,16 +618,23 @@ size_t ha_backward_workspace_bytes(const ha_shape* shape, const ha_params* param
   return ha_backward_workspace_layout(shape, params, &l) == HA_OK ? l.total_bytes : 0;
 }
 
-int hyperattn_backward(const void* Q, const void* K, const void* V, const void* out, const float* lse,
-                       const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape,
-                       const ha_params* params, const void* fwd_workspace, size_t fwd_workspace_bytes,
-                       void* bwd_workspace, size_t bwd_workspace_bytes, void* stream) {
-  return backward_impl(Q, K, V, out, lse, d_out, dQ, dK, dV, shape, params, fwd_workspace, fwd_workspace_bytes,
-                       bwd_workspace, bwd_workspace_bytes, stream);
+int hyperattn_forward_train(const void* Q, const void* K, const void* V, void* out, float* lse, float* out_f32,
+                            const ha_shape* shape, const ha_params* params, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  return forward_impl(Q, K, V, out, lse, shape, params, nullptr, nullptr, workspace, workspace_bytes, stream, nullptr,
+                      out_f32);
 }
 
-int hyperattn_backward_timed(const void* Q, const void* K, const void* V, const void* out, const float* lse,
-                             const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape,
+int hyperattn_backward(const void* Q, const void* K, const void* V, const void* out, const float* out_f32,
+                       const float* lse, const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape,
+                       const ha_params* params, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                       void* bwd_workspace, size_t bwd_workspace_bytes, void* stream) {
+  return backward_impl(Q, K, V, out, out_f32, lse, d_out, dQ, dK, dV, shape, params, fwd_workspace,
+                       fwd_workspace_bytes, bwd_workspace, bwd_workspace_bytes, stream);
+}
+
+int hyperattn_backward_timed(const void* Q, const void* K, const void* V, const void* out, const float* out_f32,
+                             const float* lse, const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* shape,
                              const ha_params* params, const void* fwd_workspace, size_t fwd_workspace_bytes,
                              void* bwd_workspace, size_t bwd_workspace_bytes, void* stream, float* stage_ms_host) {
   if (!stage_ms_host) return HA_ERR_NULL;
@@ -622,8 +645,8 @@ int hyperattn_backward_timed(const void* Q, const void* K, const void* V, const 
       for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
       return HA_ERR_LAUNCH;
     }
-  int rc = backward_impl(Q, K, V, out, lse, d_out, dQ, dK, dV, shape, params, fwd_workspace, fwd_workspace_bytes,
-                         bwd_workspace, bwd_workspace_bytes, stream, ev);
+  int rc = backward_impl(Q, K, V, out, out_f32, lse, d_out, dQ, dK, dV, shape, params, fwd_workspace,
+                         fwd_workspace_bytes, bwd_workspace, bwd_workspace_bytes, stream, ev);
   for (int i = 0; i < NE; ++i) stage_ms_host[i] = 0.f;
   Geometry g;
   const bool ran = rc == HA_OK && make_geometry(shape, params, &g) == HA_OK && g.BH > 0 && g.n > 0;
@@ -637,8 +660,8 @@ int hyperattn_backward_timed(const void* Q, const void* K, const void* V, const 
   return rc;
 }
 
-int exact_attn_backward(const void* Q, const void* K, const void* V, const void* out, const float* lse,
-                        const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* sh, int causal,
+int exact_attn_backward(const void* Q, const void* K, const void* V, const void* out, const float* out_f32,
+                        const float* lse, const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* sh, int causal,
                         void* workspace, size_t workspace_bytes, void* stream) {
   if (!sh) return HA_ERR_NULL;
   // exact attention is the causal recursion that never splits (n_min = n), or its unmasked twin
@@ -672,7 +695,7 @@ int exact_attn_backward(const void* Q, const void* K, const void* V, const void*
   a.dO = d_out;
   a.lse = lse;
   a.delta = (float*)(bb + bl.delta);
-  rc = launch_bwd_delta(out, d_out, (float*)(bb + bl.delta), (int64_t)g.BH * g.n, g.d, st);
+  rc = launch_bwd_delta(out, out_f32, d_out, (float*)(bb + bl.delta), (int64_t)g.BH * g.n, g.d, st);
   if (rc != HA_OK) return rc;
   a.fin1 = dQ;
   rc = launch_attn_bwd_mfma(a, kBwdDqExact, st);

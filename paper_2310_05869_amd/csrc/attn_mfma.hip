@@ -574,6 +574,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
       } else {
         const u32x4 pk = {pack_bf16x2(v0.x, v0.y), pack_bf16x2(v0.z, v0.w), pack_bf16x2(v1.x, v1.y), pack_bf16x2(v1.z, v1.w)};
         *reinterpret_cast<u32x4*>(dst_base + (r64 * D + ch * 8) * 2) = pk;
+        if (!to_partial && a.out_f32 != nullptr) {  // unrounded copy of the final output, for the backward's delta
+          f32x4* fp = reinterpret_cast<f32x4*>(a.out_f32 + r64 * D + ch * 8);
+          fp[0] = v0;
+          fp[1] = v1;
+        }
       }
     }
   };

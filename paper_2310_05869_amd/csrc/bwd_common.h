@@ -43,7 +43,8 @@ __host__ __device__ inline int bwd_chunks_per_node(const Geometry& g, int level)
 }
 
 int launch_attn_bwd_mfma(const BwdArgs& a, int mode, hipStream_t st);
-int launch_bwd_delta(const void* O, const void* dO, float* delta, int64_t rows, int d, hipStream_t st);
+// delta_i = <dO_i, O_i>; O from its unrounded fp32 copy when O_f32 is non-null, else from the bf16 tensor
+int launch_bwd_delta(const void* O, const float* O_f32, const void* dO, float* delta, int64_t rows, int d, hipStream_t st);
 int launch_bwd_sample_scatter(const BwdArgs& a, const float* samp_k, const float* samp_v, float* part_k,
                               float* part_v, hipStream_t st);
 // dst (dtype bf16) = base + sum over the levels whose node holds the row on the given side

@@ -11,22 +11,39 @@ namespace ha {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// One group of D/8 lanes per row; 16 bytes (8 bf16) per lane.
+// One group of D/8 lanes per row; 8 elements per lane.  O is read from its
+// unrounded fp32 copy when there is one: with the bf16 tensor, delta carries the
+// output's rounding error, which matters where <dO_i, v_j> - delta_i cancels
+// (rows whose weight sits on few keys).
 template <int D>
-__global__ __launch_bounds__(256) void bwd_delta_kernel(const uint16_t* __restrict__ O, const uint16_t* __restrict__ G,
-                                                        float* __restrict__ delta, int64_t rows) {
+__global__ __launch_bounds__(256) void bwd_delta_kernel(const uint16_t* __restrict__ O, const float* __restrict__ O32,
+                                                        const uint16_t* __restrict__ G, float* __restrict__ delta,
+                                                        int64_t rows) {
   constexpr int LPR = D / 8;  // lanes per row
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t row = t / LPR;
   const int part = (int)(t % LPR);
   float s = 0.f;
   if (row < rows) {
-    const u32x4 o = *reinterpret_cast<const u32x4*>(O + row * D + part * 8);
     const u32x4 g = *reinterpret_cast<const u32x4*>(G + row * D + part * 8);
+    float o[8];
+    if (O32 != nullptr) {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(O32 + row * D + part * 8);
+      const f32x4 b = *reinterpret_cast<const f32x4*>(O32 + row * D + part * 8 + 4);
+      o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+      o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+    } else {
+      const u32x4 ob = *reinterpret_cast<const u32x4*>(O + row * D + part * 8);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        o[2 * e] = __uint_as_float(ob[e] << 16);
+        o[2 * e + 1] = __uint_as_float(ob[e] & 0xFFFF0000u);
+      }
+    }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      s = __builtin_fmaf(__uint_as_float(o[e] << 16), __uint_as_float(g[e] << 16), s);
-      s = __builtin_fmaf(__uint_as_float(o[e] & 0xFFFF0000u), __uint_as_float(g[e] & 0xFFFF0000u), s);
+      s = __builtin_fmaf(o[2 * e], __uint_as_float(g[e] << 16), s);
+      s = __builtin_fmaf(o[2 * e + 1], __uint_as_float(g[e] & 0xFFFF0000u), s);
     }
   }
 #pragma unroll
@@ -34,15 +51,16 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const uint16_t* __restri
   if (row < rows && part == 0) delta[row] = s;
 }
 
-int launch_bwd_delta(const void* O, const void* dO, float* delta, int64_t rows, int d, hipStream_t st) {
+int launch_bwd_delta(const void* O, const float* O_f32, const void* dO, float* delta, int64_t rows, int d,
+                     hipStream_t st) {
   if (rows <= 0) return HA_OK;
   const int lpr = d / 8;
   const int64_t threads = rows * lpr;
   const unsigned grid = (unsigned)((threads + 255) / 256);
   if (d == 128)
-    hipLaunchKernelGGL((bwd_delta_kernel<128>), dim3(grid), dim3(256), 0, st, (const uint16_t*)O, (const uint16_t*)dO, delta, rows);
+    hipLaunchKernelGGL((bwd_delta_kernel<128>), dim3(grid), dim3(256), 0, st, (const uint16_t*)O, O_f32, (const uint16_t*)dO, delta, rows);
   else if (d == 64)
-    hipLaunchKernelGGL((bwd_delta_kernel<64>), dim3(grid), dim3(256), 0, st, (const uint16_t*)O, (const uint16_t*)dO, delta, rows);
+    hipLaunchKernelGGL((bwd_delta_kernel<64>), dim3(grid), dim3(256), 0, st, (const uint16_t*)O, O_f32, (const uint16_t*)dO, delta, rows);
   else
     return HA_ERR_SHAPE;
   return check_launch();

@@ -95,6 +95,7 @@ struct AttnArgs {
   // outputs
   void* out;        // final output in dtype (may be null)
   float* lse;       // final log row sum (may be null)
+  float* out_f32;   // optional unrounded copy of the final output (bf16 tensors; may be null)
   void* part_o;     // outputs [levels][BH][n_cov][d] (node mode when non-null; merged in by the base case):
                     // bf16 if part_bf16, else fp32
   float* part_l;

@@ -13,7 +13,20 @@ few times that at its worst element:
     ||got - ref||_F <= 5e-3 ||ref||_F   and   max|got - ref| <= 1e-2 max|ref|
 (measured: 2.3e-3 .. 2.6e-3 and 2e-3 .. 5e-3 when a row has hundreds of keys, up to 3.3e-3 and 7e-3 when it has
 five and the operand roundings do not average out; rounding the fp64 result to bf16 alone gives 2.3e-3).
-A dropped term, a wrong mask, sign or weight moves both by O(1)."""
+A dropped term, a wrong mask, sign or weight moves both by O(1).
+
+Peaked rows are the exception.  dS_ij = P_ij (<dO_i, v_j> - delta_i) with delta_i =
+<dO_i, O_i> is a difference that cancels when a row's weight sits on few keys, and delta
+inherits two errors of the forward: the rounding of the output to bf16 (avoided by
+hyperattn_forward_train's fp32 copy, used here) and the rounding of the softmax weights
+to bf16 as matrix operands (inherent to the forward; std of delta's error about
+2^-9/sqrt(3) * sqrt(sum_j P_ij^2 <dO_i,v_j>^2)).  dQ_i and dK_j pick that error up times
+sum_j P_ij k_j resp. q_i, with no small factor in front.  On the 64-centre mixture
+(scores up to +-250) dQ is off by 1.2e-2 in the Frobenius sense (2.6e-2 with delta from
+the bf16 output) and dK by 4e-3; that law is tested against 3e-2 / 5e-2, and the seeded
+random cases avoid the regime (no m in 1..15, whose sample weight s/m puts a row's
+weight on a handful of sampled keys).  dV carries no such difference and keeps the
+tight bound everywhere."""
 import numpy as np
 import pytest
 
@@ -40,13 +53,13 @@ def torch():
     return t
 
 
-def _assert_grad_close(got, ref, what):
+def _assert_grad_close(got, ref, what, fro_tol=FRO_TOL, max_tol=MAX_TOL):
     fro = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
     mx = np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30)
     print(f"  {what}: relative Frobenius error {fro:.2e}, worst element / max|ref| {mx:.2e}", flush=True)
     assert np.isfinite(got).all(), what
-    assert fro <= FRO_TOL, (what, fro)
-    assert mx <= MAX_TOL, (what, mx)
+    assert fro <= fro_tol, (what, fro)
+    assert mx <= max_tol, (what, mx)
 
 
 def _cotangent(shape, seed):
@@ -54,7 +67,12 @@ def _cotangent(shape, seed):
     return synth_inputs.round_to_bf16(g)
 
 
-def _run_case(ha, torch, cfg, seed_data=77):
+# Peaked rows (the mixture law): see the module docstring.
+PEAKED_FRO_TOL = 3e-2
+PEAKED_MAX_TOL = 5e-2
+
+
+def _run_case(ha, torch, cfg, seed_data=77, peaked=False):
     B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
     Q, K, V = synth_inputs.make_qkv(cfg, seed=seed_data)
     G = _cotangent(Q.shape, seed_data + 1)
@@ -63,8 +81,11 @@ def _run_case(ha, torch, cfg, seed_data=77):
     params = ha.make_params(cfg["b"], cfg["m"], cfg["r"], cfg["causal"], cfg["n_min"], cfg["seed"])
     ws = ha.alloc_workspace(shape, params)
     kw = dict(causal=cfg["causal"], n_min=cfg["n_min"], seed=cfg["seed"])
-    out, lse = ha.hyperattn_forward(dQ_, dK_, dV_, cfg["b"], cfg["m"], cfg["r"], workspace=ws, **kw)
-    gq, gk, gv = ha.hyperattn_backward(dQ_, dK_, dV_, out, lse, dG_, cfg["b"], cfg["m"], cfg["r"], fwd_workspace=ws, **kw)
+    out32 = torch.empty(dQ_.shape, dtype=torch.float32, device="cuda")
+    out, lse = ha.hyperattn_forward(dQ_, dK_, dV_, cfg["b"], cfg["m"], cfg["r"], workspace=ws, out_f32=out32, **kw)
+    assert torch.equal(out32.to(torch.bfloat16).view(torch.int16), out.view(torch.int16))  # the copy rounds to the output
+    gq, gk, gv = ha.hyperattn_backward(dQ_, dK_, dV_, out, lse, dG_, cfg["b"], cfg["m"], cfg["r"], fwd_workspace=ws,
+                                       out_f32=out32, **kw)
     torch.cuda.synchronize()
     flips = []
     lay = ha.ha_workspace_layout(shape, params)
@@ -77,10 +98,11 @@ def _run_case(ha, torch, cfg, seed_data=77):
         flips = compare_codes(gpu_codes, stages, cfg["r"])
     rq, rk, rv = orc.hyperattn_backward(Q, K, V, G, b=cfg["b"], m=cfg["m"], r=cfg["r"], causal=bool(cfg["causal"]),
                                         n_min=cfg["n_min"], seed=cfg["seed"], flip=flips or None)
-    _assert_grad_close(to_host(gq), rq, "dQ")
-    _assert_grad_close(to_host(gk), rk, "dK")
-    _assert_grad_close(to_host(gv), rv, "dV")
-    return (gq, gk, gv), (dQ_, dK_, dV_, out, lse, dG_, ws)
+    tols = (PEAKED_FRO_TOL, PEAKED_MAX_TOL) if peaked else (FRO_TOL, MAX_TOL)
+    _assert_grad_close(to_host(gq), rq, "dQ", *tols)
+    _assert_grad_close(to_host(gk), rk, "dK", *tols)
+    _assert_grad_close(to_host(gv), rv, "dV")      # dV has no cancelling difference
+    return (gq, gk, gv), (dQ_, dK_, dV_, out, lse, dG_, ws, out32)
 
 
 @pytest.mark.parametrize("d,n,b,m", [(128, 2048, 256, 256), (64, 2048, 256, 512), (128, 1536, 128, 100),
@@ -109,8 +131,9 @@ def test_exact_attn_backward(ha, torch, d, n, causal):
     Q, K, V = synth_inputs.make_qkv(cfg, seed=5)
     G = _cotangent(Q.shape, 6)
     tq, tk, tv, tg = (to_device(x, "bf16") for x in (Q, K, V, G))
-    out, lse = ha.exact_attn_forward(tq, tk, tv, causal=causal)
-    gq, gk, gv = ha.exact_attn_backward(tq, tk, tv, out, lse, tg, causal=causal)
+    out32 = torch.empty(tq.shape, dtype=torch.float32, device="cuda")
+    out, lse = ha.exact_attn_forward(tq, tk, tv, causal=causal, out_f32=out32)
+    gq, gk, gv = ha.exact_attn_backward(tq, tk, tv, out, lse, tg, causal=causal, out_f32=out32)
     torch.cuda.synchronize()
     if causal:   # the recursion that never splits is exact causal attention
         ref = orc.hyperattn_backward(Q, K, V, G, b=1, m=0, r=1, causal=True, n_min=n)
@@ -120,13 +143,38 @@ def test_exact_attn_backward(ha, torch, d, n, causal):
         _assert_grad_close(to_host(got), r_, name)
 
 
+def test_backward_on_the_mixture_law(ha, torch):
+    """Peaked attention rows (scores up to +-250): dQ and dK against the looser bound the
+    cancellation in dP - delta calls for, dV against the tight one."""
+    print("backward mixture", flush=True)
+    cfg = dict(B=1, H=2, n=4096, d=64, dtype="bf16", law="mixture", b=256, m=512, r=7, causal=0, n_min=4096, seed=0)
+    _run_case(ha, torch, cfg, peaked=True)
+
+
+def test_backward_with_delta_from_the_bf16_output(ha, torch):
+    print("backward, delta from bf16 out", flush=True)
+    cfg = dict(B=1, H=2, n=2048, d=128, dtype="bf16", law="iid", b=256, m=256, r=7, causal=1, n_min=512, seed=0)
+    Q, K, V = synth_inputs.make_qkv(cfg, seed=77)
+    G = _cotangent(Q.shape, 78)
+    tq, tk, tv, tg = (to_device(x, "bf16") for x in (Q, K, V, G))
+    shape = ha.make_shape(1, 2, 2048, 128, ha.HA_BF16)
+    ws = ha.alloc_workspace(shape, ha.make_params(256, 256, 7, True, 512, 0))
+    kw = dict(causal=True, n_min=512, seed=0)
+    out, lse = ha.hyperattn_forward(tq, tk, tv, 256, 256, 7, workspace=ws, **kw)
+    grads = ha.hyperattn_backward(tq, tk, tv, out, lse, tg, 256, 256, 7, fwd_workspace=ws, **kw)
+    torch.cuda.synchronize()
+    ref = orc.hyperattn_backward(Q, K, V, G, b=256, m=256, r=7, causal=True, n_min=512, seed=0)
+    for got, r_, what in zip(grads, ref, ("dQ", "dK", "dV")):
+        _assert_grad_close(to_host(got), r_, what)
+
+
 def test_backward_is_deterministic_and_leaves_inputs_alone(ha, torch):
     print("backward determinism", flush=True)
     cfg = dict(B=1, H=2, n=2048, d=128, dtype="bf16", law="iid", b=128, m=128, r=7, causal=1, n_min=512, seed=1)
-    (gq, gk, gv), (tq, tk, tv, out, lse, tg, ws) = _run_case(ha, torch, cfg)
+    (gq, gk, gv), (tq, tk, tv, out, lse, tg, ws, out32) = _run_case(ha, torch, cfg)
     before = [t.clone() for t in (tq, tk, tv, out, lse, tg, ws)]
     kw = dict(causal=1, n_min=512, seed=1)
-    gq2, gk2, gv2 = ha.hyperattn_backward(tq, tk, tv, out, lse, tg, 128, 128, 7, fwd_workspace=ws, **kw)
+    gq2, gk2, gv2 = ha.hyperattn_backward(tq, tk, tv, out, lse, tg, 128, 128, 7, fwd_workspace=ws, out_f32=out32, **kw)
     torch.cuda.synchronize()
     for a_, b_ in zip((gq, gk, gv), (gq2, gk2, gv2)):
         assert torch.equal(a_.view(torch.int16), b_.view(torch.int16))
@@ -211,3 +259,47 @@ def test_backward_of_nothing(ha, torch):
         ws = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
         grads = ha.hyperattn_backward(q, q, q, q, lse, q, 64, 16, 7, fwd_workspace=ws, bwd_workspace=ws.clone())
         assert all(g.shape == q.shape for g in grads)
+
+
+def _random_cases(count, seed):
+    """Seeded random (d, n, n_min, b, m, r, causal) combinations within what the library accepts."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        d = int(rng.choice([64, 128]))
+        causal = int(rng.integers(0, 2))
+        b = int(rng.choice([8, 16, 24, 32, 48, 64, 96, 128, 256]))
+        r = int(rng.integers(1, 9))
+        m = int(rng.choice([0, 16, 33, 64, 100, 256]))
+        if causal:
+            n_min = b * int(rng.integers(1, 5))
+            n = n_min * (1 << int(rng.integers(0, 5)))
+        else:
+            n_min = 4096
+            n = b * int(rng.integers(1, 20))
+        if n > 3000:
+            continue
+        cases.append((d, n, n_min, b, m, r, causal))
+    return cases
+
+
+@pytest.mark.parametrize("d,n,n_min,b,m,r,causal", _random_cases(24, 2024))
+def test_forward_and_backward_on_random_small_problems(ha, torch, d, n, n_min, b, m, r, causal):
+    """Forward (codes, outputs) and backward against the oracle on seeded random parameter combinations."""
+    from ha_testutil import assert_close, assert_lse_close, run_oracle
+    print(f"random case d={d} n={n} n_min={n_min} b={b} m={m} r={r} causal={causal}", flush=True)
+    cfg = dict(B=1, H=2, n=n, d=d, dtype="bf16", law="iid", b=b, m=m, r=r, causal=causal, n_min=n_min, seed=n + m)
+    _, (tq, tk, tv, out, lse, tg, ws, _) = _run_case(ha, torch, cfg, seed_data=1000 + n)
+    Q, K, V = synth_inputs.make_qkv(cfg, seed=1000 + n)
+    flips = []
+    shape = ha.make_shape(1, 2, n, d, ha.HA_BF16)
+    params = ha.make_params(b, m, r, causal, n_min, cfg["seed"])
+    if ha.ha_workspace_layout(shape, params).levels > 0:
+        views = ha.workspace_views(ws, shape, params)
+        stages = {}
+        run_oracle(Q, K, V, cfg, stages=stages)
+        flips = compare_codes(np.stack([views["codes_q"].cpu().numpy(), views["codes_k"].cpu().numpy()]), stages, r)
+    # rows with few keys average little: the operand-rounding term 2^-8 sum_j p_j |v_j| is passed explicitly
+    ref_out, ref_lse, absv = run_oracle(Q, K, V, cfg, flip=flips or None, with_absv=True)
+    assert_close(to_host(out), ref_out, "bf16", "out", absv)
+    assert_lse_close(to_host(lse), ref_lse, "bf16", "lse")
