@@ -485,3 +485,35 @@ def test_exact_attention_wide_workgroups_sampled_rows(ha, torch):
             ref_o, ref_l = orc.exact_attention(Q[0, hd][rows], K[0, hd], V[0, hd])
             assert_close(to_host(out[0, hd])[rows], ref_o, "bf16", f"out d={d} head {hd}")
             assert_lse_close(to_host(lse[0, hd])[rows], ref_l, "bf16", f"lse d={d} head {hd}")
+
+
+def _random_forward_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        dtype = str(rng.choice(["bf16", "bf16", "fp32"]))
+        d = int(rng.choice([64, 128]))
+        causal = int(rng.integers(0, 2))
+        b = int(rng.choice([1, 3, 8, 16, 24, 32, 48, 64, 96, 128, 200, 256]))
+        r = int(rng.integers(1, 9))
+        m = int(rng.choice([0, 1, 2, 5, 16, 33, 64, 100, 256, 300]))
+        if causal:
+            n_min = b * int(rng.integers(1, 6))
+            n = n_min * (1 << int(rng.integers(0, 6)))
+        else:
+            n_min = 4096
+            n = b * int(rng.integers(1, 24))
+        if n > 2500 or n < 2:
+            continue
+        cases.append((dtype, d, n, n_min, b, m, r, causal))
+    return cases
+
+
+@pytest.mark.parametrize("dtype,d,n,n_min,b,m,r,causal", _random_forward_cases(36, 7))
+def test_forward_on_random_small_problems(ha, torch, dtype, d, n, n_min, b, m, r, causal):
+    """Codes, permutations and outputs against the oracle on seeded random parameter combinations
+    (both dtypes, block sizes that divide nothing in the kernels' tiling, tiny and oversized m)."""
+    print(f"random forward {dtype} d={d} n={n} n_min={n_min} b={b} m={m} r={r} causal={causal}", flush=True)
+    cfg = dict(B=1, H=2, n=n, d=d, dtype=dtype, law="iid", b=b, m=m, r=r, causal=causal, n_min=n_min, seed=3 * n + m)
+    Q, K, V = synth_inputs.make_qkv(cfg, seed=500 + n + b)
+    _forward_and_compare(ha, torch, cfg, Q, K, V, p_rounding_term=(dtype == "bf16"))
