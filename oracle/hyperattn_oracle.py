@@ -32,6 +32,11 @@ algorithm's steps in the paper's order and notation:
   causal_forward       Algorithm 4 with the outputs combined by the same
                        row-sum weights (D_21 + D_C22)
   hyperattn_forward    Algorithm 3 in its Section 4 form over [B, H, n, d]
+  hyperattn_forward_alg2  Algorithm 2 as printed (cap C_i, tau from a row subset,
+                       lower cap tau / kappa) and Lemma 2 / Algorithm 3's value
+                       product D~^-1 A S^T S V with rows drawn by squared norm,
+                       evaluated densely (small n); the unspecified constants
+                       are caller's numbers
   hyperattn_backward   the forward's vector-Jacobian product (Section 4.2 times
                        forward + backward), random draws held fixed, written
                        out part by part in the forward's structure
@@ -465,3 +470,117 @@ def hyperattn_backward(Q, K, V, dO, b, m, r, causal=False, n_min=4096, seed=0, R
         dK.reshape(B * H, n, -1)[bh] = gk
         dV.reshape(B * H, n, -1)[bh] = gv
     return dQ, dK, dV
+
+
+# --------------------------------------------------------------------------
+# Algorithm 2 as printed (caps) and Lemma 2 / Algorithm 3 (value sampling by
+# squared row norms): the estimator variants that Section 4's implementation
+# paragraph leaves out.  Unmasked problems only.
+#
+# Readings: the constant in C_i = Theta(eps^2 m / (n log n) * (masked row sum +
+# tau / kappa)) is a caller's number `cap_scale` (natural log; cap_scale <= 0: no
+# cap); kappa is a caller's number (<= 0: no lower cap); the subset T is m rows
+# drawn uniformly WITH replacement from counter stream 0; the squared row norms
+# are quantised to 20 bits relative to the largest so that the draws are
+# integer decisions: q_l = floor(2^20 |V_l|^2 / max|V|^2) + 1, p_l = q_l / sum q,
+# draw r of head bh = first l with prefix(q)[l] > (u64 * sum q) >> 64, u64 from
+# counter bh * m + r of stream 2; the rescaling 1 / (m p_l) is the exact one for
+# these p_l, so S^T S stays unbiased for the identity.
+# --------------------------------------------------------------------------
+STREAM_TAU_ROWS = 0
+STREAM_VNORM = 2
+
+
+def tau_rows(seed: int, n: int, m: int) -> np.ndarray:
+    """The rows of Algorithm 2's subset T."""
+    return np.array([((rand_u64(seed, STREAM_TAU_ROWS, j) >> 32) * n) >> 32 for j in range(m)], dtype=np.int64)
+
+
+def vnorm_weights(Vh) -> np.ndarray:
+    """Integer sampling weights q_l of one head's value rows."""
+    Vh = np.asarray(Vh, dtype=np.float64)
+    w = np.zeros(Vh.shape[0], dtype=np.float64)
+    for c in range(Vh.shape[1]):                 # ascending c, one rounding per add, like the kernel
+        w = w + Vh[:, c] * Vh[:, c]
+    wmax = w.max()
+    if not wmax > 0.0:
+        return np.ones(Vh.shape[0], dtype=np.int64)
+    return np.floor(w / wmax * float(1 << 20)).astype(np.int64) + 1
+
+
+def vnorm_samples(Vh, seed: int, bh: int, m: int):
+    """(indices l'_1..l'_m, log of their rescaling factors 1 / (m p_l)) for head bh (Lemma 2)."""
+    q = vnorm_weights(Vh)
+    prefix = np.cumsum(q)
+    total = int(prefix[-1])
+    idx = np.empty(m, dtype=np.int64)
+    for r_ in range(m):
+        t = (rand_u64(seed, STREAM_VNORM, bh * m + r_) * total) >> 64
+        idx[r_] = int(np.searchsorted(prefix, t, side="right"))
+    logw = np.log(float(total)) - np.log(float(m)) - np.log(q[idx].astype(np.float64))
+    return idx, logw
+
+
+def alg2_head_forward(Qh, Kh, Vh, codes_q, codes_k, b, samples, t_rows, cap_scale, kappa, vsamp=None):
+    """One head.  Returns (out, log d~, log tau).  vsamp = (indices, log weights) selects
+    Algorithm 3's value product D~^-1 A S^T S V; None keeps Section 4's numerator (masked
+    part exactly + the uniform samples, uncapped)."""
+    n = Qh.shape[0]
+    m = len(samples)
+    perm_q, pos_q = sort_lsh(codes_q)
+    perm_k, pos_k = sort_lsh(codes_k)
+    blk_q = pos_q // b
+    blk_k = pos_k // b
+    S = Qh @ Kh.T                                                    # dense: small n only
+    Mh = blk_q[:, None] == blk_k[None, :]                            # M^H
+    with np.errstate(divide="ignore"):
+        log_masked = np.log(np.where(Mh, np.exp(S - S.max()), 0.0).sum(axis=1)) + S.max()
+        log_unmasked = np.log(np.where(Mh, 0.0, np.exp(S - S.max())).sum(axis=1)) + S.max()
+    log_tau = log_unmasked[t_rows].max() if len(t_rows) else -np.inf            # line "tau <- max_{j in T}"
+    floor_term = log_tau - math.log(kappa) if kappa > 0 else -np.inf            # tau / kappa
+    samples = np.asarray(samples, dtype=np.int64)
+    keep = ~Mh[:, samples] if m else np.zeros((n, 0), dtype=bool)               # 1 - M_{i, l_j}
+    Ss = S[:, samples] if m else np.zeros((n, 0))
+    if cap_scale > 0 and m > 0:
+        log_cap = math.log(cap_scale * m / (n * math.log(n))) + np.logaddexp(log_masked, floor_term)   # C_i
+        Sc = np.minimum(Ss, log_cap[:, None])
+    else:
+        Sc = Ss
+    with np.errstate(divide="ignore"):
+        ref = max(float(S.max()), 0.0)
+        d_i = np.where(keep, np.exp(Sc - ref), 0.0).sum(axis=1) * (n / m if m else 0.0)
+        log_d = np.log(d_i) + ref                                                # line "d_i <- (n/m) sum ..."
+    log_dt = np.logaddexp(log_masked, np.maximum(log_d, floor_term))             # line "d~_i <- ... + max(d_i, tau/kappa)"
+    if vsamp is not None:
+        vi, vlogw = vsamp
+        num = np.exp(S[:, vi] + vlogw[None, :] - log_dt[:, None]) @ Vh[vi]      # D~^-1 A S^T S V
+    else:
+        P_masked = np.where(Mh, np.exp(S - log_dt[:, None]), 0.0)
+        num = P_masked @ Vh
+        if m:
+            num = num + (n / m) * (np.where(keep, np.exp(Ss - log_dt[:, None]), 0.0) @ Vh[samples])
+    return num, log_dt, log_tau
+
+
+def hyperattn_forward_alg2(Q, K, V, b, m, r, seed=0, cap_scale=0.0, kappa=0.0, vnorm_sampling=False, R=None):
+    """Unmasked HyperAttention with Algorithm 2's estimator as printed.  Returns (out, log d~, log tau [B*H])."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    B, H, n, d = Q.shape
+    if R is None:
+        R = make_projection(seed, d, r)
+    samples = make_samples(seed, 0, 0, n, m)
+    t_rows = tau_rows(seed, n, m)
+    out = np.empty_like(V)
+    lse = np.empty((B, H, n))
+    taus = np.empty(B * H)
+    for bh in range(B * H):
+        q, k, v = (x.reshape(B * H, n, -1)[bh] for x in (Q, K, V))
+        cq, ck = lsh_codes(lsh_project(q, R), r), lsh_codes(lsh_project(k, R), r)
+        vs = vnorm_samples(v, seed, bh, m) if vnorm_sampling else None
+        o, l, t = alg2_head_forward(q, k, v, cq, ck, b, samples, t_rows, cap_scale, kappa, vs)
+        out.reshape(B * H, n, -1)[bh] = o
+        lse.reshape(B * H, n)[bh] = l
+        taus[bh] = t
+    return out, lse, taus

@@ -425,3 +425,81 @@ def test_oracle_matches_its_frozen_record(case):
     for key, val in stored.items():
         np.testing.assert_allclose(np.asarray(now[key], dtype=np.float64), np.asarray(val, dtype=np.float64),
                                    rtol=1e-12, atol=1e-14, err_msg=f"{case}: {key}")
+
+
+# --------------------------------------------------------------------------
+# Algorithm 2 as printed (caps) and Lemma 2's value sampling
+# --------------------------------------------------------------------------
+def _alg2_inputs(n=96, d=8, seed=0, scale=0.8):
+    rng = np.random.default_rng(seed)
+    return tuple(rng.standard_normal((1, 1, n, d)) * scale for _ in range(3))
+
+
+def test_alg2_without_caps_is_the_section4_forward():
+    """Two independently written evaluations (dense here, part by part there) of the same estimator."""
+    Q, K, V = _alg2_inputs()
+    a = orc.hyperattn_forward(Q, K, V, b=16, m=20, r=4, seed=5)
+    b_ = orc.hyperattn_forward_alg2(Q, K, V, b=16, m=20, r=4, seed=5)
+    np.testing.assert_allclose(b_[0], a[0], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(b_[1], a[1], rtol=1e-12, atol=1e-13)
+
+
+def test_alg2_tau_cap_and_lower_cap_follow_their_definitions():
+    n, b, m, r, seed = 96, 16, 24, 4, 2
+    Q, K, V = _alg2_inputs(n=n, seed=1)
+    q, k = Q[0, 0], K[0, 0]
+    R = orc.make_projection(seed, q.shape[1], r)
+    _, pos_q = orc.sort_lsh(orc.lsh_codes(orc.lsh_project(q, R), r))
+    _, pos_k = orc.sort_lsh(orc.lsh_codes(orc.lsh_project(k, R), r))
+    A = np.exp(q @ k.T)
+    Mh = (pos_q[:, None] // b) == (pos_k[None, :] // b)
+    masked = (A * Mh).sum(axis=1)
+    unmasked = (A * ~Mh).sum(axis=1)
+    T = orc.tau_rows(seed, n, m)
+    assert T.min() >= 0 and T.max() < n and len(T) == m
+    tau = unmasked[T].max()
+    samples = orc.make_samples(seed, 0, 0, n, m)
+    kept = (~Mh[:, samples]).sum(axis=1)
+    # a cap far below every entry: every kept sample contributes exactly C_i
+    cap_scale, kappa = 1e-6, 2.5
+    out, log_dt, log_tau = orc.hyperattn_forward_alg2(Q, K, V, b=b, m=m, r=r, seed=seed, cap_scale=cap_scale, kappa=kappa)
+    np.testing.assert_allclose(np.exp(log_tau[0]), tau, rtol=1e-12)
+    C = cap_scale * m / (n * math.log(n)) * (masked + tau / kappa)
+    d_i = (n / m) * kept * C
+    np.testing.assert_allclose(np.exp(log_dt[0, 0]), masked + np.maximum(d_i, tau / kappa), rtol=1e-11)
+    # a cap above every entry changes nothing; the lower cap alone acts as max(d_i, tau / kappa)
+    big = orc.hyperattn_forward_alg2(Q, K, V, b=b, m=m, r=r, seed=seed, cap_scale=1e12, kappa=kappa)
+    d_plain = (n / m) * (A[:, samples] * ~Mh[:, samples]).sum(axis=1)
+    np.testing.assert_allclose(np.exp(big[1][0, 0]), masked + np.maximum(d_plain, tau / kappa), rtol=1e-11)
+    assert (np.maximum(d_plain, tau / kappa) > d_plain).any()      # the lower cap binds somewhere in this instance
+
+
+def test_vnorm_sampling_weights_distribution_and_unbiasedness():
+    n, d, m = 48, 6, 16
+    rng = np.random.default_rng(4)
+    Q, K = (rng.standard_normal((1, 1, n, d)) * 0.7 for _ in range(2))
+    V = rng.standard_normal((1, 1, n, d)) * rng.uniform(0.1, 3.0, size=(1, 1, n, 1))      # very unequal row norms
+    q = orc.vnorm_weights(V[0, 0])
+    w = (V[0, 0] ** 2).sum(axis=1)
+    assert q.min() >= 1 and q.max() == (1 << 20) + 1
+    np.testing.assert_allclose(q / q.sum(), w / w.sum(), atol=2e-6)
+    assert (orc.vnorm_weights(np.zeros((5, 3))) == 1).all()
+    # draws follow p_l = q_l / sum q, and E[A S^T S V] = A V (Lemma 2's sampling matrix is unbiased)
+    A = np.exp(Q[0, 0] @ K[0, 0].T)
+    exact = A @ V[0, 0]
+    acc = np.zeros_like(exact)
+    counts = np.zeros(n)
+    trials = 3000
+    for s in range(trials):
+        idx, logw = orc.vnorm_samples(V[0, 0], s, 0, m)
+        acc += (A[:, idx] * np.exp(logw)[None, :]) @ V[0, 0][idx]
+        counts += np.bincount(idx, minlength=n)
+    p = q / q.sum()
+    assert np.abs(counts / (trials * m) - p).max() < 5 * np.sqrt(p.max() / (trials * m))
+    rel = np.linalg.norm(acc / trials - exact) / np.linalg.norm(exact)
+    assert rel < 0.05, rel
+    # the sampled value product with D~ of the same call reproduces out
+    out, log_dt, _ = orc.hyperattn_forward_alg2(Q, K, V, b=8, m=m, r=3, seed=9, vnorm_sampling=True)
+    idx, logw = orc.vnorm_samples(V[0, 0], 9, 0, m)
+    np.testing.assert_allclose(out[0, 0], ((A[:, idx] * np.exp(logw)[None, :]) @ V[0, 0][idx]) / np.exp(log_dt[0, 0])[:, None],
+                               rtol=1e-11)
