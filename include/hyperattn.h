@@ -262,6 +262,50 @@ int exact_attn_backward(const void* Q, const void* K, const void* V, const void*
                         void* workspace, size_t workspace_bytes, void* stream);
 size_t exact_attn_backward_workspace_bytes(const ha_shape* shape);
 
+/* ------------------------------------------------------------------------
+ * Algorithm 2 as printed and Lemma 2 / Algorithm 3, as options (the Section 4
+ * form above leaves them out).  Unmasked problems only (params->causal must be
+ * 0); both dtypes; plain fp32 kernels, not tuned.
+ *   tau   = max over m rows drawn uniformly (with replacement) of the unmasked row sum
+ *   C_i   = cap_scale * m / (n ln n) * (masked row sum_i + tau / kappa)     cap_scale <= 0: no cap
+ *   d_i   = (n/m) sum_j (1 - M_{i,l_j}) min(exp<q_i,k_{l_j}>, C_i)
+ *   d~_i  = masked row sum_i + max(d_i, tau / kappa)                         kappa <= 0: no lower cap
+ *   out_i = (1/d~_i) sum_r exp<q_i,k_{l'_r}> v_{l'_r} / (m p_{l'_r}),  l'_r drawn with p_l ~ |V_l|^2   (vnorm_sampling)
+ *        or (1/d~_i) (masked part + (n/m) sum_j (1 - M_{i,l_j}) exp<q_i,k_{l_j}> v_{l_j})             (otherwise)
+ * lse receives log d~.  The constants the paper leaves open (the Theta of C_i,
+ * kappa) are the caller's.  Squared row norms are quantised to 20 bits relative
+ * to the largest (p_l = q_l / sum q, q_l = floor(2^20 |V_l|^2 / max) + 1) so that
+ * the draws are integer decisions; the rescaling uses the same p_l.
+ * workspace: device, 256-byte aligned, >= ha_alg2_workspace_bytes(); it starts
+ * with the forward's layout (ha_workspace_layout) followed by the regions below.
+ * Errors as hyperattn_forward, plus HA_ERR_SHAPE for causal params. */
+typedef struct {
+  float cap_scale;
+  float kappa;
+  int32_t vnorm_sampling;
+} ha_alg2_options;
+
+typedef struct {
+  size_t forward_bytes;      /* the forward's regions come first */
+  size_t pos_q;              /* int32 [B*H][n]: inverse of perm_q */
+  size_t tau_rows;           /* int32 [m]: the rows of T */
+  size_t log_unmasked_t;     /* float [B*H][m]: log of their unmasked row sums */
+  size_t log_tau;            /* float [B*H] */
+  size_t vnorm_w;            /* double [B*H][n]: |V_l|^2 */
+  size_t vnorm_max;          /* uint64 [B*H]: bit pattern of the largest */
+  size_t vnorm_q;            /* uint32 [B*H][n]: q_l */
+  size_t vnorm_prefix;       /* uint64 [B*H][n]: inclusive prefix sums of q */
+  size_t vnorm_samples;      /* int32 [B*H][m]: l'_r */
+  size_t vnorm_logw;         /* float [B*H][m]: log(1 / (m p_{l'_r})) */
+  size_t total_bytes;
+} ha_alg2_ws_layout;
+
+int ha_alg2_workspace_layout(const ha_shape* shape, const ha_params* params, ha_alg2_ws_layout* layout);
+size_t ha_alg2_workspace_bytes(const ha_shape* shape, const ha_params* params);
+int hyperattn_forward_alg2(const void* Q, const void* K, const void* V, void* out, float* lse,
+                           const ha_shape* shape, const ha_params* params, const ha_alg2_options* options,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
 /* Measurement aids (no passage of the paper: they serve the roofline report).
  * Both run on `stream`, time themselves with events and WAIT for the stream;
  * `buf` is caller-owned device memory that they overwrite.

@@ -40,6 +40,16 @@ class HaBwdWsLayout(ctypes.Structure):
     _fields_ = [(k, c_size_t) for k in ("delta", "dq_part", "dk_part", "dv_part", "samp_k", "samp_v", "total_bytes")]
 
 
+class HaAlg2Options(ctypes.Structure):
+    _fields_ = [("cap_scale", c_float), ("kappa", c_float), ("vnorm_sampling", c_int32)]
+
+
+class HaAlg2WsLayout(ctypes.Structure):
+    _fields_ = [(k, c_size_t) for k in ("forward_bytes", "pos_q", "tau_rows", "log_unmasked_t", "log_tau", "vnorm_w",
+                                        "vnorm_max", "vnorm_q", "vnorm_prefix", "vnorm_samples", "vnorm_logw",
+                                        "total_bytes")]
+
+
 class HyperAttnError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -74,6 +84,10 @@ _SIGNATURES = {
                                                           c_void_p, c_size_t, c_void_p, POINTER(c_float)]),
     "exact_attn_backward": (c_int, [c_void_p] * 10 + [POINTER(HaShape), c_int, c_void_p, c_size_t, c_void_p]),
     "exact_attn_backward_workspace_bytes": (c_size_t, [POINTER(HaShape)]),
+    "ha_alg2_workspace_layout": (c_int, [POINTER(HaShape), POINTER(HaParams), POINTER(HaAlg2WsLayout)]),
+    "ha_alg2_workspace_bytes": (c_size_t, [POINTER(HaShape), POINTER(HaParams)]),
+    "hyperattn_forward_alg2": (c_int, [c_void_p] * 5 + [POINTER(HaShape), POINTER(HaParams), POINTER(HaAlg2Options),
+                                                       c_void_p, c_size_t, c_void_p]),
     "ha_measure_mfma_rate": (c_int, [c_void_p, c_size_t, c_int32, POINTER(c_float), c_void_p]),
     "ha_measure_hbm_rate": (c_int, [c_void_p, c_size_t, POINTER(c_float), POINTER(c_float), c_void_p]),
     "ha_strerror": (c_char_p, [c_int]),
@@ -440,3 +454,52 @@ def exact_attn_backward(Q, K, V, out, lse, d_out, causal=False, workspace=None, 
                                      ctypes.byref(shape), int(bool(causal)), workspace.data_ptr(), workspace.numel(),
                                      _stream(stream)), "exact_attn_backward")
     return dQ, dK, dV
+
+
+# ---------------------------------------------------------------- Algorithm 2 as printed / Lemma 2
+def ha_alg2_workspace_layout(shape: HaShape, params: HaParams) -> HaAlg2WsLayout:
+    lay = HaAlg2WsLayout()
+    _check(lib().ha_alg2_workspace_layout(ctypes.byref(shape), ctypes.byref(params), ctypes.byref(lay)),
+           "ha_alg2_workspace_layout")
+    return lay
+
+
+def hyperattn_forward_alg2(Q, K, V, b, m, r, seed=0, cap_scale=0.0, kappa=0.0, vnorm_sampling=False, workspace=None,
+                           out=None, lse=None, stream=None):
+    """Unmasked HyperAttention with Algorithm 2's caps and, optionally, Lemma 2's value
+    sampling by squared row norm.  Returns (out, log d~, workspace)."""
+    torch = _torch()
+    B, H, n, d = Q.shape
+    shape = make_shape(B, H, n, d, _dtype_code(Q))
+    params = make_params(b, m, r, False, 4096, seed)
+    if workspace is None:
+        workspace = torch.empty(int(ha_alg2_workspace_layout(shape, params).total_bytes), dtype=torch.uint8,
+                                device=Q.device)
+    if out is None:
+        out = torch.empty_like(Q)
+    if lse is None:
+        lse = torch.empty((B, H, n), dtype=torch.float32, device=Q.device)
+    opt = HaAlg2Options(float(cap_scale), float(kappa), int(bool(vnorm_sampling)))
+    _check(lib().hyperattn_forward_alg2(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"), _dev(lse, "lse"),
+                                        ctypes.byref(shape), ctypes.byref(params), ctypes.byref(opt),
+                                        workspace.data_ptr(), workspace.numel(), _stream(stream)),
+           "hyperattn_forward_alg2")
+    return out, lse, workspace
+
+
+def alg2_workspace_views(workspace, shape: HaShape, params: HaParams):
+    """Typed views of the option kernels' regions after hyperattn_forward_alg2."""
+    torch = _torch()
+    lay = ha_alg2_workspace_layout(shape, params)
+    BH, n, m = shape.B * shape.H, shape.n, params.m
+
+    def view(off, count, dtype, shp):
+        nbytes = count * torch.empty((), dtype=dtype).element_size()
+        return workspace[off:off + nbytes].view(dtype).view(shp)
+
+    return {"layout": lay,
+            "tau_rows": view(lay.tau_rows, m, torch.int32, (m,)),
+            "log_tau": view(lay.log_tau, BH, torch.float32, (BH,)),
+            "vnorm_q": view(lay.vnorm_q, BH * n, torch.int32, (BH, n)),
+            "vnorm_samples": view(lay.vnorm_samples, BH * m, torch.int32, (BH, m)),
+            "vnorm_logw": view(lay.vnorm_logw, BH * m, torch.float32, (BH, m))}

@@ -1,0 +1,37 @@
+// Arguments of the Algorithm 2 / Lemma 2 option kernels and their launcher.
+#pragma once
+
+#include "ha_common.h"
+
+namespace ha {
+
+struct Alg2Args {
+  const void* Q;
+  const void* K;
+  const void* V;
+  void* out;
+  float* lse;
+  Geometry g;
+  const int32_t* perm_q;   // [BH][n]
+  const int32_t* perm_k;
+  const int32_t* pos_k;
+  const int32_t* samples;  // [m]
+  const int32_t* samp_blk; // [BH][m]
+  int32_t* pos_q;          // [BH][n]
+  int32_t* tau_rows;       // [m]
+  float* log_unm_t;        // [BH][m]
+  float* log_tau;          // [BH]
+  double* vw;              // [BH][n]
+  unsigned long long* vmax;     // [BH] bit pattern of the largest vw
+  uint32_t* vq;            // [BH][n]
+  unsigned long long* vprefix;  // [BH][n] inclusive
+  int32_t* vsamp;          // [BH][m]
+  float* vlogw;            // [BH][m]
+  uint64_t seed;
+  float cap_scale, kappa;
+  int32_t vnorm;
+};
+
+int launch_alg2(const Alg2Args& a, hipStream_t st);
+
+}  // namespace ha

@@ -1,0 +1,354 @@
+// The estimator of Algorithm 2 as printed, and Lemma 2 / Algorithm 3's value
+// product, as options beside the Section 4 form the main path implements:
+//   tau      = max over a random row subset T of the unmasked row sum <1 - M^H_j, A_j>
+//   C_i      = cap_scale * m / (n ln n) * (masked row sum_i + tau / kappa)
+//   d_i      = (n/m) sum_j (1 - M_{i,l_j}) min(exp<q_i,k_{l_j}>, C_i)
+//   d~_i     = masked row sum_i + max(d_i, tau / kappa)
+//   out_i    = (1 / d~_i) sum_r exp<q_i,k_{l'_r}> v_{l'_r} / (m p_{l'_r}),  l'_r ~ p_l ~ |V_l|^2   (Lemma 2)
+//         or = (1 / d~_i) (masked part + (n/m) sum_j (1 - M) exp<q_i,k_{l_j}> v_{l_j})                (Section 4)
+// The constants the paper leaves open (the Theta in C_i, kappa) are the caller's.
+// Unmasked problems only.  These are options, not the hot path: plain fp32 FMA
+// kernels, one thread per query row, K / V rows staged through LDS as fp32.
+//
+// The draws by squared row norm are integer decisions so that they can be
+// reproduced exactly elsewhere: |V_l|^2 is summed in fp64 over ascending
+// columns, quantised to q_l = floor(2^20 |V_l|^2 / max |V|^2) + 1, and draw r of
+// head bh is the first l whose inclusive prefix sum of q exceeds
+// (u64 * sum q) >> 64, u64 being counter bh * m + r of stream 2.
+#include "attn_common.h"
+#include "alg2_common.h"
+
+namespace ha {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr uint64_t kStreamTauRows = 0;
+constexpr uint64_t kStreamVnorm = 2;
+
+template <typename T>
+__device__ inline float elem(const T* p);
+template <>
+__device__ inline float elem<float>(const float* p) { return *p; }
+template <>
+__device__ inline float elem<uint16_t>(const uint16_t* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+
+__global__ void alg2_prep_kernel(Alg2Args a) {
+  const Geometry& g = a.g;
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < g.m) {
+    const uint64_t hi = rand_u64(a.seed, kStreamTauRows, (uint64_t)t) >> 32;
+    a.tau_rows[t] = (int32_t)((hi * (uint64_t)g.n) >> 32);
+  }
+  if (t < g.BH) a.vmax[t] = 0ull;
+  // pos_q = P_Q^-1
+  if (t < (int64_t)g.BH * g.n) {
+    const int64_t bh = t / g.n;
+    a.pos_q[bh * g.n + a.perm_q[t]] = (int32_t)(t % g.n);
+  }
+}
+
+template <typename T>
+__global__ void vnorm_weight_kernel(Alg2Args a) {
+  const Geometry& g = a.g;
+  const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= (int64_t)g.BH * g.n) return;
+  const T* v = reinterpret_cast<const T*>(a.V) + row * g.d;
+  double w = 0.0;
+  for (int c = 0; c < g.d; ++c) {
+    const double x = (double)elem<T>(v + c);
+    w = w + x * x;  // one rounding per add (the product of two fp32-representable values is exact in fp64)
+  }
+  a.vw[row] = w;
+  atomicMax(&a.vmax[row / g.n], (unsigned long long)__double_as_longlong(w));  // non-negative doubles order like their bits
+}
+
+constexpr int kScanThreads = 1024;
+
+__global__ __launch_bounds__(kScanThreads) void vnorm_scan_kernel(Alg2Args a) {
+  __shared__ unsigned long long part[kScanThreads];
+  const Geometry& g = a.g;
+  const int bh = blockIdx.x;
+  const int tid = threadIdx.x;
+  const double wmax = __longlong_as_double((long long)a.vmax[bh]);
+  const int per = (g.n + kScanThreads - 1) / kScanThreads;
+  const int lo = min(g.n, tid * per), hi = min(g.n, lo + per);
+  unsigned long long sum = 0;
+  for (int l = lo; l < hi; ++l) {
+    uint32_t q = 1u;
+    if (wmax > 0.0) q = (uint32_t)floor(a.vw[(int64_t)bh * g.n + l] / wmax * 1048576.0) + 1u;
+    a.vq[(int64_t)bh * g.n + l] = q;
+    sum += q;
+  }
+  part[tid] = sum;
+  __syncthreads();
+  // exclusive prefix over the threads' sums (integers: any order gives the same result)
+  for (int off = 1; off < kScanThreads; off <<= 1) {
+    unsigned long long v = 0;
+    if (tid >= off) v = part[tid - off];
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  unsigned long long run = part[tid] - sum;
+  for (int l = lo; l < hi; ++l) {
+    run += a.vq[(int64_t)bh * g.n + l];
+    a.vprefix[(int64_t)bh * g.n + l] = run;
+  }
+}
+
+__global__ void vnorm_sample_kernel(Alg2Args a) {
+  const Geometry& g = a.g;
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= (int64_t)g.BH * g.m) return;
+  const int bh = (int)(t / g.m);
+  const unsigned long long* prefix = a.vprefix + (int64_t)bh * g.n;
+  const unsigned long long total = prefix[g.n - 1];
+  const unsigned long long target = __umul64hi(rand_u64(a.seed, kStreamVnorm, (uint64_t)t), total);
+  int lo = 0, hi = g.n - 1;  // first l with prefix[l] > target
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (prefix[mid] > target) hi = mid;
+    else lo = mid + 1;
+  }
+  a.vsamp[t] = lo;
+  a.vlogw[t] = (float)(log((double)total) - log((double)g.m) - log((double)a.vq[(int64_t)bh * g.n + lo]));
+}
+
+// log of the unmasked row sum of row T_j: one workgroup per (head, j)
+template <typename T, int D>
+__global__ __launch_bounds__(256) void alg2_tau_kernel(Alg2Args a) {
+  __shared__ float qs[D];
+  __shared__ float red_m[256], red_s[256];
+  const Geometry& g = a.g;
+  const int bh = blockIdx.x / g.m, j = blockIdx.x % g.m;
+  const int row = a.tau_rows[j];
+  const T* Qh = reinterpret_cast<const T*>(a.Q) + (int64_t)bh * g.n * D;
+  const T* Kh = reinterpret_cast<const T*>(a.K) + (int64_t)bh * g.n * D;
+  for (int c = threadIdx.x; c < D; c += 256) qs[c] = elem<T>(Qh + (int64_t)row * D + c);
+  __syncthreads();
+  const int blk = a.pos_q[(int64_t)bh * g.n + row] / g.b;
+  float mx = -INFINITY, sum = 0.f;
+  for (int l = threadIdx.x; l < g.n; l += 256) {
+    if (a.pos_k[(int64_t)bh * g.n + l] / g.b == blk) continue;  // 1 - M
+    float s = 0.f;
+    for (int c = 0; c < D; ++c) s = __builtin_fmaf(qs[c], elem<T>(Kh + (int64_t)l * D + c), s);
+    if (s > mx) {
+      sum = sum * expf(mx - s) + 1.f;
+      mx = s;
+    } else {
+      sum += expf(s - mx);
+    }
+  }
+  red_m[threadIdx.x] = mx;
+  red_s[threadIdx.x] = sum;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float M = -INFINITY;
+    for (int t = 0; t < 256; ++t) M = fmaxf(M, red_m[t]);
+    float S = 0.f;
+    for (int t = 0; t < 256; ++t)
+      if (red_m[t] > -INFINITY) S += red_s[t] * expf(red_m[t] - M);
+    a.log_unm_t[(int64_t)bh * g.m + j] = (M == -INFINITY) ? -INFINITY : M + logf(S);
+  }
+}
+
+__global__ void alg2_tau_max_kernel(Alg2Args a) {
+  const Geometry& g = a.g;
+  const int bh = blockIdx.x * blockDim.x + threadIdx.x;
+  if (bh >= g.BH) return;
+  float mx = -INFINITY;
+  for (int j = 0; j < g.m; ++j) mx = fmaxf(mx, a.log_unm_t[(int64_t)bh * g.m + j]);
+  a.log_tau[bh] = mx;
+}
+
+__device__ inline float logaddexpf(float x, float y) {
+  const float hi = fmaxf(x, y), lo = fminf(x, y);
+  if (hi == -INFINITY) return -INFINITY;
+  return hi + log1pf(expf(lo - hi));
+}
+
+constexpr int kA2Rows = 64;  // query rows (threads) per workgroup
+constexpr int kA2Tile = 32;  // key rows per LDS tile
+
+// One thread per query row; 64 consecutive sorted positions of one block per workgroup.
+template <typename T, int D>
+__global__ __launch_bounds__(kA2Rows) void alg2_main_kernel(Alg2Args a) {
+  __shared__ float Ks[kA2Tile * D];
+  __shared__ float Vs[kA2Tile * D];
+  __shared__ int32_t rows[kA2Tile];
+  __shared__ float bias[kA2Tile];
+  const Geometry& g = a.g;
+  const int tid = threadIdx.x;
+  const int tpb = (g.b + kA2Rows - 1) / kA2Rows;
+  const int tile = blockIdx.x % ((g.n / g.b) * tpb);
+  const int bh = blockIdx.x / ((g.n / g.b) * tpb);
+  const int t = tile / tpb, chunk = tile % tpb;
+  const int p0 = t * g.b + chunk * kA2Rows;
+  const bool valid = chunk * kA2Rows + tid < g.b;
+  const int64_t hb = (int64_t)bh * g.n;
+  const int qrow = a.perm_q[hb + (valid ? p0 + tid : p0)];
+  const T* Qh = reinterpret_cast<const T*>(a.Q) + hb * D;
+  const T* Kh = reinterpret_cast<const T*>(a.K) + hb * D;
+  const T* Vh = reinterpret_cast<const T*>(a.V) + hb * D;
+
+  float q[D], o[D];
+#pragma unroll
+  for (int c = 0; c < D; ++c) {
+    q[c] = elem<T>(Qh + (int64_t)qrow * D + c);
+    o[c] = 0.f;
+  }
+  float M = -INFINITY;      // reference of every exponential below
+  float msum = 0.f;         // masked row sum / e^M
+  float dsum = 0.f;         // sum of (capped) kept samples / e^M
+  const float ratio = g.m > 0 ? (float)g.n / (float)g.m : 0.f;
+  const float log_tau = a.log_tau[bh];
+  const float floor_term = a.kappa > 0.f ? log_tau - logf(a.kappa) : -INFINITY;
+
+  auto rescale_to = [&](float m_new) {
+    if (m_new > M) {
+      const float f = expf(M - m_new);  // M = -inf gives 0 with all sums 0
+      msum *= f;
+      dsum *= f;
+#pragma unroll
+      for (int c = 0; c < D; ++c) o[c] *= f;
+      M = m_new;
+    }
+  };
+  // stage `cnt` key rows (indices and per-row log weights already in LDS) as fp32
+  auto stage = [&](int cnt, bool with_v) {
+    for (int e = tid; e < cnt * D; e += kA2Rows) {
+      const int j = e / D, c = e % D;
+      Ks[e] = elem<T>(Kh + (int64_t)rows[j] * D + c);
+      if (with_v) Vs[e] = elem<T>(Vh + (int64_t)rows[j] * D + c);
+    }
+  };
+
+  // ---- pass 1: the keys of this block (mask M^H) ----
+  for (int k0 = 0; k0 < g.b; k0 += kA2Tile) {
+    const int cnt = min(kA2Tile, g.b - k0);
+    __syncthreads();
+    if (tid < cnt) rows[tid] = a.perm_k[hb + t * g.b + k0 + tid];
+    __syncthreads();
+    stage(cnt, !a.vnorm);
+    __syncthreads();
+    for (int j = 0; j < cnt; ++j) {
+      float s = 0.f;
+#pragma unroll
+      for (int c = 0; c < D; ++c) s = __builtin_fmaf(q[c], Ks[j * D + c], s);
+      rescale_to(s);
+      const float p = expf(s - M);
+      msum += p;
+      if (!a.vnorm) {
+#pragma unroll
+        for (int c = 0; c < D; ++c) o[c] = __builtin_fmaf(p, Vs[j * D + c], o[c]);
+      }
+    }
+  }
+  const float log_masked = (msum > 0.f) ? M + logf(msum) : -INFINITY;
+  const bool capped = a.cap_scale > 0.f && g.m > 0;
+  const float log_cap = capped ? logf(a.cap_scale * (float)g.m / ((float)g.n * logf((float)g.n))) + logaddexpf(log_masked, floor_term)
+                               : INFINITY;
+
+  // ---- pass 2: the uniform samples of Algorithm 2 (row-sum estimate; Section 4's numerator) ----
+  for (int j0 = 0; j0 < g.m; j0 += kA2Tile) {
+    const int cnt = min(kA2Tile, g.m - j0);
+    __syncthreads();
+    if (tid < cnt) {
+      rows[tid] = a.samples[j0 + tid];
+      bias[tid] = (a.samp_blk[(int64_t)bh * g.m + j0 + tid] == t) ? -INFINITY : 0.f;  // factor 1 - M_{i,l_j}
+    }
+    __syncthreads();
+    stage(cnt, !a.vnorm);
+    __syncthreads();
+    for (int j = 0; j < cnt; ++j) {
+      if (bias[j] == -INFINITY) continue;
+      float s = 0.f;
+#pragma unroll
+      for (int c = 0; c < D; ++c) s = __builtin_fmaf(q[c], Ks[j * D + c], s);
+      rescale_to(s);
+      dsum += expf(fminf(s, log_cap) - M);
+      if (!a.vnorm) {
+        const float p = ratio * expf(s - M);
+#pragma unroll
+        for (int c = 0; c < D; ++c) o[c] = __builtin_fmaf(p, Vs[j * D + c], o[c]);
+      }
+    }
+  }
+
+  // ---- pass 3: the value rows drawn by squared norm (Lemma 2), each with its 1 / (m p_l) ----
+  if (a.vnorm) {
+    for (int j0 = 0; j0 < g.m; j0 += kA2Tile) {
+      const int cnt = min(kA2Tile, g.m - j0);
+      __syncthreads();
+      if (tid < cnt) {
+        rows[tid] = a.vsamp[(int64_t)bh * g.m + j0 + tid];
+        bias[tid] = a.vlogw[(int64_t)bh * g.m + j0 + tid];
+      }
+      __syncthreads();
+      stage(cnt, true);
+      __syncthreads();
+      for (int j = 0; j < cnt; ++j) {
+        float s = bias[j];
+#pragma unroll
+        for (int c = 0; c < D; ++c) s = __builtin_fmaf(q[c], Ks[j * D + c], s);
+        rescale_to(s);
+        const float p = expf(s - M);
+#pragma unroll
+        for (int c = 0; c < D; ++c) o[c] = __builtin_fmaf(p, Vs[j * D + c], o[c]);
+      }
+    }
+  }
+
+  const float log_d = (dsum > 0.f) ? M + logf(dsum * ratio) : -INFINITY;
+  const float log_dt = logaddexpf(log_masked, fmaxf(log_d, floor_term));
+  const float f = (M == -INFINITY || log_dt == -INFINITY) ? 0.f : expf(M - log_dt);
+  if (!valid) return;
+  const int64_t orow = hb + qrow;
+  a.lse[orow] = log_dt;
+  if (sizeof(T) == 4) {
+    float* op = reinterpret_cast<float*>(a.out) + orow * D;
+#pragma unroll
+    for (int c = 0; c < D; ++c) op[c] = o[c] * f;
+  } else {
+    uint16_t* op = reinterpret_cast<uint16_t*>(a.out) + orow * D;
+#pragma unroll
+    for (int c = 0; c < D; c += 2) *reinterpret_cast<uint32_t*>(op + c) = pack_bf16x2(o[c] * f, o[c + 1] * f);
+  }
+}
+
+template <typename T>
+static int launch_alg2_t(const Alg2Args& a, hipStream_t st) {
+  const Geometry& g = a.g;
+  const int64_t rows = (int64_t)g.BH * g.n;
+  int64_t prep = rows > g.m ? rows : g.m;
+  if (prep < g.BH) prep = g.BH;
+  hipLaunchKernelGGL(alg2_prep_kernel, dim3((unsigned)((prep + 255) / 256)), dim3(256), 0, st, a);
+  if (a.vnorm && g.m > 0) {
+    hipLaunchKernelGGL((vnorm_weight_kernel<T>), dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(vnorm_scan_kernel, dim3((unsigned)g.BH), dim3(kScanThreads), 0, st, a);
+    hipLaunchKernelGGL(vnorm_sample_kernel, dim3((unsigned)(((int64_t)g.BH * g.m + 255) / 256)), dim3(256), 0, st, a);
+  }
+  if (g.m > 0) {
+    if (g.d == 128)
+      hipLaunchKernelGGL((alg2_tau_kernel<T, 128>), dim3((unsigned)(g.BH * g.m)), dim3(256), 0, st, a);
+    else
+      hipLaunchKernelGGL((alg2_tau_kernel<T, 64>), dim3((unsigned)(g.BH * g.m)), dim3(256), 0, st, a);
+  }
+  hipLaunchKernelGGL(alg2_tau_max_kernel, dim3((unsigned)((g.BH + 63) / 64)), dim3(64), 0, st, a);
+  const int tpb = (g.b + kA2Rows - 1) / kA2Rows;
+  const unsigned grid = (unsigned)((int64_t)g.BH * (g.n / g.b) * tpb);
+  if (g.d == 128)
+    hipLaunchKernelGGL((alg2_main_kernel<T, 128>), dim3(grid), dim3(kA2Rows), 0, st, a);
+  else
+    hipLaunchKernelGGL((alg2_main_kernel<T, 64>), dim3(grid), dim3(kA2Rows), 0, st, a);
+  return check_launch();
+}
+
+int launch_alg2(const Alg2Args& a, hipStream_t st) {
+  if (a.g.d != 64 && a.g.d != 128) return HA_ERR_SHAPE;
+  if (a.g.dtype == HA_BF16) return launch_alg2_t<uint16_t>(a, st);
+  if (a.g.dtype == HA_FP32) return launch_alg2_t<float>(a, st);
+  return HA_ERR_DTYPE;
+}
+
+}  // namespace ha

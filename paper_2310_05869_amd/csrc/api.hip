@@ -27,6 +27,7 @@
 #include <cstring>
 
 #include "ha_common.h"
+#include "alg2_common.h"
 #include "bwd_common.h"
 
 namespace ha {
@@ -413,6 +414,39 @@ static int backward_impl(const void* Q, const void* K, const void* V, const void
   return HA_OK;
 }
 
+// ---------------------------------------------------------------------------
+// Algorithm 2 as printed / Lemma 2 options
+// ---------------------------------------------------------------------------
+static void fill_alg2_layout(const Geometry& g, const ha_ws_layout& fwd, ha_alg2_ws_layout* l) {
+  std::memset(l, 0, sizeof(*l));
+  size_t off = align256(fwd.total_bytes);
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off = align256(off + bytes);
+    return at;
+  };
+  const size_t rows = (size_t)g.BH * g.n;
+  l->forward_bytes = fwd.total_bytes;
+  l->pos_q = take(rows * 4);
+  l->tau_rows = take((size_t)g.m * 4);
+  l->log_unmasked_t = take((size_t)g.BH * g.m * 4);
+  l->log_tau = take((size_t)g.BH * 4);
+  l->vnorm_w = take(rows * 8);
+  l->vnorm_max = take((size_t)g.BH * 8);
+  l->vnorm_q = take(rows * 4);
+  l->vnorm_prefix = take(rows * 8);
+  l->vnorm_samples = take((size_t)g.BH * g.m * 4);
+  l->vnorm_logw = take((size_t)g.BH * g.m * 4);
+  l->total_bytes = off;
+}
+
+static int alg2_geometry(const ha_shape* sh, const ha_params* p, Geometry* g) {
+  const int rc = make_geometry(sh, p, g);
+  if (rc != HA_OK) return rc;
+  if (g->causal) return HA_ERR_SHAPE;  // Algorithms 2 and 3 are stated for the unmasked problem
+  return HA_OK;
+}
+
 }  // namespace ha
 
 using namespace ha;
@@ -714,6 +748,85 @@ size_t exact_attn_backward_workspace_bytes(const ha_shape* sh) {
   p.causal = 1;
   p.n_min = sh->n > 0 ? sh->n : 1;
   return ha_backward_workspace_bytes(sh, &p);
+}
+
+int ha_alg2_workspace_layout(const ha_shape* shape, const ha_params* params, ha_alg2_ws_layout* layout) {
+  if (!layout) return HA_ERR_NULL;
+  Geometry g;
+  const int rc = alg2_geometry(shape, params, &g);
+  if (rc != HA_OK) return rc;
+  ha_ws_layout fwd;
+  fill_layout(g, &fwd);
+  fill_alg2_layout(g, fwd, layout);
+  return HA_OK;
+}
+
+size_t ha_alg2_workspace_bytes(const ha_shape* shape, const ha_params* params) {
+  ha_alg2_ws_layout l;
+  return ha_alg2_workspace_layout(shape, params, &l) == HA_OK ? l.total_bytes : 0;
+}
+
+int hyperattn_forward_alg2(const void* Q, const void* K, const void* V, void* out, float* lse, const ha_shape* shape,
+                           const ha_params* params, const ha_alg2_options* opt, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  if (!opt) return HA_ERR_NULL;
+  Geometry g;
+  int rc = alg2_geometry(shape, params, &g);
+  if (rc != HA_OK) return rc;
+  if (g.BH == 0 || g.n == 0) return HA_OK;
+  if (!Q || !K || !V || !out || !lse || !workspace) return HA_ERR_NULL;
+  ha_ws_layout lay;
+  fill_layout(g, &lay);
+  ha_alg2_ws_layout al;
+  fill_alg2_layout(g, lay, &al);
+  if (workspace_bytes < al.total_bytes || ((uintptr_t)workspace & 255) != 0) return HA_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  unsigned char* base = (unsigned char*)workspace;
+  // hash, sort and draws exactly as the forward does them
+  uint16_t Rb[1024];
+  for (int c = 0; c < g.d; ++c)
+    for (int k = 0; k < g.r; ++k) Rb[c * g.r + k] = projection_bits(params->seed, c, k);
+  float* proj = (float*)(base + lay.proj);
+  int32_t* samples = (int32_t*)(base + lay.samples);
+  rc = launch_prep(proj, nullptr, Rb, samples, nullptr, g, params->seed, st);
+  if (rc != HA_OK) return rc;
+  uint8_t* codes_q = base + lay.codes_q;
+  uint8_t* codes_k = base + lay.codes_k;
+  rc = launch_lsh_hash(Q, codes_q, (int64_t)g.BH * g.n, g.d, g.dtype, proj, g.r, st);
+  if (rc != HA_OK) return rc;
+  rc = launch_lsh_hash(K, codes_k, (int64_t)g.BH * g.n, g.d, g.dtype, proj, g.r, st);
+  if (rc != HA_OK) return rc;
+  rc = launch_seg_sort_nodes(codes_q, codes_k, (int32_t*)(base + lay.perm_q), (int32_t*)(base + lay.perm_k),
+                             (int32_t*)(base + lay.pos_k), g.m > 0 ? samples : nullptr,
+                             (int32_t*)(base + lay.samp_blk), (uint32_t*)(base + lay.sort_hist), g, st);
+  if (rc != HA_OK) return rc;
+  Alg2Args a{};
+  a.Q = Q;
+  a.K = K;
+  a.V = V;
+  a.out = out;
+  a.lse = lse;
+  a.g = g;
+  a.perm_q = (const int32_t*)(base + lay.perm_q);
+  a.perm_k = (const int32_t*)(base + lay.perm_k);
+  a.pos_k = (const int32_t*)(base + lay.pos_k);
+  a.samples = samples;
+  a.samp_blk = (const int32_t*)(base + lay.samp_blk);
+  a.pos_q = (int32_t*)(base + al.pos_q);
+  a.tau_rows = (int32_t*)(base + al.tau_rows);
+  a.log_unm_t = (float*)(base + al.log_unmasked_t);
+  a.log_tau = (float*)(base + al.log_tau);
+  a.vw = (double*)(base + al.vnorm_w);
+  a.vmax = (unsigned long long*)(base + al.vnorm_max);
+  a.vq = (uint32_t*)(base + al.vnorm_q);
+  a.vprefix = (unsigned long long*)(base + al.vnorm_prefix);
+  a.vsamp = (int32_t*)(base + al.vnorm_samples);
+  a.vlogw = (float*)(base + al.vnorm_logw);
+  a.seed = params->seed;
+  a.cap_scale = opt->cap_scale;
+  a.kappa = opt->kappa;
+  a.vnorm = opt->vnorm_sampling ? 1 : 0;
+  return launch_alg2(a, st);
 }
 
 const char* ha_strerror(int status) {

@@ -1,0 +1,83 @@
+"""GPU parity of the Algorithm 2 / Lemma 2 options (hyperattn_forward_alg2) against the
+oracle's dense evaluation: the draws (rows of T, rows drawn by squared value norm and
+their quantised weights) bit-exact, log tau and log d~ within fp32 accuracy, outputs
+within the forward's tolerance (bf16: 2e-3 + half an ulp + the operand-free fp32 error;
+fp32: 1e-5 + 1e-5 |ref|; these kernels multiply in fp32, nothing is rounded to bf16 before
+the output)."""
+import numpy as np
+import pytest
+
+import synth_inputs
+from oracle import hyperattn_oracle as orc
+from ha_testutil import assert_close, have_gpu, to_device, to_host
+
+pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not have_gpu(), reason="needs a GPU")]
+
+
+@pytest.fixture(scope="module")
+def ha():
+    import paper_2310_05869_amd as mod
+    mod.lib()
+    return mod
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    return t
+
+
+CASES = [  # dtype, d, n, b, m, r, cap_scale, kappa, vnorm
+    ("bf16", 64, 512, 64, 48, 5, 0.0, 0.0, False),      # no caps: the Section 4 estimator
+    ("bf16", 64, 512, 64, 48, 5, 8.0, 1.2, False),      # both caps bind on part of the rows (12 % / 65 %)
+    ("bf16", 128, 768, 96, 100, 6, 1e-4, 2.0, False),   # cap below every entry
+    ("bf16", 128, 768, 96, 100, 6, 4.0, 1.1, True),     # Lemma 2's value product, caps binding (27 % / 86 %)
+    ("fp32", 64, 384, 32, 20, 4, 25.0, 1.5, True),
+    ("fp32", 64, 384, 32, 20, 4, 0.0, 0.0, True),
+    ("bf16", 64, 600, 200, 7, 7, 10.0, 0.0, True),      # block not a multiple of the row tile, cap without lower cap
+]
+
+
+@pytest.mark.parametrize("dtype,d,n,b,m,r,cap_scale,kappa,vnorm", CASES)
+def test_alg2_options_match_the_oracle(ha, torch, dtype, d, n, b, m, r, cap_scale, kappa, vnorm):
+    print(f"alg2 {dtype} d={d} n={n} b={b} m={m} r={r} cap={cap_scale} kappa={kappa} vnorm={vnorm}", flush=True)
+    cfg = dict(B=1, H=2, n=n, d=d, dtype=dtype, law="iid")
+    Q, K, V = synth_inputs.make_qkv(cfg, seed=11 + n)
+    rng = np.random.default_rng(n)
+    V = V * rng.uniform(0.2, 2.0, size=(1, 2, n, 1)).astype(np.float32)       # unequal value-row norms
+    V = synth_inputs.round_to_bf16(V) if dtype == "bf16" else V.astype(np.float32)
+    seed = 5
+    tq, tk, tv = (to_device(x, dtype) for x in (Q, K, V))
+    out, lse, ws = ha.hyperattn_forward_alg2(tq, tk, tv, b, m, r, seed=seed, cap_scale=cap_scale, kappa=kappa,
+                                             vnorm_sampling=vnorm)
+    torch.cuda.synchronize()
+    shape = ha.make_shape(1, 2, n, d, ha.HA_BF16 if dtype == "bf16" else ha.HA_FP32)
+    params = ha.make_params(b, m, r, False, 4096, seed)
+    views = ha.alg2_workspace_views(ws, shape, params)
+    ref_out, ref_lse, ref_tau = orc.hyperattn_forward_alg2(Q, K, V, b=b, m=m, r=r, seed=seed, cap_scale=cap_scale,
+                                                           kappa=kappa, vnorm_sampling=vnorm)
+    if cap_scale > 0 or kappa > 0:   # the options must actually act in this instance, or the case tests nothing
+        plain = orc.hyperattn_forward_alg2(Q, K, V, b=b, m=m, r=r, seed=seed)[1]
+        changed = np.abs(plain - ref_lse) > 1e-9
+        print(f"  caps change log d~ on {changed.mean():.0%} of the rows", flush=True)
+        assert changed.any()
+    np.testing.assert_array_equal(views["tau_rows"].cpu().numpy(), orc.tau_rows(seed, n, m))
+    np.testing.assert_allclose(views["log_tau"].cpu().numpy(), ref_tau, rtol=2e-5, atol=2e-5)
+    if vnorm:
+        for bh in range(2):
+            np.testing.assert_array_equal(views["vnorm_q"][bh].cpu().numpy(), orc.vnorm_weights(V[0, bh]))
+            idx, logw = orc.vnorm_samples(V[0, bh], seed, bh, m)
+            np.testing.assert_array_equal(views["vnorm_samples"][bh].cpu().numpy(), idx)
+            np.testing.assert_allclose(views["vnorm_logw"][bh].cpu().numpy(), logw, rtol=1e-6, atol=1e-6)
+    np.testing.assert_allclose(to_host(lse), ref_lse, rtol=3e-5, atol=3e-5)
+    assert_close(to_host(out), ref_out, dtype, "out")
+
+
+def test_alg2_rejects_causal_and_bad_workspace(ha, torch):
+    print("alg2 errors", flush=True)
+    shape = ha.make_shape(1, 1, 256, 64, ha.HA_BF16)
+    with pytest.raises(ha.HyperAttnError):
+        ha.ha_alg2_workspace_layout(shape, ha.make_params(64, 16, 7, True, 64, 0))
+    q = torch.zeros((1, 1, 256, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(ha.HyperAttnError):
+        ha.hyperattn_forward_alg2(q, q, q, 64, 16, 7, workspace=torch.zeros(256, dtype=torch.uint8, device="cuda"))
