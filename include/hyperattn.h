@@ -105,7 +105,7 @@ size_t ha_workspace_bytes(const ha_shape* shape, const ha_params* params);
 /* HyperAttention forward (Algorithm 3 in its Section 4 form; Algorithm 4 when
  * params->causal).  out: [B,H,n,d] of shape->dtype; lse: float [B,H,n].
  * HA_ERR_SHAPE unless: d in {64,128}; 1 <= r <= 8; b >= 1; 0 <= m <= 4096;
- * b <= 4096; unmasked: n % b == 0; causal: n_min >= 1 and either n <= n_min
+ * b <= 4096; B*H <= 2^20, n <= 2^22 and B*H*n <= 2^30; unmasked: n % b == 0; causal: n_min >= 1 and either n <= n_min
  * (plain exact causal attention) or n / n_min is a power of two with
  * n_min % b == 0.  The hyperplanes and sample indices are those
  * ha_make_projection / ha_make_samples return for params->seed. */

@@ -42,6 +42,7 @@ static int make_geometry(const ha_shape* sh, const ha_params* p, Geometry* g) {
   if (p->r < 1 || p->r > 8) return HA_ERR_SHAPE;
   if (p->b < 1 || p->b > 4096 || p->m < 0 || p->m > 4096) return HA_ERR_SHAPE;
   if ((int64_t)sh->B * sh->H > (1 << 20) || sh->n > (1 << 22)) return HA_ERR_SHAPE;
+  if ((int64_t)sh->B * sh->H * sh->n > (1ll << 30)) return HA_ERR_SHAPE;  // launch grids and row ids are 32-bit
   g->BH = sh->B * sh->H;
   g->n = sh->n;
   g->d = sh->d;
@@ -508,6 +509,7 @@ static int exact_forward_impl(const void* Q, const void* K, const void* V, void*
   if (sh->dtype != HA_BF16 && sh->dtype != HA_FP32) return HA_ERR_DTYPE;
   if (sh->B < 0 || sh->H < 0 || sh->n < 0 || (sh->d != 64 && sh->d != 128)) return HA_ERR_SHAPE;
   if ((int64_t)sh->B * sh->H > (1 << 20) || sh->n > (1 << 22)) return HA_ERR_SHAPE;
+  if ((int64_t)sh->B * sh->H * sh->n > (1ll << 30)) return HA_ERR_SHAPE;
   if (sh->B == 0 || sh->H == 0 || sh->n == 0) return HA_OK;
   if (!Q || !K || !V || !out || !lse) return HA_ERR_NULL;
   if (out_f32 && sh->dtype != HA_BF16) return HA_ERR_DTYPE;
