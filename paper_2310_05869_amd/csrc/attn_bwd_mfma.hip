@@ -543,7 +543,7 @@ static int launch_bwd_d(const BwdArgs& a, int mode, int grid, hipStream_t st) {
     default: return HA_ERR_SHAPE;
   }
 }
-int bwd_grid(const BwdArgs& a, int mode) {
+int64_t bwd_grid(const BwdArgs& a, int mode) {
   const Geometry& g = a.f.g;
   if (mode == kBwdDqNode || mode == kBwdDkvBlock) return node_grid<kRT>(g);
   if (mode == kBwdDqExact || mode == kBwdDkvExact) return exact_grid<kRT>(a.f);
@@ -552,7 +552,9 @@ int bwd_grid(const BwdArgs& a, int mode) {
 
 int launch_attn_bwd_mfma(const BwdArgs& a, int mode, hipStream_t st) {
   if (a.f.g.dtype != HA_BF16) return HA_ERR_DTYPE;
-  const int grid = bwd_grid(a, mode);
+  const int64_t grid64 = bwd_grid(a, mode);
+  if (grid64 > kMaxGrid) return HA_ERR_SHAPE;
+  const int grid = (int)grid64;
   if (a.f.g.d == 128) return launch_bwd_d<128>(a, mode, grid, st);
   if (a.f.g.d == 64) return launch_bwd_d<64>(a, mode, grid, st);
   return HA_ERR_SHAPE;

@@ -61,9 +61,9 @@ __device__ inline TileWork decode_node_tile(const AttnArgs& a, int idx) {
 }
 
 template <int QT>
-__host__ __device__ inline int node_grid(const Geometry& g) {
+__host__ __device__ inline int64_t node_grid(const Geometry& g) {
   const int tpb = (g.b + QT - 1) / QT;
-  return g.levels * g.BH * (g.n_cov / g.b) * tpb;
+  return (int64_t)g.levels * g.BH * (g.n_cov / g.b) * tpb;
 }
 
 template <int QT>
@@ -86,12 +86,14 @@ __device__ inline TileWork decode_exact_tile(const AttnArgs& a, int idx) {
 }
 
 template <int QT>
-__host__ __device__ inline int exact_grid(const AttnArgs& a) {
+__host__ __device__ inline int64_t exact_grid(const AttnArgs& a) {
   const int eb = a.exact_block;
   const int tpb = (eb + QT - 1) / QT;
   const int nblk = (a.exact_rows_q + eb - 1) / eb;
-  return a.g.BH * nblk * tpb;
+  return (int64_t)a.g.BH * nblk * tpb;
 }
+
+constexpr int64_t kMaxGrid = 0x7fffffff;  // workgroup ids are decoded as 32-bit integers
 
 // Builds the key list of a node tile in LDS.  `list` has room for b + m entries
 // rounded up to a multiple of 64; `scratch` for (NT/64 + 1) ints.  All NT

@@ -203,8 +203,10 @@ static int launch_generic_t(const AttnArgs& a, int mode, int grid, hipStream_t s
 }
 
 int launch_attn_generic(const AttnArgs& a, int mode, hipStream_t st) {
-  const int grid = mode == kModeNode ? node_grid<kGQT>(a.g) : exact_grid<kGQT>(a);
-  if (grid <= 0) return HA_OK;
+  const int64_t grid64 = mode == kModeNode ? node_grid<kGQT>(a.g) : exact_grid<kGQT>(a);
+  if (grid64 <= 0) return HA_OK;
+  if (grid64 > kMaxGrid) return HA_ERR_SHAPE;
+  const int grid = (int)grid64;
   if (a.g.dtype == HA_FP32) return launch_generic_t<float>(a, mode, grid, st);
   if (a.g.dtype == HA_BF16) return launch_generic_t<uint16_t>(a, mode, grid, st);
   return HA_ERR_DTYPE;

@@ -601,8 +601,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
 
 template <int D, int MODE, int NW>
 static int launch_one(const AttnArgs& a, hipStream_t st) {
-  const int grid = MODE == kModeNode ? node_grid<32 * NW>(a.g) : exact_grid<32 * NW>(a);
+  const int64_t grid = MODE == kModeNode ? node_grid<32 * NW>(a.g) : exact_grid<32 * NW>(a);
   if (grid <= 0) return HA_OK;
+  if (grid > kMaxGrid) return HA_ERR_SHAPE;
   size_t lds = mfma_lds_bytes<D>(a.g.b, a.g.m, MODE);
   if (lds < (size_t)NW * EpLds<D>::WAVE) lds = (size_t)NW * EpLds<D>::WAVE;
   static std::atomic<uint64_t> lds_set{0};  // per instantiation: devices on which the LDS limit is raised
