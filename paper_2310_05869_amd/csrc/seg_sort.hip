@@ -53,6 +53,12 @@ template <int kSortWaves>
 __global__ __launch_bounds__(kSortWaves * 64) void seg_sort_kernel(SortArgs a) {
   __shared__ uint32_t hist[kSortWaves][256];
   __shared__ uint32_t bucket_base[256];
+  // chunked scatter: the chunk is first ordered inside LDS, then written out in that order, so
+  // that a wave's 64 stores fall into a few runs of consecutive entries instead of 64 places
+  constexpr bool kStaged = (kSortWaves == kChunkWaves);
+  __shared__ uint32_t lbase[kStaged ? 256 : 1];        // where each bucket starts inside the chunk
+  __shared__ int32_t staged[kStaged ? kChunk : 1];
+  __shared__ uint8_t scode[kStaged ? kChunk : 1];
 
   const uint8_t* codes;
   int32_t* perm;
@@ -160,18 +166,20 @@ __global__ __launch_bounds__(kSortWaves * 64) void seg_sort_kernel(SortArgs a) {
         if (c < chunk) before += v;
         all += v;
       }
-      total = all;  // the bucket's size in the whole segment
+      if (kStaged) lbase[tid] = total;  // the bucket's size in this chunk
+      total = all;                      // the bucket's size in the whole segment
     }
     bucket_base[tid] = total;
   }
   if (a.phase == 1) return;
   __syncthreads();
-  if (w == 0) {
+  // exclusive prefix sums over the 256 buckets, one wave per array
+  auto scan256 = [&](uint32_t* arr) {
     uint32_t v[4], sum = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       v[j] = sum;
-      sum += bucket_base[lane * 4 + j];
+      sum += arr[lane * 4 + j];
     }
     uint32_t incl = sum;
 #pragma unroll
@@ -181,8 +189,10 @@ __global__ __launch_bounds__(kSortWaves * 64) void seg_sort_kernel(SortArgs a) {
     }
     const uint32_t excl = incl - sum;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) bucket_base[lane * 4 + j] = excl + v[j];
-  }
+    for (int j = 0; j < 4; ++j) arr[lane * 4 + j] = excl + v[j];
+  };
+  if (w == 0) scan256(bucket_base);
+  if (kStaged && a.phase == 2 && w == 1) scan256(lbase);
   __syncthreads();
   if (a.phase == 2 && tid < 256) bucket_base[tid] += before;
   __syncthreads();
@@ -214,10 +224,23 @@ __global__ __launch_bounds__(kSortWaves * 64) void seg_sort_kernel(SortArgs a) {
         const uint32_t dest = bucket_base[code] + run + rank;
         __builtin_amdgcn_wave_barrier();
         if (rank == cnt - 1) hist[w][code] = run + cnt;  // one lane per distinct key
-        perm[dest] = value_base + i;
+        if (kStaged && a.phase == 2) {
+          const uint32_t lr = lbase[code] + run + rank;  // place inside the chunk's own order
+          staged[lr] = value_base + i;
+          scode[lr] = (uint8_t)code;
+        } else {
+          perm[dest] = value_base + i;
+        }
         if (pos) pos[i] = (int32_t)dest;  // (chunked: pos points at this chunk's rows, dest is segment-wide)
       }
       __builtin_amdgcn_wave_barrier();
+    }
+  }
+  if (kStaged && a.phase == 2) {
+    __syncthreads();
+    for (int j = tid; j < s; j += kSortWaves * 64) {
+      const uint32_t c = scode[j];
+      perm[bucket_base[c] + ((uint32_t)j - lbase[c])] = staged[j];
     }
   }
 
