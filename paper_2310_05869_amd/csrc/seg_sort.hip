@@ -2,8 +2,10 @@
 // sort of 8-bit bucket codes, independently per segment (one segment per head,
 // per node of the causal recursion, and per tensor Q / K).
 //
-// Keys have at most 256 distinct values, so one counting pass does it.  A
-// segment is sorted by one workgroup of 16 waves entirely through LDS:
+// Keys have at most 256 distinct values, so one counting pass does it.
+//
+// Whole-segment kernel (the single-stage entry point): a segment is sorted by
+// one workgroup of 16 waves entirely through LDS:
 //   1. wave w histograms its contiguous slice of the segment (LDS atomics on
 //      integers);
 //   2. the 16 x 256 counters are turned into starting offsets in (bucket, wave)
@@ -11,17 +13,23 @@
 //   3. every wave walks its slice again in order, 64 keys at a time; a lane's
 //      rank among the equal keys of its 64 is a popcount of a ballot-built peer
 //      mask, so equal keys keep their original order inside the wave too.
-// Traffic is 2 bytes read and 8 bytes written per key.
 //
 // Long segments (the upper levels of the causal recursion have 64 segments of
 // 65536 keys) would leave most of the chip idle, so the forward pass sorts in
-// chunks of kChunk keys, one workgroup each, in two launches:
+// chunks of kChunk keys, one 4-wave workgroup each, in two launches:
 //   A. every chunk's bucket counts go to a table in the workspace;
-//   B. every chunk recounts per wave, finds where its buckets start (buckets
-//      before it in the segment + the same bucket in earlier chunks) and
-//      scatters, with the same in-wave ranking: the result is the same stable
-//      order, whatever the chunking.
-// A third small launch records the sorted block of every sampled key.
+//   B. every chunk finds where its buckets start (buckets before it in the
+//      segment + the same bucket in earlier chunks), ranks its keys and
+//      scatters: the result is the same stable order, whatever the chunking.
+// In B the peer mask of a key comes from LDS rather than from ballots: the
+// lanes of a 64-key tile OR their lane bit into a 64-bit word per (wave,
+// bucket) and read the word back; the same 16-byte slot carries the wave's
+// running rank for the bucket, so ranking a tile costs one LDS atomic, one
+// 16-byte read and one 16-byte write.  The chunk is first ordered inside LDS and
+// then written out in that order, so a wave's 64 stores fall into a few runs of
+// consecutive entries.  B also records the sorted block of every sampled key
+// (the factor 1 - M_{i,l_j} of Algorithm 2 needs nothing else).
+// Traffic is 2 bytes read and 8 (Q) or 12 (K) bytes written per key.
 #include "ha_common.h"
 
 namespace ha {
@@ -35,93 +43,28 @@ struct SortArgs {
   int32_t* perm_q;
   int32_t* perm_k;
   int32_t* pos_k;
-  const int32_t* samples;  // node mode: [total_nodes][m] sample indices ...
+  const int32_t* samples;  // chunked: [total_nodes][m] sample indices ...
   int32_t* samp_blk;       // ... and where to put the sorted block of each: [BH][total_nodes][m]
   Geometry g;
-  int32_t flat;  // 1: n_seg consecutive segments of seg_len keys in codes_q -> perm_q / pos_k, local indices
-  int32_t seg_len;
-  // chunked node mode: bucket counts of every chunk, and the first workgroup of every level
-  uint32_t* chunk_hist;   // [chunks][256]
-  int32_t phase;          // 0: whole segments (one launch); 1: count chunks; 2: scatter chunks
+  int32_t seg_len;         // whole-segment mode: consecutive segments of seg_len keys in codes_q -> perm_q / pos_k
+  // chunked mode: bucket counts of every chunk, and the first workgroup of every level
+  uint32_t* chunk_hist;    // [chunks][256]
   int32_t lvl_wg[kSortMaxLevels + 1];
 };
 
 constexpr int kFlatWaves = 16;   // whole-segment mode: one workgroup has to cover a long segment
 constexpr int kChunkWaves = 4;   // chunked mode: many small workgroups per CU hide each other's barriers
 
-template <int kSortWaves>
-__global__ __launch_bounds__(kSortWaves * 64) void seg_sort_kernel(SortArgs a) {
+__global__ __launch_bounds__(kFlatWaves * 64) void seg_sort_kernel(SortArgs a) {
+  constexpr int kSortWaves = kFlatWaves;
   __shared__ uint32_t hist[kSortWaves][256];
   __shared__ uint32_t bucket_base[256];
-  // chunked scatter: the chunk is first ordered inside LDS, then written out in that order, so
-  // that a wave's 64 stores fall into a few runs of consecutive entries instead of 64 places
-  constexpr bool kStaged = (kSortWaves == kChunkWaves);
-  __shared__ uint32_t lbase[kStaged ? 256 : 1];        // where each bucket starts inside the chunk
-  __shared__ int32_t staged[kStaged ? kChunk : 1];
-  __shared__ uint8_t scode[kStaged ? kChunk : 1];
 
-  const uint8_t* codes;
-  int32_t* perm;
-  int32_t* pos;
-  int s, value_base;
-  const int32_t* smp = nullptr;
-  int32_t* sblk = nullptr;
-  int chunk = 0, nchunks = 1, chunk_off = 0;
-  uint32_t* seg_hist = nullptr;  // chunked: bucket counts of this segment's chunks [nchunks][256]
-  if (a.flat) {
-    const int64_t off = (int64_t)blockIdx.x * a.seg_len;
-    codes = a.codes_q + off;
-    perm = a.perm_q + off;
-    pos = a.pos_k + off;
-    s = a.seg_len;
-    value_base = 0;
-  } else if (a.phase == 0) {
-    const int which = blockIdx.x & 1;  // 0: queries, 1: keys
-    const int rest = blockIdx.x >> 1;
-    const int heap = rest % a.g.total_nodes;
-    const int bh = rest / a.g.total_nodes;
-    const int level = 31 - __clz(heap + 1);
-    const int node = heap + 1 - (1 << level);
-    const NodeRef nr = node_ref(a.g, level, node);
-    s = nr.s;
-    value_base = which ? nr.k_start : nr.q_start;
-    codes = (which ? a.codes_k : a.codes_q) + (int64_t)bh * a.g.n + value_base;
-    const int64_t off = ((int64_t)level * a.g.BH + bh) * a.g.n_cov + (int64_t)node * nr.s;
-    perm = (which ? a.perm_k : a.perm_q) + off;
-    pos = which ? a.pos_k + off : nullptr;
-    if (which && a.samples && a.samp_blk && a.g.m > 0) {
-      smp = a.samples + (int64_t)heap * a.g.m;
-      sblk = a.samp_blk + ((int64_t)bh * a.g.total_nodes + heap) * a.g.m;
-    }
-  } else {
-    // chunked: workgroups ordered (level, head, node, tensor, chunk); a segment's chunks are consecutive
-    int level = 0, wg0 = 0;
-#pragma unroll
-    for (int l = 0; l < kSortMaxLevels; ++l)
-      if (l < a.g.levels && (int)blockIdx.x >= a.lvl_wg[l]) {
-        level = l;
-        wg0 = a.lvl_wg[l];
-      }
-    const NodeRef probe = node_ref(a.g, level, 0);
-    nchunks = (probe.s + kChunk - 1) / kChunk;
-    const int nodes = a.g.causal ? (1 << level) : 1;
-    int idx = (int)blockIdx.x - wg0;
-    chunk = idx % nchunks;
-    idx /= nchunks;
-    const int which = idx & 1;
-    idx >>= 1;
-    const int node = idx % nodes;
-    const int bh = idx / nodes;
-    const NodeRef nr = node_ref(a.g, level, node);
-    chunk_off = chunk * kChunk;
-    s = min(kChunk, nr.s - chunk_off);
-    value_base = (which ? nr.k_start : nr.q_start) + chunk_off;
-    codes = (which ? a.codes_k : a.codes_q) + (int64_t)bh * a.g.n + value_base;
-    const int64_t off = ((int64_t)level * a.g.BH + bh) * a.g.n_cov + (int64_t)node * nr.s;
-    perm = (which ? a.perm_k : a.perm_q) + off;          // destinations are segment-wide
-    pos = which ? a.pos_k + off + chunk_off : nullptr;    // sources are this chunk's
-    seg_hist = a.chunk_hist + ((int64_t)blockIdx.x - chunk) * 256;
-  }
+  const int64_t off = (int64_t)blockIdx.x * a.seg_len;
+  const uint8_t* codes = a.codes_q + off;
+  int32_t* perm = a.perm_q + off;
+  int32_t* pos = a.pos_k + off;
+  const int s = a.seg_len;
 
   const int tid = threadIdx.x;
   const int w = tid >> 6, lane = tid & 63;
@@ -149,37 +92,22 @@ __global__ __launch_bounds__(kSortWaves * 64) void seg_sort_kernel(SortArgs a) {
   __syncthreads();
 
   // offsets in (bucket, wave) order
-  uint32_t total = 0;
-  uint32_t before = 0;  // chunked: keys of this bucket in earlier chunks of the segment
   if (tid < 256) {
+    uint32_t total = 0;
     for (int ww = 0; ww < kSortWaves; ++ww) {
       const uint32_t v = hist[ww][tid];
       hist[ww][tid] = total;
       total += v;
     }
-    if (a.phase == 1) {
-      seg_hist[chunk * 256 + tid] = total;
-    } else if (a.phase == 2) {
-      uint32_t all = 0;
-      for (int c = 0; c < nchunks; ++c) {
-        const uint32_t v = seg_hist[c * 256 + tid];
-        if (c < chunk) before += v;
-        all += v;
-      }
-      if (kStaged) lbase[tid] = total;  // the bucket's size in this chunk
-      total = all;                      // the bucket's size in the whole segment
-    }
     bucket_base[tid] = total;
   }
-  if (a.phase == 1) return;
   __syncthreads();
-  // exclusive prefix sums over the 256 buckets, one wave per array
-  auto scan256 = [&](uint32_t* arr) {
+  if (w == 0) {  // exclusive prefix sums over the 256 buckets
     uint32_t v[4], sum = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       v[j] = sum;
-      sum += arr[lane * 4 + j];
+      sum += bucket_base[lane * 4 + j];
     }
     uint32_t incl = sum;
 #pragma unroll
@@ -189,12 +117,8 @@ __global__ __launch_bounds__(kSortWaves * 64) void seg_sort_kernel(SortArgs a) {
     }
     const uint32_t excl = incl - sum;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) arr[lane * 4 + j] = excl + v[j];
-  };
-  if (w == 0) scan256(bucket_base);
-  if (kStaged && a.phase == 2 && w == 1) scan256(lbase);
-  __syncthreads();
-  if (a.phase == 2 && tid < 256) bucket_base[tid] += before;
+    for (int j = 0; j < 4; ++j) bucket_base[lane * 4 + j] = excl + v[j];
+  }
   __syncthreads();
 
   for (int tb = t0; tb < t1; tb += kAhead) {
@@ -224,46 +148,235 @@ __global__ __launch_bounds__(kSortWaves * 64) void seg_sort_kernel(SortArgs a) {
         const uint32_t dest = bucket_base[code] + run + rank;
         __builtin_amdgcn_wave_barrier();
         if (rank == cnt - 1) hist[w][code] = run + cnt;  // one lane per distinct key
-        if (kStaged && a.phase == 2) {
-          const uint32_t lr = lbase[code] + run + rank;  // place inside the chunk's own order
-          staged[lr] = value_base + i;
-          scode[lr] = (uint8_t)code;
-        } else {
-          perm[dest] = value_base + i;
-        }
-        if (pos) pos[i] = (int32_t)dest;  // (chunked: pos points at this chunk's rows, dest is segment-wide)
+        perm[dest] = i;
+        pos[i] = (int32_t)dest;
       }
       __builtin_amdgcn_wave_barrier();
     }
   }
-  if (kStaged && a.phase == 2) {
-    __syncthreads();
-    for (int j = tid; j < s; j += kSortWaves * 64) {
-      const uint32_t c = scode[j];
-      perm[bucket_base[c] + ((uint32_t)j - lbase[c])] = staged[j];
-    }
-  }
-
-  // Algorithm 2's factor (1 - M_{i,l_j}) only needs the sorted block of each
-  // sampled key; record it here, where the key segment's positions are at hand.
-  if (sblk) {
-    __threadfence_block();
-    __syncthreads();
-    for (int j = tid; j < a.g.m; j += kSortWaves * 64) sblk[j] = pos[smp[j]] / a.g.b;
-  }
 }
 
-// Algorithm 2's factor (1 - M_{i,l_j}): the sorted block of every sampled key, one workgroup per (head, node).
-__global__ __launch_bounds__(256) void sample_block_kernel(const int32_t* __restrict__ pos_k, const int32_t* __restrict__ samples,
-                                                           int32_t* __restrict__ samp_blk, Geometry g) {
-  const int heap = blockIdx.x % g.total_nodes;
-  const int bh = blockIdx.x / g.total_nodes;
-  const int level = 31 - __clz(heap + 1);
-  const int node = heap + 1 - (1 << level);
-  const NodeRef nr = node_ref(g, level, node);
-  const int64_t off = ((int64_t)level * g.BH + bh) * g.n_cov + (int64_t)node * nr.s;
-  for (int j = threadIdx.x; j < g.m; j += blockDim.x)
-    samp_blk[((int64_t)bh * g.total_nodes + heap) * g.m + j] = pos_k[off + samples[(int64_t)heap * g.m + j]] / g.b;
+// ---------------------------------------------------------------------------
+// Chunked passes.
+// ---------------------------------------------------------------------------
+struct ChunkRef {
+  const uint8_t* codes;  // the chunk's keys
+  int32_t* perm;         // the segment's permutation (destinations are segment-wide)
+  int32_t* pos;          // the chunk's slice of pos_k, or null (queries)
+  const uint32_t* seg_hist;  // bucket counts of the segment's chunks [nchunks][256]
+  uint32_t* own_hist;        // this chunk's row of that table
+  const int32_t* smp;    // key chunks with samples: the node's sample indices ...
+  int32_t* sblk;         // ... and where the sorted block of each goes
+  int s, value_base, chunk, nchunks, chunk_off;
+};
+
+// workgroups are ordered (level, head, node, tensor, chunk); a segment's chunks are consecutive
+__device__ inline ChunkRef decode_chunk(const SortArgs& a, int wg) {
+  ChunkRef c{};
+  int level = 0, wg0 = 0;
+#pragma unroll
+  for (int l = 0; l < kSortMaxLevels; ++l)
+    if (l < a.g.levels && wg >= a.lvl_wg[l]) {
+      level = l;
+      wg0 = a.lvl_wg[l];
+    }
+  const NodeRef probe = node_ref(a.g, level, 0);
+  c.nchunks = (probe.s + kChunk - 1) / kChunk;
+  const int nodes = a.g.causal ? (1 << level) : 1;
+  int idx = wg - wg0;
+  c.chunk = idx % c.nchunks;
+  idx /= c.nchunks;
+  const int which = idx & 1;  // 0: queries, 1: keys
+  idx >>= 1;
+  const int node = idx % nodes;
+  const int bh = idx / nodes;
+  const NodeRef nr = node_ref(a.g, level, node);
+  c.chunk_off = c.chunk * kChunk;
+  c.s = min(kChunk, nr.s - c.chunk_off);
+  c.value_base = (which ? nr.k_start : nr.q_start) + c.chunk_off;
+  c.codes = (which ? a.codes_k : a.codes_q) + (int64_t)bh * a.g.n + c.value_base;
+  const int64_t off = ((int64_t)level * a.g.BH + bh) * a.g.n_cov + (int64_t)node * nr.s;
+  c.perm = (which ? a.perm_k : a.perm_q) + off;
+  c.pos = which ? a.pos_k + off + c.chunk_off : nullptr;
+  uint32_t* seg = a.chunk_hist + ((int64_t)wg - c.chunk) * 256;
+  c.seg_hist = seg;
+  c.own_hist = seg + (int64_t)c.chunk * 256;
+  if (which && a.samples && a.samp_blk && a.g.m > 0) {
+    c.smp = a.samples + (int64_t)nr.heap * a.g.m;
+    c.sblk = a.samp_blk + ((int64_t)bh * a.g.total_nodes + nr.heap) * a.g.m;
+  }
+  return c;
+}
+
+// Thread t of the workgroup fetches keys [16 t, 16 t + 16) of the chunk: one
+// 16-byte load where the address allows it.  Keys past the chunk's end read as 0.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline u32x4 load_16_codes(const uint8_t* codes, int s, int t) {
+  const int i0 = 16 * t;
+  u32x4 v = {0, 0, 0, 0};
+  if (i0 + 16 <= s && (reinterpret_cast<uintptr_t>(codes) & 15u) == 0) {
+    v = *reinterpret_cast<const u32x4*>(codes + i0);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+      if (i0 + j < s) v[j >> 2] |= (uint32_t)codes[i0 + j] << (8 * (j & 3));
+  }
+  return v;
+}
+
+// Pass A: the chunk's bucket counts.
+__global__ __launch_bounds__(kChunkWaves * 64) void chunk_count_kernel(SortArgs a) {
+  __shared__ uint32_t hist[256];
+  const ChunkRef c = decode_chunk(a, (int)blockIdx.x);
+  const int tid = threadIdx.x;
+  const u32x4 v = load_16_codes(c.codes, c.s, tid);
+  hist[tid] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 16; ++j)
+    if (16 * tid + j < c.s) atomicAdd(&hist[(v[j >> 2] >> (8 * (j & 3))) & 255u], 1u);
+  __syncthreads();
+  c.own_hist[tid] = hist[tid];
+}
+
+// One 16-byte LDS slot per (wave, bucket) of pass B.
+struct __attribute__((aligned(16))) RankSlot {
+  unsigned long long peers;  // lanes of the tile being ranked that hold this bucket
+  uint32_t next;             // place inside the chunk's order of the wave's next key of this bucket
+  uint32_t shift;            // segment-wide destination = place inside the chunk + shift (mod 2^32)
+};
+
+constexpr int kTilesPerWave = kChunk / 64 / kChunkWaves;
+
+__host__ __device__ inline size_t chunk_scatter_lds(int nbk) {
+  return (size_t)kChunk + (size_t)kChunk * 4 + 64 + (size_t)kChunkWaves * nbk * sizeof(RankSlot);
+}
+
+// Pass B.  nbk = number of buckets (a power of two >= every code + 1, at most 256).
+__global__ __launch_bounds__(kChunkWaves * 64) void chunk_scatter_kernel(SortArgs a, int nbk) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char sm[];
+  uint8_t* codes_lds = sm;
+  uint32_t* staged = reinterpret_cast<uint32_t*>(sm + kChunk);
+  uint32_t* wave_tot = staged + kChunk;  // [2][kChunkWaves]
+  RankSlot* slot = reinterpret_cast<RankSlot*>(wave_tot + 16);
+
+  const ChunkRef c = decode_chunk(a, (int)blockIdx.x);
+  const int tid = threadIdx.x;
+  const int w = tid >> 6, lane = tid & 63;
+  const int s = c.s;
+
+  // the bucket's keys in earlier chunks of the segment, and in the whole segment
+  uint32_t before = 0, all = 0;
+  if (tid < nbk) {
+    for (int c0 = 0; c0 < c.nchunks; c0 += 8) {
+      uint32_t v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = (c0 + u < c.nchunks) ? c.seg_hist[(int64_t)(c0 + u) * 256 + tid] : 0u;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        all += v[u];
+        if (c0 + u < c.chunk) before += v[u];
+      }
+    }
+  }
+  {
+    const u32x4 v = load_16_codes(c.codes, s, tid);
+    *reinterpret_cast<u32x4*>(codes_lds + 16 * tid) = v;
+    for (int i = tid; i < kChunkWaves * nbk; i += kChunkWaves * 64) slot[i] = RankSlot{0ull, 0u, 0u};
+  }
+  __syncthreads();
+
+  // wave w ranks tiles [w kTilesPerWave, (w + 1) kTilesPerWave) of the chunk, in order
+  uint32_t code[kTilesPerWave];
+  RankSlot* my = slot + w * nbk;
+#pragma unroll
+  for (int u = 0; u < kTilesPerWave; ++u) {
+    const int i = (w * kTilesPerWave + u) * 64 + lane;
+    code[u] = codes_lds[i] & (uint32_t)(nbk - 1);  // (codes are below nbk by construction; keeps a bad one inside the table)
+    if (i < s) atomicAdd(&my[code[u]].next, 1u);
+  }
+  __syncthreads();
+
+  // starting places in (bucket, wave) order: exclusive sums over the buckets of the
+  // chunk's counts (place inside the chunk) and of the segment's counts (destination)
+  uint32_t cnt_w[kChunkWaves], mine = 0;
+  if (tid < nbk) {
+#pragma unroll
+    for (int ww = 0; ww < kChunkWaves; ++ww) {
+      cnt_w[ww] = slot[ww * nbk + tid].next;
+      mine += cnt_w[ww];
+    }
+  }
+  uint32_t inc_l = mine, inc_g = all;  // contributions of tid >= nbk are zero
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t ul = __shfl_up(inc_l, o), ug = __shfl_up(inc_g, o);
+    if (lane >= o) {
+      inc_l += ul;
+      inc_g += ug;
+    }
+  }
+  if (lane == 63) {
+    wave_tot[w] = inc_l;
+    wave_tot[kChunkWaves + w] = inc_g;
+  }
+  __syncthreads();
+  if (tid < nbk) {
+    uint32_t lb = inc_l - mine, gb = inc_g - all + before;
+#pragma unroll
+    for (int ww = 0; ww < kChunkWaves; ++ww)
+      if (ww < w) {
+        lb += wave_tot[ww];
+        gb += wave_tot[kChunkWaves + ww];
+      }
+    const uint32_t shift = gb - lb;
+#pragma unroll
+    for (int ww = 0; ww < kChunkWaves; ++ww) {
+      slot[ww * nbk + tid] = RankSlot{0ull, lb, shift};
+      lb += cnt_w[ww];
+    }
+  }
+  __syncthreads();
+
+  const unsigned long long lane_bit = 1ull << lane;
+#pragma unroll
+  for (int u = 0; u < kTilesPerWave; ++u) {
+    const int i = (w * kTilesPerWave + u) * 64 + lane;
+    if (i < s) {
+      RankSlot* sl = my + code[u];
+      atomicOr(&sl->peers, lane_bit);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      const RankSlot cur = *sl;  // after every lane's OR: LDS operations of a wave complete in order
+      const uint32_t rank = __popcll(cur.peers & (lane_bit - 1ull));
+      const uint32_t cnt = __popcll(cur.peers);
+      const uint32_t place = cur.next + rank;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      if (rank == cnt - 1) *sl = RankSlot{0ull, cur.next + cnt, cur.shift};  // one lane per distinct key
+      staged[place] = (code[u] << 12) | (uint32_t)(i & (kChunk - 1));
+      if (c.pos) c.pos[i] = (int32_t)(place + cur.shift);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+  __syncthreads();
+  for (int j = tid; j < s; j += kChunkWaves * 64) {
+    const uint32_t v = staged[j];
+    c.perm[(uint32_t)j + slot[v >> 12].shift] = c.value_base + (int32_t)(v & (kChunk - 1));
+  }
+
+  // the sorted block of the node's sampled keys that fall into this chunk
+  if (c.sblk) {
+    __threadfence_block();  // the positions were stored by other threads of this workgroup
+    __syncthreads();
+    for (int j = tid; j < a.g.m; j += kChunkWaves * 64) {
+      const int l = c.smp[j] - c.chunk_off;
+      if (l >= 0 && l < s)
+        c.sblk[j] = __hip_atomic_load(&c.pos[l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) / a.g.b;
+    }
+  }
 }
 
 int64_t seg_sort_chunks(const Geometry& g) {
@@ -280,31 +393,30 @@ int launch_seg_sort_nodes(const uint8_t* codes_q, const uint8_t* codes_k, int32_
                           int32_t* pos_k, const int32_t* samples, int32_t* samp_blk, uint32_t* chunk_hist,
                           const Geometry& g, hipStream_t st) {
   if (g.levels <= 0 || g.total_nodes <= 0) return HA_OK;
-  if (g.levels > kSortMaxLevels) return HA_ERR_SHAPE;
+  if (g.levels > kSortMaxLevels || g.r < 1 || g.r > 8) return HA_ERR_SHAPE;
   SortArgs a{};
   a.codes_q = codes_q;
   a.codes_k = codes_k;
   a.perm_q = perm_q;
   a.perm_k = perm_k;
   a.pos_k = pos_k;
+  a.samples = samples;
+  a.samp_blk = samp_blk;
   a.g = g;
   a.chunk_hist = chunk_hist;
-  int wg = 0;
+  int64_t wg = 0;
   for (int l = 0; l < g.levels; ++l) {
     const int s = g.causal ? (g.n >> (l + 1)) : g.n;
     const int nodes = g.causal ? (1 << l) : 1;
-    a.lvl_wg[l] = wg;
-    wg += 2 * g.BH * nodes * ((s + kChunk - 1) / kChunk);
+    a.lvl_wg[l] = (int32_t)wg;
+    wg += (int64_t)2 * g.BH * nodes * ((s + kChunk - 1) / kChunk);
+    if (wg > 0x7fffffff) return HA_ERR_SHAPE;
   }
-  a.lvl_wg[g.levels] = wg;
+  a.lvl_wg[g.levels] = (int32_t)wg;
+  const int nbk = 1 << g.r;  // bucket codes of Definition 1 are below 2^r
   dim3 grid((unsigned)wg), block(kChunkWaves * 64);
-  a.phase = 1;
-  hipLaunchKernelGGL(seg_sort_kernel<kChunkWaves>, grid, block, 0, st, a);
-  a.phase = 2;
-  hipLaunchKernelGGL(seg_sort_kernel<kChunkWaves>, grid, block, 0, st, a);
-  if (samples && samp_blk && g.m > 0)
-    hipLaunchKernelGGL(sample_block_kernel, dim3((unsigned)(g.BH * g.total_nodes)), dim3(256), 0, st, pos_k, samples,
-                       samp_blk, g);
+  hipLaunchKernelGGL(chunk_count_kernel, grid, block, 0, st, a);
+  hipLaunchKernelGGL(chunk_scatter_kernel, grid, block, chunk_scatter_lds(nbk), st, a, nbk);
   return check_launch();
 }
 
@@ -315,10 +427,9 @@ int launch_seg_sort_flat(const uint8_t* codes, int32_t* perm, int32_t* pos, int 
   a.codes_q = codes;
   a.perm_q = perm;
   a.pos_k = pos;
-  a.flat = 1;
   a.seg_len = seg_len;
   dim3 grid((unsigned)n_seg), block(kFlatWaves * 64);
-  hipLaunchKernelGGL(seg_sort_kernel<kFlatWaves>, grid, block, 0, st, a);
+  hipLaunchKernelGGL(seg_sort_kernel, grid, block, 0, st, a);
   return check_launch();
 }
 
