@@ -23,11 +23,13 @@
 //      scatters: the result is the same stable order, whatever the chunking.
 // In B the peer mask of a key comes from LDS rather than from ballots: the
 // lanes of a 64-key tile OR their lane bit into a 64-bit word per (wave,
-// bucket) and read the word back; the same 16-byte slot carries the wave's
-// running rank for the bucket, so ranking a tile costs one LDS atomic, one
-// 16-byte read and one 16-byte write.  The chunk is first ordered inside LDS and
-// then written out in that order, so a wave's 64 stores fall into a few runs of
-// consecutive entries.  B also records the sorted block of every sampled key
+// bucket) and read the word back; a counter per (wave, bucket) carries the
+// number of the wave's earlier keys of the bucket, and ends up as the wave's
+// bucket count, so no separate counting walk is needed.  Mask and counter
+// arrays are packed (8 and 4 bytes per bucket): wider slots would put the 2^r
+// buckets on a quarter of the LDS banks.  The chunk is first ordered inside LDS
+// and then written out in that order, so a wave's 64 stores fall into a few
+// runs of consecutive entries.  B also records the sorted block of every sampled key
 // (the factor 1 - M_{i,l_j} of Algorithm 2 needs nothing else).
 // Traffic is 2 bytes read and 8 (Q) or 12 (K) bytes written per key.
 #include "ha_common.h"
@@ -239,26 +241,25 @@ __global__ __launch_bounds__(kChunkWaves * 64) void chunk_count_kernel(SortArgs 
   c.own_hist[tid] = hist[tid];
 }
 
-// One 16-byte LDS slot per (wave, bucket) of pass B.
-struct __attribute__((aligned(16))) RankSlot {
-  unsigned long long peers;  // lanes of the tile being ranked that hold this bucket
-  uint32_t next;             // place inside the chunk's order of the wave's next key of this bucket
-  uint32_t shift;            // segment-wide destination = place inside the chunk + shift (mod 2^32)
-};
-
 constexpr int kTilesPerWave = kChunk / 64 / kChunkWaves;
 
+// LDS of pass B: the chunk's order (kChunk words, whose first quarter holds the keys
+// until they are in registers), wave totals, and per (wave, bucket) a 64-bit peer
+// mask (later the pair {first place, shift to the destination}) and a counter.
 __host__ __device__ inline size_t chunk_scatter_lds(int nbk) {
-  return (size_t)kChunk + (size_t)kChunk * 4 + 64 + (size_t)kChunkWaves * nbk * sizeof(RankSlot);
+  return (size_t)kChunk * 4 + 64 + (size_t)kChunkWaves * nbk * 12;
 }
 
 // Pass B.  nbk = number of buckets (a power of two >= every code + 1, at most 256).
 __global__ __launch_bounds__(kChunkWaves * 64) void chunk_scatter_kernel(SortArgs a, int nbk) {
   extern __shared__ __attribute__((aligned(16))) unsigned char sm[];
-  uint8_t* codes_lds = sm;
-  uint32_t* staged = reinterpret_cast<uint32_t*>(sm + kChunk);
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  uint32_t* staged = reinterpret_cast<uint32_t*>(sm);
+  const uint8_t* codes_lds = sm;
   uint32_t* wave_tot = staged + kChunk;  // [2][kChunkWaves]
-  RankSlot* slot = reinterpret_cast<RankSlot*>(wave_tot + 16);
+  unsigned long long* peers = reinterpret_cast<unsigned long long*>(wave_tot + 16);  // [kChunkWaves][nbk]
+  u32x2* first = reinterpret_cast<u32x2*>(peers);                                    // the same words, after the ranking
+  uint32_t* count = reinterpret_cast<uint32_t*>(peers + kChunkWaves * nbk);          // [kChunkWaves][nbk]
 
   const ChunkRef c = decode_chunk(a, (int)blockIdx.x);
   const int tid = threadIdx.x;
@@ -281,29 +282,57 @@ __global__ __launch_bounds__(kChunkWaves * 64) void chunk_scatter_kernel(SortArg
   }
   {
     const u32x4 v = load_16_codes(c.codes, s, tid);
-    *reinterpret_cast<u32x4*>(codes_lds + 16 * tid) = v;
-    for (int i = tid; i < kChunkWaves * nbk; i += kChunkWaves * 64) slot[i] = RankSlot{0ull, 0u, 0u};
+    *reinterpret_cast<u32x4*>(sm + 16 * tid) = v;
+    for (int i = tid; i < kChunkWaves * nbk; i += kChunkWaves * 64) {
+      peers[i] = 0ull;
+      count[i] = 0u;
+    }
   }
   __syncthreads();
 
-  // wave w ranks tiles [w kTilesPerWave, (w + 1) kTilesPerWave) of the chunk, in order
-  uint32_t code[kTilesPerWave];
-  RankSlot* my = slot + w * nbk;
+  // Wave w ranks tiles [w kTilesPerWave, (w + 1) kTilesPerWave) of the chunk, in order:
+  // a key's place among the wave's keys of its bucket = keys of the bucket in the wave's
+  // earlier tiles (the counter) + lanes below it in its tile that hold the bucket too.
+  // Afterwards the counters hold the wave's bucket counts.
+  uint32_t cr[kTilesPerWave];  // bucket | place among the wave's keys of the bucket << 8
+  unsigned long long* my_peers = peers + w * nbk;
+  uint32_t* my_count = count + w * nbk;
+  const unsigned long long lane_bit = 1ull << lane;
+#pragma unroll
+  for (int u = 0; u < kTilesPerWave; ++u) cr[u] = codes_lds[(w * kTilesPerWave + u) * 64 + lane] & (uint32_t)(nbk - 1);
 #pragma unroll
   for (int u = 0; u < kTilesPerWave; ++u) {
     const int i = (w * kTilesPerWave + u) * 64 + lane;
-    code[u] = codes_lds[i] & (uint32_t)(nbk - 1);  // (codes are below nbk by construction; keeps a bad one inside the table)
-    if (i < s) atomicAdd(&my[code[u]].next, 1u);
+    if (i < s) {
+      const uint32_t code = cr[u];
+      atomicOr(&my_peers[code], lane_bit);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      const unsigned long long pm = my_peers[code];  // after every lane's OR: LDS operations of a wave complete in order
+      const uint32_t seen = my_count[code];
+      const uint32_t rank = __popcll(pm & (lane_bit - 1ull));
+      const uint32_t cnt = __popcll(pm);
+      cr[u] = code | ((seen + rank) << 8);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      if (rank == cnt - 1) {  // one lane per distinct key
+        my_peers[code] = 0ull;
+        my_count[code] = seen + cnt;
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
   }
   __syncthreads();
 
-  // starting places in (bucket, wave) order: exclusive sums over the buckets of the
+  // first places in (bucket, wave) order: exclusive sums over the buckets of the
   // chunk's counts (place inside the chunk) and of the segment's counts (destination)
   uint32_t cnt_w[kChunkWaves], mine = 0;
   if (tid < nbk) {
 #pragma unroll
     for (int ww = 0; ww < kChunkWaves; ++ww) {
-      cnt_w[ww] = slot[ww * nbk + tid].next;
+      cnt_w[ww] = count[ww * nbk + tid];
       mine += cnt_w[ww];
     }
   }
@@ -329,42 +358,31 @@ __global__ __launch_bounds__(kChunkWaves * 64) void chunk_scatter_kernel(SortArg
         lb += wave_tot[ww];
         gb += wave_tot[kChunkWaves + ww];
       }
-    const uint32_t shift = gb - lb;
+    const uint32_t shift = gb - lb;  // destination in the segment = place in the chunk + shift (mod 2^32)
 #pragma unroll
     for (int ww = 0; ww < kChunkWaves; ++ww) {
-      slot[ww * nbk + tid] = RankSlot{0ull, lb, shift};
+      first[ww * nbk + tid] = (u32x2){lb, shift};
       lb += cnt_w[ww];
     }
   }
-  __syncthreads();
+  __syncthreads();  // (also: every wave has its keys in registers, the first quarter of `staged` is free)
 
-  const unsigned long long lane_bit = 1ull << lane;
+  // the chunk in its own sorted order: bucket << 12 | index within the chunk
 #pragma unroll
   for (int u = 0; u < kTilesPerWave; ++u) {
     const int i = (w * kTilesPerWave + u) * 64 + lane;
     if (i < s) {
-      RankSlot* sl = my + code[u];
-      atomicOr(&sl->peers, lane_bit);
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      const RankSlot cur = *sl;  // after every lane's OR: LDS operations of a wave complete in order
-      const uint32_t rank = __popcll(cur.peers & (lane_bit - 1ull));
-      const uint32_t cnt = __popcll(cur.peers);
-      const uint32_t place = cur.next + rank;
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      if (rank == cnt - 1) *sl = RankSlot{0ull, cur.next + cnt, cur.shift};  // one lane per distinct key
-      staged[place] = (code[u] << 12) | (uint32_t)(i & (kChunk - 1));
-      if (c.pos) c.pos[i] = (int32_t)(place + cur.shift);
+      const uint32_t code = cr[u] & 255u;
+      const u32x2 f = first[w * nbk + code];
+      const uint32_t place = f.x + (cr[u] >> 8);
+      staged[place] = (code << 12) | (uint32_t)i;
+      if (c.pos) c.pos[i] = (int32_t)(place + f.y);
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
   }
   __syncthreads();
   for (int j = tid; j < s; j += kChunkWaves * 64) {
     const uint32_t v = staged[j];
-    c.perm[(uint32_t)j + slot[v >> 12].shift] = c.value_base + (int32_t)(v & (kChunk - 1));
+    c.perm[(uint32_t)j + first[v >> 12].y] = c.value_base + (int32_t)(v & (kChunk - 1));
   }
 
   // the sorted block of the node's sampled keys that fall into this chunk
