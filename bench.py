@@ -30,8 +30,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc runs summarised in
 # profiles/bench_cfg4_n131k_causal_hbm_traffic.txt (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB).
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg4_n131k_causal", "base"): int((3196595.6 * 2.0 + 1064960.0) * 1024),
-    ("cfg4_n131k_causal", "node"): int((3981478.6 * 2.0 + 2802342.0) * 1024),
+    ("cfg4_n131k_causal", "base"): int((3188658.0 * 2.0 + 1064960.0) * 1024),
+    ("cfg4_n131k_causal", "node"): int((3981219.9 * 2.0 + 2802428.5) * 1024),
 }
 
 
