@@ -294,6 +294,8 @@ def workspace_views(workspace, shape: HaShape, params: HaParams):
             v[name] = view(getattr(lay, name), cov, torch.int32, (lay.levels, BH, lay.n_cov))
         if params.m and lay.total_nodes:
             v["samples"] = view(lay.samples, lay.total_nodes * params.m, torch.int32, (lay.total_nodes, params.m))
+            v["samp_blk"] = view(lay.samp_blk, BH * lay.total_nodes * params.m, torch.int32,
+                                 (BH, lay.total_nodes, params.m))
         if params.causal:
             pdt = torch.bfloat16 if shape.dtype == HA_BF16 else torch.float32
             v["part_o"] = view(lay.part_o, cov * d, pdt, (lay.levels, BH, lay.n_cov, d))

@@ -173,6 +173,9 @@ def _forward_and_compare(ha, torch, cfg, Q, K, V, R=None, samples=None, sample_f
                                                 with_absv=True)
         # stage 2: permutations of every node
         pq, pk, posk = (views[k].cpu().numpy() for k in ("perm_q", "perm_k", "pos_k"))
+        # (and the sorted block of every sampled key, which Algorithm 2's factor 1 - M_{i,l_j} is read from)
+        smp = views["samples"].cpu().numpy() if "samples" in views else None
+        sblk = views["samp_blk"].cpu().numpy() if "samp_blk" in views else None
         for bh in range(B * H):
             for level in range(lay.levels):
                 nodes = (1 << level) if cfg["causal"] else 1
@@ -185,6 +188,9 @@ def _forward_and_compare(ha, torch, cfg, Q, K, V, R=None, samples=None, sample_f
                     np.testing.assert_array_equal(pq[level, bh, node * s:(node + 1) * s], rq + q0)
                     np.testing.assert_array_equal(pk[level, bh, node * s:(node + 1) * s], rk + k0)
                     np.testing.assert_array_equal(posk[level, bh, node * s:(node + 1) * s], rposk)
+                    if sblk is not None and samples is None:
+                        heap = (1 << level) - 1 + node
+                        np.testing.assert_array_equal(sblk[bh, heap], rposk[smp[heap]] // cfg["b"])
     # stage 3: outputs
     got = to_host(out)
     err = assert_close(got, ref_out, dtype, "out", absv if p_rounding_term else None)
@@ -485,6 +491,22 @@ def test_exact_attention_wide_workgroups_sampled_rows(ha, torch):
             ref_o, ref_l = orc.exact_attention(Q[0, hd][rows], K[0, hd], V[0, hd])
             assert_close(to_host(out[0, hd])[rows], ref_o, "bf16", f"out d={d} head {hd}")
             assert_lse_close(to_host(lse[0, hd])[rows], ref_l, "bf16", f"lse d={d} head {hd}")
+
+
+@pytest.mark.parametrize("H,n,n_min,b,m,r,causal", [
+    (3, 9999, 4096, 3, 40, 7, 0),       # three chunks, the last ragged; odd head offsets (no 16-byte key loads)
+    (2, 12288, 4096, 256, 256, 8, 0),   # exactly three chunks, all 256 buckets in use
+    (2, 8200, 4096, 8, 16, 1, 0),       # two buckets; 8 keys in the last chunk
+    (2, 32768, 1024, 128, 64, 7, 1),    # causal: segments of 16384 ... 1024 keys = 4, 2, 1, 1, 1 chunks
+    (1, 20480, 4096, 256, 300, 5, 0),   # five chunks, more samples than a block holds
+])
+def test_forward_with_segments_longer_than_a_sort_chunk(ha, torch, H, n, n_min, b, m, r, causal):
+    """The forward sorts segments above 4096 keys in chunks, in two passes; codes, permutations,
+    positions, the sampled keys' blocks and the outputs are compared with the oracle as everywhere."""
+    print(f"chunked sort H={H} n={n} n_min={n_min} b={b} m={m} r={r} causal={causal}", flush=True)
+    cfg = dict(B=1, H=H, n=n, d=64, dtype="bf16", law="iid", b=b, m=m, r=r, causal=causal, n_min=n_min, seed=n + r)
+    Q, K, V = synth_inputs.make_qkv(cfg, seed=900 + n)
+    _forward_and_compare(ha, torch, cfg, Q, K, V, p_rounding_term=True)
 
 
 def _random_forward_cases(count, seed):
