@@ -240,7 +240,7 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="time the 12-head d=64 sweep shape at every length instead")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (heads shard with no communication; see DESIGN.md); "
+        sys.exit("bench.py: this build runs on ONE GPU (heads would shard over GPUs with no communication); "
                  "use --gpus 1")
 
     import torch
