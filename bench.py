@@ -81,6 +81,8 @@ def algorithmic_work(cfg):
         node_rows, w["base_flop"] = n, 0.0
     w["node_flop"] = BH * node_rows * 4.0 * d * (b + m)
     w["hash_bytes"] = 2 * BH * n * (d * esz + 1)
+    # the sort: every key of every node is read once (1 B) and written as perm (4 B), keys also as pos (4 B)
+    w["sort_bytes"] = BH * node_rows * (2 * (1 + 4) + 4) if node_rows else 0
     w["exact_flop"] = BH * 4.0 * n * n * d * (0.5 if cfg["causal"] else 1.0)
     return w
 
@@ -296,6 +298,9 @@ def main():
     node_tf = tflops(work["node_flop"], stage["node_attn"])
     base_tf = tflops(work["base_flop"], stage["causal_base"])
     hash_gbs = work["hash_bytes"] / (stage["lsh_hash"] * 1e-3) / 1e9 if stage["lsh_hash"] > 0 else 0.0
+    sort_gbs = work["sort_bytes"] / (stage["seg_sort"] * 1e-3) / 1e9 if stage["seg_sort"] > 0 else 0.0
+    hs_ms = stage["lsh_hash"] + stage["seg_sort"]
+    hash_sort_gbs = (work["hash_bytes"] + work["sort_bytes"]) / (hs_ms * 1e-3) / 1e9 if hs_ms > 0 else 0.0
     # the dominant kernel: the causal base case when there is one, else the node attention
     if stage["causal_base"] >= stage["node_attn"]:
         dom, dom_tf, dom_flop, dom_ms, key = ("attn_mfma_kernel<exact> (causal base case)", base_tf, work["base_flop"],
@@ -320,7 +325,10 @@ def main():
         "event_ms_median": round(float(np.median(totals)), 4), "event_ms_min": round(float(np.min(totals)), 4),
         "stage_rates": {"node_attn_TFLOPs": round(node_tf, 2), "node_attn_frac_mfma": round(node_tf / PEAK_BF16_TFLOPS, 4),
                         "causal_base_TFLOPs": round(base_tf, 2), "causal_base_frac_mfma": round(base_tf / PEAK_BF16_TFLOPS, 4),
-                        "lsh_hash_GBs": round(hash_gbs, 1), "lsh_hash_frac_hbm": round(hash_gbs / PEAK_HBM_GBS, 4)},
+                        "lsh_hash_GBs": round(hash_gbs, 1), "lsh_hash_frac_hbm": round(hash_gbs / PEAK_HBM_GBS, 4),
+                        "seg_sort_GBs": round(sort_gbs, 1), "seg_sort_frac_hbm": round(sort_gbs / PEAK_HBM_GBS, 4),
+                        "hash_plus_sort_GBs": round(hash_sort_gbs, 1),
+                        "hash_plus_sort_frac_hbm": round(hash_sort_gbs / PEAK_HBM_GBS, 4)},
         "tokens_per_s": round(B * n / (ms_per_step * 1e-3), 1),
     }
 
