@@ -23,7 +23,8 @@
  * Conventions for every entry point
  *   - Tensors are contiguous [B, H, n, d] in DEVICE memory, caller-owned, of the
  *     dtype in ha_shape (HA_BF16: 16-bit bfloat; HA_FP32: IEEE float).  `lse` is
- *     float [B, H, n], natural log of the (estimated) row sum.
+ *     float [B, H, n], natural log of the (estimated) row sum.  Tensors start at a
+ *     16-byte boundary, float and index arrays at a 4-byte one (HA_ERR_ALIGN).
  *   - The library allocates no device memory, never synchronises and enqueues
  *     only on `stream` (a hipStream_t passed as void*; NULL = the null stream).
  *     Scratch comes from the caller: `workspace` of at least
@@ -54,7 +55,8 @@ typedef enum {
   HA_ERR_DTYPE = -2,     /* dtype is neither HA_BF16 nor HA_FP32 */
   HA_ERR_SHAPE = -3,     /* shape or parameters outside what is supported (see each call) */
   HA_ERR_WORKSPACE = -4, /* workspace too small or not 256-byte aligned */
-  HA_ERR_LAUNCH = -5     /* the HIP runtime refused a launch (hipGetLastError) */
+  HA_ERR_LAUNCH = -5,    /* the HIP runtime refused a launch (hipGetLastError) */
+  HA_ERR_ALIGN = -6      /* a tensor does not start at a 16-byte boundary, or a float / index array at a 4-byte one */
 } ha_status;
 
 /* [B, H, n, d]; d must be 64 or 128; n <= 2^22; B*H <= 2^20. */

@@ -34,6 +34,13 @@ namespace ha {
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// Tensors and float arrays are accessed 16 bytes at a time; index arrays 4 bytes at a time.
+static bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+template <typename... P>
+static bool any_misaligned16(P... ptrs) { return (misaligned(ptrs, 16) || ...); }
+template <typename... P>
+static bool any_misaligned4(P... ptrs) { return (misaligned(ptrs, 4) || ...); }
+
 static int make_geometry(const ha_shape* sh, const ha_params* p, Geometry* g) {
   if (!sh || !p) return HA_ERR_NULL;
   if (sh->dtype != HA_BF16 && sh->dtype != HA_FP32) return HA_ERR_DTYPE;
@@ -145,6 +152,7 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
   if (g.BH == 0 || g.n == 0) return HA_OK;
   if (!Q || !K || !V || !out || !lse) return HA_ERR_NULL;
   if (out_f32 && g.dtype != HA_BF16) return HA_ERR_DTYPE;
+  if (any_misaligned16(Q, K, V, out, out_f32) || any_misaligned4(lse, R_dev, samples_dev)) return HA_ERR_ALIGN;
   ha_ws_layout lay;
   fill_layout(g, &lay);
   if (!ws) return HA_ERR_NULL;
@@ -308,6 +316,7 @@ static int backward_impl(const void* Q, const void* K, const void* V, const void
   if (g.levels > kBwdMaxLevels) return HA_ERR_SHAPE;
   if (g.BH == 0 || g.n == 0) return HA_OK;
   if (!Q || !K || !V || !out || !lse || !d_out || !dQ || !dK || !dV || !fws || !bws) return HA_ERR_NULL;
+  if (any_misaligned16(Q, K, V, out, out_f32, d_out, dQ, dK, dV) || any_misaligned4(lse)) return HA_ERR_ALIGN;
   ha_ws_layout lay;
   fill_layout(g, &lay);
   ha_bwd_ws_layout bl;
@@ -513,6 +522,7 @@ static int exact_forward_impl(const void* Q, const void* K, const void* V, void*
   if (sh->B == 0 || sh->H == 0 || sh->n == 0) return HA_OK;
   if (!Q || !K || !V || !out || !lse) return HA_ERR_NULL;
   if (out_f32 && sh->dtype != HA_BF16) return HA_ERR_DTYPE;
+  if (any_misaligned16(Q, K, V, out, out_f32) || any_misaligned4(lse)) return HA_ERR_ALIGN;
   AttnArgs a{};
   a.Q = Q;
   a.K = K;
@@ -567,6 +577,7 @@ int ha_lsh_hash(const void* X, uint8_t* codes, int64_t rows, int32_t d, int32_t 
   if (rows < 0 || (d != 64 && d != 128) || r < 1 || r > 8) return HA_ERR_SHAPE;
   if (rows == 0) return HA_OK;
   if (!X || !codes || !R_dev) return HA_ERR_NULL;
+  if (any_misaligned16(X) || any_misaligned4(R_dev)) return HA_ERR_ALIGN;
   return launch_lsh_hash(X, codes, rows, d, dtype, R_dev, r, (hipStream_t)stream);
 }
 
@@ -575,6 +586,7 @@ int ha_seg_sort(const uint8_t* codes, int32_t* perm, int32_t* pos, int32_t n_seg
   if (n_seg < 0 || seg_len < 0 || seg_len > (1 << 24)) return HA_ERR_SHAPE;
   if (n_seg == 0 || seg_len == 0) return HA_OK;
   if (!codes || !perm || !pos) return HA_ERR_NULL;
+  if (any_misaligned4(perm, pos)) return HA_ERR_ALIGN;
   return launch_seg_sort_flat(codes, perm, pos, n_seg, seg_len, (hipStream_t)stream);
 }
 
@@ -584,6 +596,7 @@ int ha_gather_rows(const void* src, const int32_t* idx, void* dst, int32_t group
   if (groups < 0 || n < 0 || (d != 64 && d != 128)) return HA_ERR_SHAPE;
   if (groups == 0 || n == 0) return HA_OK;
   if (!src || !idx || !dst) return HA_ERR_NULL;
+  if (any_misaligned16(src, dst) || any_misaligned4(idx)) return HA_ERR_ALIGN;
   return launch_gather_rows(src, idx, dst, groups, n, d, dtype, (hipStream_t)stream);
 }
 
@@ -594,6 +607,7 @@ int ha_block_attn(const void* Qs, const void* Ks, const void* Vs, float* o_b, fl
   if (rc != HA_OK) return rc;
   if (groups == 0 || n == 0) return HA_OK;
   if (!Qs || !Ks || !Vs || !o_b || !lse_b) return HA_ERR_NULL;
+  if (any_misaligned16(Qs, Ks, Vs, o_b) || any_misaligned4(lse_b)) return HA_ERR_ALIGN;
   AttnArgs a{};
   a.Q = Qs;
   a.K = Ks;
@@ -614,6 +628,7 @@ int ha_sampled_attn(const void* Qs, const void* K, const void* V, const int32_t*
   if (rc != HA_OK) return rc;
   if (groups == 0 || n == 0) return HA_OK;
   if (!Qs || !K || !V || !o_r || !lse_r || !pos_k || (m > 0 && !samples)) return HA_ERR_NULL;
+  if (any_misaligned16(Qs, K, V, o_r) || any_misaligned4(lse_r, pos_k, samples)) return HA_ERR_ALIGN;
   AttnArgs a{};
   a.Q = Qs;
   a.K = K;
@@ -635,6 +650,7 @@ int ha_merge_unpermute(const float* o_b, const float* lse_b, const float* o_r, c
   if (groups < 0 || n < 0 || (d != 64 && d != 128)) return HA_ERR_SHAPE;
   if (groups == 0 || n == 0) return HA_OK;
   if (!o_b || !lse_b || !o_r || !lse_r || !perm_q || !out || !lse) return HA_ERR_NULL;
+  if (any_misaligned16(o_b, o_r, out) || any_misaligned4(lse_b, lse_r, perm_q, lse)) return HA_ERR_ALIGN;
   return launch_merge_unpermute(o_b, lse_b, o_r, lse_r, perm_q, out, lse, groups, n, d, dtype,
                                 (hipStream_t)stream);
 }
@@ -714,6 +730,7 @@ int exact_attn_backward(const void* Q, const void* K, const void* V, const void*
   if (g.dtype != HA_BF16) return HA_ERR_DTYPE;
   if (g.BH == 0 || g.n == 0) return HA_OK;
   if (!Q || !K || !V || !out || !lse || !d_out || !dQ || !dK || !dV || !workspace) return HA_ERR_NULL;
+  if (any_misaligned16(Q, K, V, out, out_f32, d_out, dQ, dK, dV) || any_misaligned4(lse)) return HA_ERR_ALIGN;
   ha_bwd_ws_layout bl;
   fill_bwd_layout(g, &bl);
   if (workspace_bytes < bl.total_bytes || ((uintptr_t)workspace & 255) != 0) return HA_ERR_WORKSPACE;
@@ -777,6 +794,7 @@ int hyperattn_forward_alg2(const void* Q, const void* K, const void* V, void* ou
   if (rc != HA_OK) return rc;
   if (g.BH == 0 || g.n == 0) return HA_OK;
   if (!Q || !K || !V || !out || !lse || !workspace) return HA_ERR_NULL;
+  if (any_misaligned16(Q, K, V, out) || any_misaligned4(lse)) return HA_ERR_ALIGN;
   ha_ws_layout lay;
   fill_layout(g, &lay);
   ha_alg2_ws_layout al;
@@ -839,6 +857,7 @@ const char* ha_strerror(int status) {
     case HA_ERR_SHAPE: return "unsupported shape or parameters";
     case HA_ERR_WORKSPACE: return "workspace too small or misaligned";
     case HA_ERR_LAUNCH: return "HIP launch failed";
+    case HA_ERR_ALIGN: return "a tensor is not 16-byte aligned (or an index / float array not 4-byte aligned)";
     default: return "unknown status";
   }
 }

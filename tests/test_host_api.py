@@ -111,9 +111,25 @@ def test_null_pointers_and_strerror(ha):
     assert ha.lib().ha_lsh_hash(None, None, 10, 64, 0, None, 7, None) == -1
     assert ha.lib().ha_lsh_hash(None, None, 10, 65, 0, None, 7, None) == -3
     assert ha.lib().ha_seg_sort(None, None, None, 1, 2 ** 25, None) == -3
-    for code in (0, -1, -2, -3, -4, -5):
+    for code in (0, -1, -2, -3, -4, -5, -6):
         assert ha.strerror(code) and ha.strerror(code) != "unknown status"
     assert ha.strerror(-99) == "unknown status"
+
+
+def test_misaligned_arrays_are_rejected_on_the_host(ha):
+    """Tensors must start at a 16-byte boundary, float / index arrays at a 4-byte one; the check
+    runs on the host before anything is enqueued (the addresses here are never dereferenced)."""
+    sh = ha.make_shape(1, 1, 1024, 64, 0)
+    p = ha.make_params(64, 64, 7)
+    ok = 0x7F0000000000
+    fwd = ha.lib().hyperattn_forward
+    assert fwd(ok + 8, ok, ok, ok, ok, ctypes.byref(sh), ctypes.byref(p), ok, 1 << 30, None) == -6
+    assert fwd(ok, ok, ok + 2, ok, ok, ctypes.byref(sh), ctypes.byref(p), ok, 1 << 30, None) == -6
+    assert fwd(ok, ok, ok, ok, ok + 2, ctypes.byref(sh), ctypes.byref(p), ok, 1 << 30, None) == -6
+    assert ha.lib().exact_attn_forward(ok, ok + 4, ok, ok, ok, ctypes.byref(sh), 0, None) == -6
+    assert ha.lib().ha_lsh_hash(ok + 4, ok, 10, 64, 0, ok, 7, None) == -6
+    assert ha.lib().ha_seg_sort(ok, ok + 1, ok, 1, 16, None) == -6
+    assert "aligned" in ha.strerror(-6)
 
 
 def test_product_package_does_not_import_the_oracle():
