@@ -338,7 +338,7 @@ def main():
     # what this GPU sustains on code that does nothing else: MFMA chains in registers, streaming reads
     cal = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
     cal.zero_()
-    mfma_tf = ha.ha_measure_mfma_rate(cal)
+    mfma_tf = ha.ha_measure_mfma_rate(cal, iters=4000)   # about 5 ms: as long as the dominant kernel runs
     read_gbs, copy_gbs = ha.ha_measure_hbm_rate(cal)
     del cal
     result["attainable"] = {"mfma_bf16_TFLOPs": round(mfma_tf, 1), "hbm_read_GBs": round(read_gbs, 1),

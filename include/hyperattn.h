@@ -313,8 +313,10 @@ int hyperattn_forward_alg2(const void* Q, const void* K, const void* V, void* ou
  * `buf` is caller-owned device memory that they overwrite.
  *
  * ha_measure_mfma_rate: bf16 matrix-core rate of register-resident chains of the
- * 32x32x16 MFMA the attention kernels use, `iters` loop trips per wave
- * (1..2^20; 2000 takes a few ms), in TFLOP/s.  buf >= 512 KiB.
+ * 32x32x16 MFMA the attention kernels use, over operands that change from one
+ * instruction to the next, `iters` loop trips per wave (1..2^20; 1000 take about
+ * 1.2 ms, and the rate falls with the duration as the chip lowers its clock), in
+ * TFLOP/s.  buf >= 512 KiB.
  * ha_measure_hbm_rate: GB/s of a streaming read of the first half of buf, and of
  * a copy of the first half onto the second (read + written bytes counted).
  * buf 16-byte aligned, bytes >= 1 MiB; use a buffer well beyond the caches.

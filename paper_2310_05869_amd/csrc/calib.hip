@@ -2,8 +2,11 @@
 // GPU sustains on code that does nothing else, so that a kernel's achieved rate
 // can be set against an attainable figure as well as the published peak.
 //
-//   MFMA   every wave runs independent chains of v_mfma_f32_32x32x16_bf16 with
-//          operands in registers (the instruction the attention kernels use).
+//   MFMA   every wave runs independent chains of v_mfma_f32_32x32x16_bf16 (the
+//          instruction the attention kernels use) over eight register-resident
+//          operand pairs of pseudo-random values; the rate depends on how long the
+//          probe runs (the chip lowers its clock within milliseconds under this
+//          load), so `iters` should give a duration like the kernel's it is set against.
 //   HBM    a grid-stride read of a buffer (16 bytes per lane and step), and a
 //          copy of its first half onto its second.
 // Both time themselves with events on the given stream and wait for it.
@@ -18,23 +21,46 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kChains = 4;       // independent accumulators per wave
 constexpr int kPerIter = 8;      // MFMAs per chain and loop trip
 
+constexpr int kOperands = 8;     // operand pairs a wave rotates through
+
+// bf16 pair with pseudo-random sign, mantissa and an exponent in [2^-3, 2): operands that differ
+// from one instruction to the next, as a kernel's do (constant operands toggle no wires and
+// flatter the rate)
+__device__ inline uint32_t rate_operand_bits(uint32_t seed) {
+  uint32_t v = 0;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    seed = seed * 1664525u + 1013904223u;
+    const uint32_t b = ((seed >> 31) << 15) | ((0x7Cu + ((seed >> 20) & 3u)) << 7) | ((seed >> 8) & 0x7Fu);
+    v |= b << (16 * half);
+  }
+  return v;
+}
+
 __global__ __launch_bounds__(256) void mfma_rate_kernel(float* out, int iters) {
   f32x16 acc[kChains];
 #pragma unroll
   for (int c = 0; c < kChains; ++c)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
-  bf16x8 x, y;
+  bf16x8 x[kOperands], y[kOperands];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    x[i] = (__bf16)((threadIdx.x & 15) * 0.03125f + i);
-    y[i] = (__bf16)(i * 0.5f - 1.f);
+  for (int u = 0; u < kOperands; ++u) {
+    u32x4 xb, yb;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      xb[i] = rate_operand_bits((threadIdx.x * 64u + u * 8u + i) * 2654435761u);
+      yb[i] = rate_operand_bits((threadIdx.x * 64u + u * 8u + i + 4u) * 2246822519u);
+    }
+    x[u] = __builtin_bit_cast(bf16x8, xb);
+    y[u] = __builtin_bit_cast(bf16x8, yb);
   }
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int u = 0; u < kPerIter; ++u)
 #pragma unroll
-      for (int c = 0; c < kChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc[c], 0, 0, 0);
+      for (int c = 0; c < kChains; ++c)
+        acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[(u + c) % kOperands], y[(u + 2 * c) % kOperands], acc[c], 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
