@@ -31,7 +31,8 @@
 // and then written out in that order, so a wave's 64 stores fall into a few
 // runs of consecutive entries.  B also records the sorted block of every sampled key
 // (the factor 1 - M_{i,l_j} of Algorithm 2 needs nothing else).
-// Traffic is 2 bytes read and 8 (Q) or 12 (K) bytes written per key.
+// Traffic per key: 1 byte read in each pass, 4 bytes written (the permutation) for queries and
+// 8 (permutation and position) for keys.
 #include "ha_common.h"
 
 namespace ha {
