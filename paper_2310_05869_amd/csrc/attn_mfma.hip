@@ -264,6 +264,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
     }
     mask_tile(c, 0, bias);
     t_max = tile_max(c, bias);
+    m_run = t_max;  // the first tile sets the reference: the accumulators are still zero, nothing to rescale
   }
 
   auto body = [&](int kt, f32x16 (&c)[2], float& bias, f32x16 (&cn)[2], float& bias_n, auto has_next) {
