@@ -47,19 +47,49 @@ __global__ void alg2_prep_kernel(Alg2Args a) {
   }
 }
 
-template <typename T>
-__global__ void vnorm_weight_kernel(Alg2Args a) {
+// Squared row norms of V in fp64, summed over ascending columns (one thread per row, so the order
+// is fixed); 64 rows per workgroup come in through LDS so that the global loads are coalesced.
+constexpr int kVwRows = 64;
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void vnorm_weight_kernel(Alg2Args a) {
+  constexpr int kRowBytes = D * (int)sizeof(T);
+  constexpr int kStride = kRowBytes + 4;  // odd number of words: the 64 row readers hit 64 banks
+  __shared__ __attribute__((aligned(16))) unsigned char tile[kVwRows * kStride];
   const Geometry& g = a.g;
-  const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (row >= (int64_t)g.BH * g.n) return;
-  const T* v = reinterpret_cast<const T*>(a.V) + row * g.d;
+  const int64_t rows = (int64_t)g.BH * g.n;
+  const int64_t row0 = (int64_t)blockIdx.x * kVwRows;
+  const int nrows = (int)min((int64_t)kVwRows, rows - row0);
+  const unsigned char* src = reinterpret_cast<const unsigned char*>(a.V) + row0 * kRowBytes;
+  for (int e = threadIdx.x; e < nrows * (kRowBytes / 4); e += 256) {
+    const int r = e / (kRowBytes / 4), w = e % (kRowBytes / 4);
+    *reinterpret_cast<uint32_t*>(tile + r * kStride + 4 * w) = *reinterpret_cast<const uint32_t*>(src + (int64_t)e * 4);
+  }
+  __syncthreads();
+  if (threadIdx.x >= 64) return;  // the first wave sums the rows (whole waves leave; no partial wave)
+  const bool active = (int)threadIdx.x < nrows;
+  const T* v = reinterpret_cast<const T*>(tile + (active ? threadIdx.x : 0) * kStride);
   double w = 0.0;
-  for (int c = 0; c < g.d; ++c) {
+  for (int c = 0; c < D; ++c) {
     const double x = (double)elem<T>(v + c);
     w = w + x * x;  // one rounding per add (the product of two fp32-representable values is exact in fp64)
   }
-  a.vw[row] = w;
-  atomicMax(&a.vmax[row / g.n], (unsigned long long)__double_as_longlong(w));  // non-negative doubles order like their bits
+  const int64_t row = row0 + (active ? threadIdx.x : 0);
+  if (active) a.vw[row] = w;
+  // largest weight of the head (non-negative doubles order like their bits): one atomic per
+  // workgroup when its rows share a head, else one per row
+  unsigned long long bits = active ? (unsigned long long)__double_as_longlong(w) : 0ull;
+  const int64_t head = row / g.n;
+  if (row0 / g.n == (row0 + nrows - 1) / g.n) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      const unsigned long long other = __shfl_xor(bits, o);
+      bits = other > bits ? other : bits;
+    }
+    if (threadIdx.x == 0) atomicMax(&a.vmax[head], bits);
+  } else if (active) {
+    atomicMax(&a.vmax[head], bits);
+  }
 }
 
 constexpr int kScanThreads = 1024;
@@ -114,41 +144,106 @@ __global__ void vnorm_sample_kernel(Alg2Args a) {
   a.vlogw[t] = (float)(log((double)total) - log((double)g.m) - log((double)a.vq[(int64_t)bh * g.n + lo]));
 }
 
-// log of the unmasked row sum of row T_j: one workgroup per (head, j)
+// log of the unmasked row sum of the rows T_j: one workgroup per head and kTauRows of them.
+// Key rows pass through LDS in tiles (coalesced loads, every key element serves several rows);
+// a thread owns one key of the tile for some of the rows and keeps their running log sums.
+constexpr int kTauRows = 8;
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void alg2_tau_kernel(Alg2Args a) {
-  __shared__ float qs[D];
-  __shared__ float red_m[256], red_s[256];
+  constexpr int kKeys = sizeof(T) == 2 ? 128 : 64;   // keys per tile
+  constexpr int kGroups = 256 / kKeys;               // thread groups, each with its own rows
+  constexpr int kRpt = kTauRows / kGroups;           // rows per thread
+  constexpr int kRowBytes = D * (int)sizeof(T);
+  constexpr int kStride = kRowBytes + 4;             // odd number of words: no bank conflicts between the keys
+  __shared__ __attribute__((aligned(16))) unsigned char tile[kKeys * kStride];
+  __shared__ __attribute__((aligned(16))) float qs[kTauRows][D];
+  __shared__ float red_m[kTauRows][kKeys], red_s[kTauRows][kKeys];
+  __shared__ int blk_of[kTauRows];
   const Geometry& g = a.g;
-  const int bh = blockIdx.x / g.m, j = blockIdx.x % g.m;
-  const int row = a.tau_rows[j];
-  const T* Qh = reinterpret_cast<const T*>(a.Q) + (int64_t)bh * g.n * D;
-  const T* Kh = reinterpret_cast<const T*>(a.K) + (int64_t)bh * g.n * D;
-  for (int c = threadIdx.x; c < D; c += 256) qs[c] = elem<T>(Qh + (int64_t)row * D + c);
-  __syncthreads();
-  const int blk = a.pos_q[(int64_t)bh * g.n + row] / g.b;
-  float mx = -INFINITY, sum = 0.f;
-  for (int l = threadIdx.x; l < g.n; l += 256) {
-    if (a.pos_k[(int64_t)bh * g.n + l] / g.b == blk) continue;  // 1 - M
-    float s = 0.f;
-    for (int c = 0; c < D; ++c) s = __builtin_fmaf(qs[c], elem<T>(Kh + (int64_t)l * D + c), s);
-    if (s > mx) {
-      sum = sum * expf(mx - s) + 1.f;
-      mx = s;
-    } else {
-      sum += expf(s - mx);
+  const int groups_per_head = (g.m + kTauRows - 1) / kTauRows;
+  const int bh = blockIdx.x / groups_per_head, j0 = (blockIdx.x % groups_per_head) * kTauRows;
+  const int nr = min(kTauRows, g.m - j0);
+  const int64_t hb = (int64_t)bh * g.n;
+  const T* Qh = reinterpret_cast<const T*>(a.Q) + hb * D;
+  const unsigned char* Kh = reinterpret_cast<const unsigned char*>(a.K) + hb * kRowBytes;
+  const int tid = threadIdx.x;
+  for (int e = tid; e < kTauRows * D; e += 256) {
+    const int r = e / D, c = e % D;
+    qs[r][c] = r < nr ? elem<T>(Qh + (int64_t)a.tau_rows[j0 + r] * D + c) : 0.f;
+  }
+  if (tid < kTauRows) blk_of[tid] = tid < nr ? a.pos_q[hb + a.tau_rows[j0 + tid]] / g.b : -1;
+  const int k = tid % kKeys, grp = tid / kKeys;
+  float mx[kRpt], sum[kRpt];
+#pragma unroll
+  for (int r = 0; r < kRpt; ++r) {
+    mx[r] = -INFINITY;
+    sum[r] = 0.f;
+  }
+  for (int l0 = 0; l0 < g.n; l0 += kKeys) {
+    const int cnt = min(kKeys, g.n - l0);
+    __syncthreads();
+    for (int e = tid; e < cnt * (kRowBytes / 4); e += 256) {
+      const int r = e / (kRowBytes / 4), w = e % (kRowBytes / 4);
+      *reinterpret_cast<uint32_t*>(tile + r * kStride + 4 * w) =
+          *reinterpret_cast<const uint32_t*>(Kh + (int64_t)l0 * kRowBytes + (int64_t)e * 4);
+    }
+    __syncthreads();
+    if (k >= cnt) continue;
+    const int kblk = a.pos_k[hb + l0 + k] / g.b;
+    const T* kr = reinterpret_cast<const T*>(tile + k * kStride);
+    float s[kRpt];
+#pragma unroll
+    for (int r = 0; r < kRpt; ++r) s[r] = 0.f;
+    // ascending columns, one fused multiply-add each (the scores of an fp32 dot product); four columns
+    // per step so that a row of q is read 16 bytes at a time
+#pragma unroll 4
+    for (int c = 0; c < D; c += 4) {
+      float x[4];
+      if (sizeof(T) == 2) {
+        const uint32_t lo = *reinterpret_cast<const uint32_t*>(kr + c), hi = *reinterpret_cast<const uint32_t*>(kr + c + 2);
+        x[0] = __uint_as_float(lo << 16);
+        x[1] = __uint_as_float(lo & 0xFFFF0000u);
+        x[2] = __uint_as_float(hi << 16);
+        x[3] = __uint_as_float(hi & 0xFFFF0000u);
+      } else {
+#pragma unroll
+        for (int z = 0; z < 4; ++z) x[z] = elem<T>(kr + c + z);
+      }
+#pragma unroll
+      for (int r = 0; r < kRpt; ++r) {
+        const float4 qv = *reinterpret_cast<const float4*>(&qs[grp * kRpt + r][c]);
+        s[r] = __builtin_fmaf(qv.x, x[0], s[r]);
+        s[r] = __builtin_fmaf(qv.y, x[1], s[r]);
+        s[r] = __builtin_fmaf(qv.z, x[2], s[r]);
+        s[r] = __builtin_fmaf(qv.w, x[3], s[r]);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < kRpt; ++r) {
+      if (kblk == blk_of[grp * kRpt + r]) continue;  // 1 - M (rows beyond nr have block -1 and are dropped below)
+      if (s[r] > mx[r]) {
+        sum[r] = sum[r] * expf(mx[r] - s[r]) + 1.f;
+        mx[r] = s[r];
+      } else {
+        sum[r] += expf(s[r] - mx[r]);
+      }
     }
   }
-  red_m[threadIdx.x] = mx;
-  red_s[threadIdx.x] = sum;
   __syncthreads();
-  if (threadIdx.x == 0) {
+#pragma unroll
+  for (int r = 0; r < kRpt; ++r) {
+    red_m[grp * kRpt + r][k] = mx[r];
+    red_s[grp * kRpt + r][k] = sum[r];
+  }
+  __syncthreads();
+  if (tid < nr) {
     float M = -INFINITY;
-    for (int t = 0; t < 256; ++t) M = fmaxf(M, red_m[t]);
+    for (int t = 0; t < kKeys; ++t) M = fmaxf(M, red_m[tid][t]);
     float S = 0.f;
-    for (int t = 0; t < 256; ++t)
-      if (red_m[t] > -INFINITY) S += red_s[t] * expf(red_m[t] - M);
-    a.log_unm_t[(int64_t)bh * g.m + j] = (M == -INFINITY) ? -INFINITY : M + logf(S);
+    for (int t = 0; t < kKeys; ++t)
+      if (red_m[tid][t] > -INFINITY) S += red_s[tid][t] * expf(red_m[tid][t] - M);
+    a.log_unm_t[(int64_t)bh * g.m + j0 + tid] = (M == -INFINITY) ? -INFINITY : M + logf(S);
   }
 }
 
@@ -324,15 +419,16 @@ static int launch_alg2_t(const Alg2Args& a, hipStream_t st) {
   if (prep < g.BH) prep = g.BH;
   hipLaunchKernelGGL(alg2_prep_kernel, dim3((unsigned)((prep + 255) / 256)), dim3(256), 0, st, a);
   if (a.vnorm && g.m > 0) {
-    hipLaunchKernelGGL((vnorm_weight_kernel<T>), dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, a);
+    const unsigned vw_grid = (unsigned)((rows + kVwRows - 1) / kVwRows);
+    if (g.d == 128) hipLaunchKernelGGL((vnorm_weight_kernel<T, 128>), dim3(vw_grid), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((vnorm_weight_kernel<T, 64>), dim3(vw_grid), dim3(256), 0, st, a);
     hipLaunchKernelGGL(vnorm_scan_kernel, dim3((unsigned)g.BH), dim3(kScanThreads), 0, st, a);
     hipLaunchKernelGGL(vnorm_sample_kernel, dim3((unsigned)(((int64_t)g.BH * g.m + 255) / 256)), dim3(256), 0, st, a);
   }
   if (g.m > 0) {
-    if (g.d == 128)
-      hipLaunchKernelGGL((alg2_tau_kernel<T, 128>), dim3((unsigned)(g.BH * g.m)), dim3(256), 0, st, a);
-    else
-      hipLaunchKernelGGL((alg2_tau_kernel<T, 64>), dim3((unsigned)(g.BH * g.m)), dim3(256), 0, st, a);
+    const unsigned tau_grid = (unsigned)((int64_t)g.BH * ((g.m + kTauRows - 1) / kTauRows));
+    if (g.d == 128) hipLaunchKernelGGL((alg2_tau_kernel<T, 128>), dim3(tau_grid), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((alg2_tau_kernel<T, 64>), dim3(tau_grid), dim3(256), 0, st, a);
   }
   hipLaunchKernelGGL(alg2_tau_max_kernel, dim3((unsigned)((g.BH + 63) / 64)), dim3(64), 0, st, a);
   const int tpb = (g.b + kA2Rows - 1) / kA2Rows;
