@@ -299,6 +299,7 @@ typedef struct {
   size_t vnorm_prefix;       /* uint64 [B*H][n]: inclusive prefix sums of q */
   size_t vnorm_samples;      /* int32 [B*H][m]: l'_r */
   size_t vnorm_logw;         /* float [B*H][m]: log(1 / (m p_{l'_r})) */
+  size_t log_unmasked_parts; /* float [8][B*H][m]: scratch, the unmasked row sums of T over eight ranges of keys */
   size_t total_bytes;
 } ha_alg2_ws_layout;
 

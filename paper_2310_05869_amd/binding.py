@@ -47,6 +47,7 @@ class HaAlg2Options(ctypes.Structure):
 class HaAlg2WsLayout(ctypes.Structure):
     _fields_ = [(k, c_size_t) for k in ("forward_bytes", "pos_q", "tau_rows", "log_unmasked_t", "log_tau", "vnorm_w",
                                         "vnorm_max", "vnorm_q", "vnorm_prefix", "vnorm_samples", "vnorm_logw",
+                                        "log_unmasked_parts",
                                         "total_bytes")]
 
 

@@ -5,6 +5,8 @@
 
 namespace ha {
 
+constexpr int kAlg2TauSplits = 8;  // key ranges the tau rows' sums are split over, for enough workgroups
+
 struct Alg2Args {
   const void* Q;
   const void* K;
@@ -20,6 +22,8 @@ struct Alg2Args {
   int32_t* pos_q;          // [BH][n]
   int32_t* tau_rows;       // [m]
   float* log_unm_t;        // [BH][m]
+  float* log_unm_parts;    // [kAlg2TauSplits][BH][m]: the same over ranges of keys (matrix-core form)
+  int32_t tau_splits;      // 0: log_unm_t is final; else the number of key ranges to combine
   float* log_tau;          // [BH]
   double* vw;              // [BH][n]
   unsigned long long* vmax;     // [BH] bit pattern of the largest vw
@@ -33,5 +37,10 @@ struct Alg2Args {
 };
 
 int launch_alg2(const Alg2Args& a, hipStream_t st);
+
+// bf16 matrix-core forms of the two heavy steps (alg2_mfma.hip); the fp32 FMA kernels take what they do not
+bool alg2_mfma_supported(const Alg2Args& a);
+int launch_alg2_tau_mfma(const Alg2Args& a, hipStream_t st);
+int launch_alg2_main_mfma(const Alg2Args& a, hipStream_t st);
 
 }  // namespace ha

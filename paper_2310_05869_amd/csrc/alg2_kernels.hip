@@ -7,8 +7,10 @@
 //   out_i    = (1 / d~_i) sum_r exp<q_i,k_{l'_r}> v_{l'_r} / (m p_{l'_r}),  l'_r ~ p_l ~ |V_l|^2   (Lemma 2)
 //         or = (1 / d~_i) (masked part + (n/m) sum_j (1 - M) exp<q_i,k_{l_j}> v_{l_j})                (Section 4)
 // The constants the paper leaves open (the Theta in C_i, kappa) are the caller's.
-// Unmasked problems only.  These are options, not the hot path: plain fp32 FMA
-// kernels, one thread per query row, K / V rows staged through LDS as fp32.
+// Unmasked problems only.  The kernels here are plain fp32 FMA code (one thread per query row,
+// K / V rows staged through LDS): they serve fp32 tensors and whatever the bf16 matrix-core
+// forms of the two heavy steps (alg2_mfma.hip) do not take; the draws, weights and prefix
+// sums are computed here for both.
 //
 // The draws by squared row norm are integer decisions so that they can be
 // reproduced exactly elsewhere: |V_l|^2 is summed in fp64 over ascending
@@ -247,19 +249,37 @@ __global__ __launch_bounds__(256) void alg2_tau_kernel(Alg2Args a) {
   }
 }
 
-__global__ void alg2_tau_max_kernel(Alg2Args a) {
-  const Geometry& g = a.g;
-  const int bh = blockIdx.x * blockDim.x + threadIdx.x;
-  if (bh >= g.BH) return;
-  float mx = -INFINITY;
-  for (int j = 0; j < g.m; ++j) mx = fmaxf(mx, a.log_unm_t[(int64_t)bh * g.m + j]);
-  a.log_tau[bh] = mx;
-}
-
 __device__ inline float logaddexpf(float x, float y) {
   const float hi = fmaxf(x, y), lo = fminf(x, y);
   if (hi == -INFINITY) return -INFINITY;
   return hi + log1pf(expf(lo - hi));
+}
+
+// log tau = the largest log unmasked row sum over the rows of T, one workgroup per head; where the
+// sums came in over ranges of keys they are added up first (and kept in log_unm_t).
+__global__ __launch_bounds__(256) void alg2_tau_max_kernel(Alg2Args a) {
+  __shared__ float red[256];
+  const Geometry& g = a.g;
+  const int bh = blockIdx.x;
+  float mx = -INFINITY;
+  for (int j = threadIdx.x; j < g.m; j += 256) {
+    float v;
+    if (a.tau_splits > 0) {
+      v = -INFINITY;
+      for (int sp = 0; sp < a.tau_splits; ++sp) v = logaddexpf(v, a.log_unm_parts[((int64_t)sp * g.BH + bh) * g.m + j]);
+      a.log_unm_t[(int64_t)bh * g.m + j] = v;
+    } else {
+      v = a.log_unm_t[(int64_t)bh * g.m + j];
+    }
+    mx = fmaxf(mx, v);
+  }
+  red[threadIdx.x] = mx;
+  __syncthreads();
+  for (int s = 128; s >= 1; s >>= 1) {
+    if ((int)threadIdx.x < s) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + s]);
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) a.log_tau[bh] = red[0];
 }
 
 constexpr int kA2Rows = 64;  // query rows (threads) per workgroup
@@ -412,8 +432,11 @@ __global__ __launch_bounds__(kA2Rows) void alg2_main_kernel(Alg2Args a) {
 }
 
 template <typename T>
-static int launch_alg2_t(const Alg2Args& a, hipStream_t st) {
-  const Geometry& g = a.g;
+static int launch_alg2_t(const Alg2Args& a_in, hipStream_t st) {
+  const Geometry& g = a_in.g;
+  Alg2Args a = a_in;
+  const bool mfma = alg2_mfma_supported(a);
+  a.tau_splits = mfma ? kAlg2TauSplits : 0;
   const int64_t rows = (int64_t)g.BH * g.n;
   int64_t prep = rows > g.m ? rows : g.m;
   if (prep < g.BH) prep = g.BH;
@@ -426,11 +449,17 @@ static int launch_alg2_t(const Alg2Args& a, hipStream_t st) {
     hipLaunchKernelGGL(vnorm_sample_kernel, dim3((unsigned)(((int64_t)g.BH * g.m + 255) / 256)), dim3(256), 0, st, a);
   }
   if (g.m > 0) {
-    const unsigned tau_grid = (unsigned)((int64_t)g.BH * ((g.m + kTauRows - 1) / kTauRows));
-    if (g.d == 128) hipLaunchKernelGGL((alg2_tau_kernel<T, 128>), dim3(tau_grid), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((alg2_tau_kernel<T, 64>), dim3(tau_grid), dim3(256), 0, st, a);
+    if (mfma) {
+      const int rc = launch_alg2_tau_mfma(a, st);
+      if (rc != HA_OK) return rc;
+    } else {
+      const unsigned tau_grid = (unsigned)((int64_t)g.BH * ((g.m + kTauRows - 1) / kTauRows));
+      if (g.d == 128) hipLaunchKernelGGL((alg2_tau_kernel<T, 128>), dim3(tau_grid), dim3(256), 0, st, a);
+      else hipLaunchKernelGGL((alg2_tau_kernel<T, 64>), dim3(tau_grid), dim3(256), 0, st, a);
+    }
   }
-  hipLaunchKernelGGL(alg2_tau_max_kernel, dim3((unsigned)((g.BH + 63) / 64)), dim3(64), 0, st, a);
+  hipLaunchKernelGGL(alg2_tau_max_kernel, dim3((unsigned)g.BH), dim3(256), 0, st, a);
+  if (mfma) return launch_alg2_main_mfma(a, st);
   const int tpb = (g.b + kA2Rows - 1) / kA2Rows;
   const unsigned grid = (unsigned)((int64_t)g.BH * (g.n / g.b) * tpb);
   if (g.d == 128)

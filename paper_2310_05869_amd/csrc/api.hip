@@ -447,6 +447,7 @@ static void fill_alg2_layout(const Geometry& g, const ha_ws_layout& fwd, ha_alg2
   l->vnorm_prefix = take(rows * 8);
   l->vnorm_samples = take((size_t)g.BH * g.m * 4);
   l->vnorm_logw = take((size_t)g.BH * g.m * 4);
+  l->log_unmasked_parts = take((size_t)kAlg2TauSplits * g.BH * g.m * 4);
   l->total_bytes = off;
 }
 
@@ -842,6 +843,7 @@ int hyperattn_forward_alg2(const void* Q, const void* K, const void* V, void* ou
   a.vprefix = (unsigned long long*)(base + al.vnorm_prefix);
   a.vsamp = (int32_t*)(base + al.vnorm_samples);
   a.vlogw = (float*)(base + al.vnorm_logw);
+  a.log_unm_parts = (float*)(base + al.log_unmasked_parts);
   a.seed = params->seed;
   a.cap_scale = opt->cap_scale;
   a.kappa = opt->kappa;
