@@ -267,7 +267,8 @@ size_t exact_attn_backward_workspace_bytes(const ha_shape* shape);
 /* ------------------------------------------------------------------------
  * Algorithm 2 as printed and Lemma 2 / Algorithm 3, as options (the Section 4
  * form above leaves them out).  Unmasked problems only (params->causal must be
- * 0); both dtypes; plain fp32 kernels, not tuned.
+ * 0); both dtypes (bf16 tensors on the matrix cores, weights rounded to bf16
+ * as operands like in the forward; fp32 tensors in plain fp32 arithmetic).
  *   tau   = max over m rows drawn uniformly (with replacement) of the unmasked row sum
  *   C_i   = cap_scale * m / (n ln n) * (masked row sum_i + tau / kappa)     cap_scale <= 0: no cap
  *   d_i   = (n/m) sum_j (1 - M_{i,l_j}) min(exp<q_i,k_{l_j}>, C_i)
