@@ -134,6 +134,36 @@ def sweep(args, torch, ha):
         "sweep": points}), flush=True)
 
 
+def alg2_bench(args, torch, ha):
+    """Algorithm 2 as printed (caps, tau) and Lemma 2's value sampling, the options beside the
+    Section 4 form, at the unmasked 32-head workload: time of each next to the main path's."""
+    name = "cfg2_n32k"
+    cfg = dict(synth_inputs.CONFIGS[name])
+    (Q, K, V), _ = device_inputs(cfg, torch)
+    B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
+    b, m, r = cfg["b"], cfg["m"], cfg["r"]
+    out, lse = torch.empty_like(Q), torch.empty((B, H, n), dtype=torch.float32, device="cuda")
+    shape = ha.make_shape(B, H, n, d, ha.HA_BF16)
+    ws = ha.alloc_workspace(shape, ha.make_params(b, m, r, False, cfg["n_min"], cfg["seed"]))
+    main_ms = time_call(torch, lambda: ha.hyperattn_forward(Q, K, V, b, m, r, seed=cfg["seed"], workspace=ws, out=out,
+                                                            lse=lse), args.warmup, args.steps)
+    res = {}
+    ws2 = None
+    for key, vn in (("caps_ms", False), ("caps_and_value_sampling_ms", True)):
+        kw = dict(seed=cfg["seed"], cap_scale=8.0, kappa=1.2, vnorm_sampling=vn, out=out, lse=lse)
+        _, _, ws2 = ha.hyperattn_forward_alg2(Q, K, V, b, m, r, workspace=ws2, **kw)
+        res[key] = round(time_call(torch, lambda: ha.hyperattn_forward_alg2(Q, K, V, b, m, r, workspace=ws2, **kw),
+                                   args.warmup, args.steps), 4)
+        log(f"[bench] {key}: {res[key]:.3f} ms (Section 4 form: {main_ms:.3f} ms)")
+    print(json.dumps({
+        "metric": "HyperAttention fwd ms", "value": res["caps_ms"], "unit": "ms", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": res["caps_ms"], "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": name, "B": B, "H": H, "n": n, "d": d, "b": b, "m": m, "r": r, "causal": False,
+                   "estimator": "Algorithm 2 as printed: cap_scale 8, kappa 1.2"},
+        "section4_form_ms": round(main_ms, 4), **res}), flush=True)
+
+
 def backward_bench(args, torch, ha):
     """Forward + backward of the chosen workload (Section 4.2 quotes its speed-ups on that sum),
     with exact attention forward + backward beside it.  One JSON line."""
@@ -241,6 +271,7 @@ def main():
     ap.add_argument("--no-exact", action="store_true")
     ap.add_argument("--backward", action="store_true", help="time forward + backward instead of the forward alone")
     ap.add_argument("--sweep", action="store_true", help="time the 12-head d=64 sweep shape at every length instead")
+    ap.add_argument("--alg2", action="store_true", help="time Algorithm 2 as printed / Lemma 2's value sampling instead")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (heads would shard over GPUs with no communication); "
@@ -254,6 +285,8 @@ def main():
 
     if args.sweep:
         return sweep(args, torch, ha)
+    if args.alg2:
+        return alg2_bench(args, torch, ha)
     if args.backward:
         return backward_bench(args, torch, ha)
 
