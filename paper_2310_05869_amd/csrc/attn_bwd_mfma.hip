@@ -66,8 +66,9 @@ __host__ __device__ inline size_t bwd_lds_bytes(const Geometry& g, int mode) {
 }
 
 // WHAT: which product the pass accumulates.
-enum BwdWhat : int { kAccDs = 0,   // acc += Y^T dS^T : dQ (dQ passes) or dK (dK/dV passes)
-                     kAccP = 1 };  // acc += Bt^T P^T : dV (dK/dV passes only)
+enum BwdWhat : int { kAccDs = 0,    // acc += Y^T dS^T : dQ (dQ passes) or dK (dK/dV passes)
+                     kAccP = 1,     // acc += Bt^T P^T : dV (dK/dV passes only)
+                     kAccBoth = 2 };  // dK, then dV, in one launch: the workgroup keeps its R rows and walks its T rows twice
 
 template <int D, int MODE, int WHAT>
 __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
@@ -76,8 +77,8 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
   constexpr bool kDq = (MODE == kBwdDqNode || MODE == kBwdDqExact);
   constexpr bool kExact = (MODE == kBwdDqExact || MODE == kBwdDkvExact);
   constexpr bool kSorted = (MODE == kBwdDkvBlock || MODE == kBwdDkvSamp);  // T rows = a run of sorted query positions
-  constexpr bool kWantDs = (WHAT == kAccDs);
-  static_assert(kWantDs || !kDq, "the dQ passes accumulate dS only");
+  constexpr bool kLoadA = (WHAT != kAccP);  // the operand of dP is needed whenever dS is formed
+  static_assert(WHAT == kAccDs || !kDq, "the dQ passes accumulate dS only");
   constexpr int KS = D / 16;
   constexpr int DT = D / 32;
   constexpr int CPR = D / 8;                 // 16-byte chunks per row
@@ -191,14 +192,14 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
     r_row = w.q0 + r_use;
     out_row = (int64_t)w.bh * g.n + r_row;
   }
-  bf16x8 xreg[KS], areg[kWantDs ? KS : 1];
+  bf16x8 xreg[KS], areg[kLoadA ? KS : 1];
   {
     const u32x4* xp = reinterpret_cast<const u32x4*>(Xh + (int64_t)r_row * D + 8 * h);
     const u32x4* ap = reinterpret_cast<const u32x4*>(Ah + (int64_t)r_row * D + 8 * h);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       xreg[ks] = __builtin_bit_cast(bf16x8, xp[2 * ks]);
-      if constexpr (kWantDs) areg[ks] = __builtin_bit_cast(bf16x8, ap[2 * ks]);
+      if constexpr (kLoadA) areg[ks] = __builtin_bit_cast(bf16x8, ap[2 * ks]);
     }
   }
   float nl2_r = 0.f, del_r = 0.f;  // dQ passes: -L log2(e) and delta of the R row
@@ -256,7 +257,7 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
         soff = 0;
       }
       yreg[i] = __builtin_amdgcn_raw_buffer_load_b128(yrsrc, voff, soff, 0);
-      if (kWantDs || !kDq) breg[i] = __builtin_amdgcn_raw_buffer_load_b128(brsrc, voff, soff, 0);
+      breg[i] = __builtin_amdgcn_raw_buffer_load_b128(brsrc, voff, soff, 0);
     }
     if (!kDq && tid < kTT) {
       int row = kSorted ? six : min(w.k0 + kt * kTT + tid, g.n - 1);
@@ -284,233 +285,246 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
   };
   const int vtr_off = ((lane & 15) >> 2) * L::TSTR + ((lane & 3) * 4 + ((lane >> 4) & 1) * 16) * 2 + (4 * h) * L::TSTR;
 
-  f32x16 acc[DT];
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
+  // One pass over the T rows: accumulate, then write the wave's rows.  `what_tag` says what is
+  // accumulated (dS products or P products).
+  auto run_pass = [&](auto what_tag) {
+    constexpr bool kWantDs = (decltype(what_tag)::value == kAccDs);
+    f32x16 acc[DT];
+  #pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+  #pragma unroll
+      for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
 
-  if (ntiles > 0) {
-    if (kSorted) fetch_rows(0);
-    load_tile(0);
-    store_tile(0);
-  }
-  __syncthreads();
-
-  const int r_global = r_row;  // exact passes: for the causal mask
-  for (int kt = 0; kt < ntiles; ++kt) {
-    const bool more = kt + 1 < ntiles;
-    if (more) load_tile(kt + 1);
-
-    const unsigned char* yb = bufs + (kt & 1) * L::BUF;
-    const unsigned char* bb = yb + L::TILE;
-    const float* scb = sc + (kt & 1) * (2 * kTT);
-
-    // ---- P^T and dS^T ----
-    // Masks as limits on the in-tile row offset ko = koff - 4 h of an accumulator element
-    // (koff = 32 sub + 8 (i / 4) + 4 h + i % 4): masked iff ko >= hi2 (end of the T rows; keys
-    // after the query), ko < lo2 (queries before the key) or mlo2 <= ko < mhi2 (queries of
-    // the sampled key's own block, factor 1 - M of Algorithm 2).
-    const int tbase = kt * kTT;
-    int hi2 = nT - tbase - 4 * h;
-    int lo2 = -0x40000000, mlo2 = 0x40000000, mhi2 = 0x40000000, nb2 = 0x40000000;
-    float tile_bias = 0.f;
-    if (MODE == kBwdDqNode) {
-      tile_bias = (tbase >= nb) ? bias2 : 0.f;
-      if (tbase < nb) nb2 = nb - tbase - 4 * h;  // tile_bias is 0 on a tile that straddles nb
+    if (ntiles > 0) {
+      if (kSorted) fetch_rows(0);
+      load_tile(0);
+      store_tile(0);
     }
-    if (MODE == kBwdDkvSamp) {
-      tile_bias = bias2;
-      mlo2 = blk_r * g.b - (chunk_start + tbase) - 4 * h;
-      mhi2 = mlo2 + g.b;
-    }
-    if (MODE == kBwdDqExact && f.exact_causal) hi2 = min(hi2, r_global - w.k0 - tbase + 1 - 4 * h);
-    if (MODE == kBwdDkvExact && f.exact_causal) lo2 = r_global - t0 - tbase - 4 * h;
-    // highest / lowest ko of a lane: 59 / 0
-    const bool special = __any(hi2 <= 59 || lo2 > 0 || nb2 <= 59 || (mlo2 <= 59 && mhi2 > 0));
-
-    bf16x8 bf[2];  // B operand of the accumulating product (per half): dS^T or P^T as bf16
-    // one 32-row half of the tile at a time: S^T = Y X^T and dP^T = Bt A^T, then P^T / dS^T
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      f32x16 cs, es;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        cs[i] = 0.f;
-        es[i] = 0.f;
-      }
-      {
-        const unsigned char* yp0 = yb + (32 * sub + lq) * L::TSTR + 16 * h;
-        const unsigned char* bp0 = bb + (32 * sub + lq) * L::TSTR + 16 * h;
-#pragma unroll
-        for (int j = 0; j < KS; ++j) {
-          cs = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(yp0 + 32 * j), xreg[j], cs, 0, 0, 0);
-          if constexpr (kWantDs)
-            es = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(bp0 + 32 * j), areg[j], es, 0, 0, 0);
-        }
-      }
-      f32x4 nlq = {0.f, 0.f, 0.f, 0.f}, dq4 = {0.f, 0.f, 0.f, 0.f};  // -L log2(e), delta of four T rows (dK/dV passes)
-#pragma unroll
-      for (int jj = 0; jj < 2; ++jj) {
-        u32x4 pk, dk;
-#pragma unroll
-        for (int ee = 0; ee < 4; ++ee) {
-          // elements 8 jj + 2 ee, + 1: T rows 32 sub + 16 jj + 8 (ee / 2) + 4 h + 2 (ee % 2), + 1
-          f32x4 nlT = {0.f, 0.f, 0.f, 0.f}, dT = {0.f, 0.f, 0.f, 0.f};
-          if (!kDq && (ee % 2 == 0)) {
-            const int at = 32 * sub + 16 * jj + 8 * (ee / 2) + 4 * h;
-            nlq = *reinterpret_cast<const f32x4*>(scb + at);
-            dq4 = *reinterpret_cast<const f32x4*>(scb + kTT + at);
-          }
-          nlT = nlq;
-          dT = dq4;
-          float pv[2], dv[2];
-#pragma unroll
-          for (int z = 0; z < 2; ++z) {
-            const int i = 8 * jj + 2 * ee + z;          // accumulator element
-            float arg;
-            float dsub;
-            if (kDq) {
-              arg = __builtin_fmaf(cs[i], kLog2e, nl2_r + tile_bias);
-              dsub = del_r;
-            } else {
-              arg = __builtin_fmaf(cs[i], kLog2e, nlT[i % 4] + tile_bias);
-              dsub = dT[i % 4];
-            }
-            if (special) {
-              const int ko = 32 * sub + 8 * (i / 4) + (i % 4);
-              if (MODE == kBwdDqNode && ko >= nb2) arg += bias2;
-              bool msk = ko >= hi2;
-              if (MODE == kBwdDkvExact) msk = msk || (ko < lo2);
-              if (MODE == kBwdDkvSamp) msk = msk || ((unsigned)(ko - mlo2) < (unsigned)g.b);
-              if (msk) arg = -INFINITY;
-            }
-            const float p = __builtin_amdgcn_exp2f(arg);
-            pv[z] = p;
-            dv[z] = p * (es[i] - dsub);
-          }
-          pk[ee] = pack_bf16x2(pv[0], pv[1]);
-          dk[ee] = pack_bf16x2(dv[0], dv[1]);
-        }
-        bf[jj] = __builtin_bit_cast(bf16x8, kWantDs ? dk : pk);
-      }
-      // ---- acc^T += Y^T dS^T  or  acc^T += Bt^T P^T  for the 32 rows of this half ----
-      {
-        typedef short s16x4 __attribute__((ext_vector_type(4)));
-        typedef short s16x8 __attribute__((ext_vector_type(8)));
-        typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
-        const unsigned char* tb = (kWantDs ? yb : bb) + vtr_off;
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-          const int j = 2 * sub + jj;
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt) {
-            const unsigned char* tp = tb + (16 * j) * L::TSTR + (32 * dt) * 2;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(tp));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(tp + 8 * L::TSTR));
-            const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), bf[jj], acc[dt], 0, 0, 0);
-          }
-        }
-      }
-    }
-    if (more) store_tile(kt + 1);
     __syncthreads();
-  }
 
-  // ---- epilogue: the wave's 32 rows leave through an LDS transpose as whole rows.
-  // Node passes write fp32 rows into the per-level buffers.  Exact passes (the
-  // base case of Algorithm 4) write the final gradient in the tensors' dtype,
-  // after adding the rows of every level whose node holds these rows on the
-  // pass's side (queries: second half of the node; keys: first half).  The 32
-  // rows of a wave lie in one n_min block, so a level holds all or none of them
-  // and then as 32 consecutive rows.
-  unsigned char* ep = smem + wave * L::EP_WAVE;
-  int64_t* ep_rows = reinterpret_cast<int64_t*>(ep + 32 * L::EP_ROW);
-  int64_t* ep_pr = ep_rows + 32;
-  if (h == 0) ep_rows[lq] = r_valid ? out_row : (int64_t)-1;
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int g4 = 0; g4 < 4; ++g4) {
-      const int col = 32 * dt + 8 * g4 + 4 * h;
-      const f32x4 v = {acc[dt][4 * g4], acc[dt][4 * g4 + 1], acc[dt][4 * g4 + 2], acc[dt][4 * g4 + 3]};
-      *reinterpret_cast<f32x4*>(ep + lq * L::EP_ROW + col * 4) = v;
+    const int r_global = r_row;  // exact passes: for the causal mask
+    for (int kt = 0; kt < ntiles; ++kt) {
+      const bool more = kt + 1 < ntiles;
+      if (more) load_tile(kt + 1);
+
+      const unsigned char* yb = bufs + (kt & 1) * L::BUF;
+      const unsigned char* bb = yb + L::TILE;
+      const float* scb = sc + (kt & 1) * (2 * kTT);
+
+      // ---- P^T and dS^T ----
+      // Masks as limits on the in-tile row offset ko = koff - 4 h of an accumulator element
+      // (koff = 32 sub + 8 (i / 4) + 4 h + i % 4): masked iff ko >= hi2 (end of the T rows; keys
+      // after the query), ko < lo2 (queries before the key) or mlo2 <= ko < mhi2 (queries of
+      // the sampled key's own block, factor 1 - M of Algorithm 2).
+      const int tbase = kt * kTT;
+      int hi2 = nT - tbase - 4 * h;
+      int lo2 = -0x40000000, mlo2 = 0x40000000, mhi2 = 0x40000000, nb2 = 0x40000000;
+      float tile_bias = 0.f;
+      if (MODE == kBwdDqNode) {
+        tile_bias = (tbase >= nb) ? bias2 : 0.f;
+        if (tbase < nb) nb2 = nb - tbase - 4 * h;  // tile_bias is 0 on a tile that straddles nb
+      }
+      if (MODE == kBwdDkvSamp) {
+        tile_bias = bias2;
+        mlo2 = blk_r * g.b - (chunk_start + tbase) - 4 * h;
+        mhi2 = mlo2 + g.b;
+      }
+      if (MODE == kBwdDqExact && f.exact_causal) hi2 = min(hi2, r_global - w.k0 - tbase + 1 - 4 * h);
+      if (MODE == kBwdDkvExact && f.exact_causal) lo2 = r_global - t0 - tbase - 4 * h;
+      // highest / lowest ko of a lane: 59 / 0
+      const bool special = __any(hi2 <= 59 || lo2 > 0 || nb2 <= 59 || (mlo2 <= 59 && mhi2 > 0));
+
+      bf16x8 bf[2];  // B operand of the accumulating product (per half): dS^T or P^T as bf16
+      // one 32-row half of the tile at a time: S^T = Y X^T and dP^T = Bt A^T, then P^T / dS^T
+  #pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        f32x16 cs, es;
+  #pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          cs[i] = 0.f;
+          es[i] = 0.f;
+        }
+        {
+          const unsigned char* yp0 = yb + (32 * sub + lq) * L::TSTR + 16 * h;
+          const unsigned char* bp0 = bb + (32 * sub + lq) * L::TSTR + 16 * h;
+  #pragma unroll
+          for (int j = 0; j < KS; ++j) {
+            cs = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(yp0 + 32 * j), xreg[j], cs, 0, 0, 0);
+            if constexpr (kWantDs)
+              es = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(bp0 + 32 * j), areg[j], es, 0, 0, 0);
+          }
+        }
+        f32x4 nlq = {0.f, 0.f, 0.f, 0.f}, dq4 = {0.f, 0.f, 0.f, 0.f};  // -L log2(e), delta of four T rows (dK/dV passes)
+  #pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          u32x4 pk, dk;
+  #pragma unroll
+          for (int ee = 0; ee < 4; ++ee) {
+            // elements 8 jj + 2 ee, + 1: T rows 32 sub + 16 jj + 8 (ee / 2) + 4 h + 2 (ee % 2), + 1
+            f32x4 nlT = {0.f, 0.f, 0.f, 0.f}, dT = {0.f, 0.f, 0.f, 0.f};
+            if (!kDq && (ee % 2 == 0)) {
+              const int at = 32 * sub + 16 * jj + 8 * (ee / 2) + 4 * h;
+              nlq = *reinterpret_cast<const f32x4*>(scb + at);
+              dq4 = *reinterpret_cast<const f32x4*>(scb + kTT + at);
+            }
+            nlT = nlq;
+            dT = dq4;
+            float pv[2], dv[2];
+  #pragma unroll
+            for (int z = 0; z < 2; ++z) {
+              const int i = 8 * jj + 2 * ee + z;          // accumulator element
+              float arg;
+              float dsub;
+              if (kDq) {
+                arg = __builtin_fmaf(cs[i], kLog2e, nl2_r + tile_bias);
+                dsub = del_r;
+              } else {
+                arg = __builtin_fmaf(cs[i], kLog2e, nlT[i % 4] + tile_bias);
+                dsub = dT[i % 4];
+              }
+              if (special) {
+                const int ko = 32 * sub + 8 * (i / 4) + (i % 4);
+                if (MODE == kBwdDqNode && ko >= nb2) arg += bias2;
+                bool msk = ko >= hi2;
+                if (MODE == kBwdDkvExact) msk = msk || (ko < lo2);
+                if (MODE == kBwdDkvSamp) msk = msk || ((unsigned)(ko - mlo2) < (unsigned)g.b);
+                if (msk) arg = -INFINITY;
+              }
+              const float p = __builtin_amdgcn_exp2f(arg);
+              pv[z] = p;
+              dv[z] = p * (es[i] - dsub);
+            }
+            pk[ee] = pack_bf16x2(pv[0], pv[1]);
+            dk[ee] = pack_bf16x2(dv[0], dv[1]);
+          }
+          bf[jj] = __builtin_bit_cast(bf16x8, kWantDs ? dk : pk);
+        }
+        // ---- acc^T += Y^T dS^T  or  acc^T += Bt^T P^T  for the 32 rows of this half ----
+        {
+          typedef short s16x4 __attribute__((ext_vector_type(4)));
+          typedef short s16x8 __attribute__((ext_vector_type(8)));
+          typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+          const unsigned char* tb = (kWantDs ? yb : bb) + vtr_off;
+  #pragma unroll
+          for (int jj = 0; jj < 2; ++jj) {
+            const int j = 2 * sub + jj;
+  #pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+              const unsigned char* tp = tb + (16 * j) * L::TSTR + (32 * dt) * 2;
+              const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(tp));
+              const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(tp + 8 * L::TSTR));
+              const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+              acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), bf[jj], acc[dt], 0, 0, 0);
+            }
+          }
+        }
+      }
+      if (more) store_tile(kt + 1);
+      __syncthreads();
     }
-  float* dst32 = kWantDs ? a.out1 : a.out2;
-  if (!kExact) {
+
+    // ---- epilogue: the wave's 32 rows leave through an LDS transpose as whole rows.
+    // Node passes write fp32 rows into the per-level buffers.  Exact passes (the
+    // base case of Algorithm 4) write the final gradient in the tensors' dtype,
+    // after adding the rows of every level whose node holds these rows on the
+    // pass's side (queries: second half of the node; keys: first half).  The 32
+    // rows of a wave lie in one n_min block, so a level holds all or none of them
+    // and then as 32 consecutive rows.
+    unsigned char* ep = smem + wave * L::EP_WAVE;
+    int64_t* ep_rows = reinterpret_cast<int64_t*>(ep + 32 * L::EP_ROW);
+    int64_t* ep_pr = ep_rows + 32;
+    if (h == 0) ep_rows[lq] = r_valid ? out_row : (int64_t)-1;
+  #pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+  #pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int col = 32 * dt + 8 * g4 + 4 * h;
+        const f32x4 v = {acc[dt][4 * g4], acc[dt][4 * g4 + 1], acc[dt][4 * g4 + 2], acc[dt][4 * g4 + 3]};
+        *reinterpret_cast<f32x4*>(ep + lq * L::EP_ROW + col * 4) = v;
+      }
+    float* dst32 = kWantDs ? a.out1 : a.out2;
+    if (!kExact) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      constexpr int CH = D / 4;  // 16-byte pieces per fp32 row
+      for (int idx = lane; idx < 32 * CH; idx += 64) {
+        const int row = idx / CH, ch = idx % CH;
+        const int64_t r64 = ep_rows[row];
+        if (r64 >= 0)
+          *reinterpret_cast<f32x4*>(dst32 + r64 * D + ch * 4) = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 16);
+      }
+      return;
+    }
+    uint16_t* dst16 = reinterpret_cast<uint16_t*>(kWantDs ? a.fin1 : a.fin2);
+    const float* lvl = kWantDs ? a.lvl1 : a.lvl2;
+    int nfold = 0;
+    if (lvl != nullptr) {
+      const int i0 = w.q0 + 32 * __builtin_amdgcn_readfirstlane(wave);
+      const bool want_second = kDq;
+      for (int l = 0; l < g.levels; ++l) {
+        const int sl = g.n >> (l + 1);
+        const bool second = ((i0 / sl) & 1) != 0;
+        if (second != want_second) continue;
+        if (lane == 0) ep_pr[nfold] = ((int64_t)l * g.BH + w.bh) * g.n_cov + (int64_t)(i0 / (2 * sl)) * sl + (i0 % sl);
+        ++nfold;
+      }
+    }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    constexpr int CH = D / 4;  // 16-byte pieces per fp32 row
-    for (int idx = lane; idx < 32 * CH; idx += 64) {
-      const int row = idx / CH, ch = idx % CH;
-      const int64_t r64 = ep_rows[row];
-      if (r64 >= 0)
-        *reinterpret_cast<f32x4*>(dst32 + r64 * D + ch * 4) = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 16);
-    }
-    return;
-  }
-  uint16_t* dst16 = reinterpret_cast<uint16_t*>(kWantDs ? a.fin1 : a.fin2);
-  const float* lvl = kWantDs ? a.lvl1 : a.lvl2;
-  int nfold = 0;
-  if (lvl != nullptr) {
-    const int i0 = w.q0 + 32 * __builtin_amdgcn_readfirstlane(wave);
-    const bool want_second = kDq;
-    for (int l = 0; l < g.levels; ++l) {
-      const int sl = g.n >> (l + 1);
-      const bool second = ((i0 / sl) & 1) != 0;
-      if (second != want_second) continue;
-      if (lane == 0) ep_pr[nfold] = ((int64_t)l * g.BH + w.bh) * g.n_cov + (int64_t)(i0 / (2 * sl)) * sl + (i0 % sl);
-      ++nfold;
-    }
-  }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  constexpr int CH8 = D / 8;  // 8-element pieces per row
-  // NF: compile-time count of folded rows so their loads are issued together; 0 = run-time count nfold
-  auto rows_out = [&](auto nf_tag) {
-    constexpr int NF = decltype(nf_tag)::value;
-    const int nf = NF > 0 ? NF : nfold;
-    for (int idx = lane; idx < 32 * CH8; idx += 64) {
-      const int row = idx / CH8, ch = idx % CH8;
-      const int64_t r64 = ep_rows[row];
-      if (r64 < 0) continue;
-      f32x4 v0 = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 32);
-      f32x4 v1 = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 32 + 16);
-      if (NF > 0) {
-        f32x4 p0[NF > 0 ? NF : 1], p1[NF > 0 ? NF : 1];
-#pragma unroll
-        for (int c = 0; c < NF; ++c) {
-          const float* pp = lvl + (ep_pr[c] + row) * D + ch * 8;
-          p0[c] = *reinterpret_cast<const f32x4*>(pp);
-          p1[c] = *reinterpret_cast<const f32x4*>(pp + 4);
+    constexpr int CH8 = D / 8;  // 8-element pieces per row
+    // NF: compile-time count of folded rows so their loads are issued together; 0 = run-time count nfold
+    auto rows_out = [&](auto nf_tag) {
+      constexpr int NF = decltype(nf_tag)::value;
+      const int nf = NF > 0 ? NF : nfold;
+      for (int idx = lane; idx < 32 * CH8; idx += 64) {
+        const int row = idx / CH8, ch = idx % CH8;
+        const int64_t r64 = ep_rows[row];
+        if (r64 < 0) continue;
+        f32x4 v0 = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 32);
+        f32x4 v1 = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 32 + 16);
+        if (NF > 0) {
+          f32x4 p0[NF > 0 ? NF : 1], p1[NF > 0 ? NF : 1];
+  #pragma unroll
+          for (int c = 0; c < NF; ++c) {
+            const float* pp = lvl + (ep_pr[c] + row) * D + ch * 8;
+            p0[c] = *reinterpret_cast<const f32x4*>(pp);
+            p1[c] = *reinterpret_cast<const f32x4*>(pp + 4);
+          }
+  #pragma unroll
+          for (int c = 0; c < NF; ++c) {
+            v0 += p0[c];
+            v1 += p1[c];
+          }
+        } else {
+          for (int c = 0; c < nf; ++c) {
+            const float* pp = lvl + (ep_pr[c] + row) * D + ch * 8;
+            v0 += *reinterpret_cast<const f32x4*>(pp);
+            v1 += *reinterpret_cast<const f32x4*>(pp + 4);
+          }
         }
-#pragma unroll
-        for (int c = 0; c < NF; ++c) {
-          v0 += p0[c];
-          v1 += p1[c];
-        }
-      } else {
-        for (int c = 0; c < nf; ++c) {
-          const float* pp = lvl + (ep_pr[c] + row) * D + ch * 8;
-          v0 += *reinterpret_cast<const f32x4*>(pp);
-          v1 += *reinterpret_cast<const f32x4*>(pp + 4);
-        }
+        const u32x4 pk = {pack_bf16x2(v0.x, v0.y), pack_bf16x2(v0.z, v0.w), pack_bf16x2(v1.x, v1.y), pack_bf16x2(v1.z, v1.w)};
+        *reinterpret_cast<u32x4*>(dst16 + r64 * D + ch * 8) = pk;
       }
-      const u32x4 pk = {pack_bf16x2(v0.x, v0.y), pack_bf16x2(v0.z, v0.w), pack_bf16x2(v1.x, v1.y), pack_bf16x2(v1.z, v1.w)};
-      *reinterpret_cast<u32x4*>(dst16 + r64 * D + ch * 8) = pk;
+    };
+    switch (nfold) {
+      case 1: rows_out(std::integral_constant<int, 1>{}); break;
+      case 2: rows_out(std::integral_constant<int, 2>{}); break;
+      case 3: rows_out(std::integral_constant<int, 3>{}); break;
+      case 4: rows_out(std::integral_constant<int, 4>{}); break;
+      case 5: rows_out(std::integral_constant<int, 5>{}); break;
+      case 6: rows_out(std::integral_constant<int, 6>{}); break;
+      default: rows_out(std::integral_constant<int, 0>{}); break;  // none, or more than six
     }
   };
-  switch (nfold) {
-    case 1: rows_out(std::integral_constant<int, 1>{}); break;
-    case 2: rows_out(std::integral_constant<int, 2>{}); break;
-    case 3: rows_out(std::integral_constant<int, 3>{}); break;
-    case 4: rows_out(std::integral_constant<int, 4>{}); break;
-    case 5: rows_out(std::integral_constant<int, 5>{}); break;
-    case 6: rows_out(std::integral_constant<int, 6>{}); break;
-    default: rows_out(std::integral_constant<int, 0>{}); break;  // none, or more than six
+  if constexpr (WHAT == kAccBoth) {
+    static_assert(WHAT != kAccBoth || !kExact, "the two-in-one form writes per-level rows only");
+    run_pass(std::integral_constant<int, kAccDs>{});
+    __syncthreads();  // the epilogue staged rows where the T tiles go
+    run_pass(std::integral_constant<int, kAccP>{});
+  } else {
+    run_pass(std::integral_constant<int, WHAT>{});
   }
 }
 
@@ -537,7 +551,7 @@ static int launch_bwd_d(const BwdArgs& a, int mode, int grid, hipStream_t st) {
   switch (mode) {
     case kBwdDqNode: return launch_bwd_one<D, kBwdDqNode, kAccDs>(a, grid, st);
     case kBwdDqExact: return launch_bwd_one<D, kBwdDqExact, kAccDs>(a, grid, st);
-    case kBwdDkvBlock: return launch_bwd_pair<D, kBwdDkvBlock>(a, grid, st);
+    case kBwdDkvBlock: return launch_bwd_one<D, kBwdDkvBlock, kAccBoth>(a, grid, st);  // short T loops: one launch, shared prologue
     case kBwdDkvSamp: return launch_bwd_pair<D, kBwdDkvSamp>(a, grid, st);
     case kBwdDkvExact: return launch_bwd_pair<D, kBwdDkvExact>(a, grid, st);
     default: return HA_ERR_SHAPE;
