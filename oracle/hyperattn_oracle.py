@@ -480,12 +480,12 @@ def hyperattn_backward(Q, K, V, dO, b, m, r, causal=False, n_min=4096, seed=0, R
 # Readings: the constant in C_i = Theta(eps^2 m / (n log n) * (masked row sum +
 # tau / kappa)) is a caller's number `cap_scale` (natural log; cap_scale <= 0: no
 # cap); kappa is a caller's number (<= 0: no lower cap); the subset T is m rows
-# drawn uniformly WITH replacement from counter stream 0; the squared row norms
-# are quantised to 20 bits relative to the largest so that the draws are
-# integer decisions: q_l = floor(2^20 |V_l|^2 / max|V|^2) + 1, p_l = q_l / sum q,
-# draw r of head bh = first l with prefix(q)[l] > (u64 * sum q) >> 64, u64 from
-# counter bh * m + r of stream 2; the rescaling 1 / (m p_l) is the exact one for
-# these p_l, so S^T S stays unbiased for the identity.
+# drawn uniformly WITH replacement (Lemma 1's proof bounds the chance that T
+# misses the t heaviest rows by (1 - t/n)^m, the bound for independent draws)
+# from counter stream 0.  Lemma 2's rows are drawn with p_l = |V_l|^2 / |V|_F^2
+# by inverting the cumulative distribution: draw r of head bh takes the uniform
+# u in (0, 1) given by the top 53 bits of counter bh * m + r of stream 2 and is
+# the first l with p_0 + ... + p_l > u; its rescaling is 1 / (m p_l).
 # --------------------------------------------------------------------------
 STREAM_TAU_ROWS = 0
 STREAM_VNORM = 2
@@ -496,28 +496,38 @@ def tau_rows(seed: int, n: int, m: int) -> np.ndarray:
     return np.array([((rand_u64(seed, STREAM_TAU_ROWS, j) >> 32) * n) >> 32 for j in range(m)], dtype=np.int64)
 
 
-def vnorm_weights(Vh) -> np.ndarray:
-    """Integer sampling weights q_l of one head's value rows."""
+def vnorm_probabilities(Vh) -> np.ndarray:
+    """Lemma 2: p_l = |V_l|^2 / |V|_F^2 (uniform if V = 0, where every choice gives the same product)."""
     Vh = np.asarray(Vh, dtype=np.float64)
-    w = np.zeros(Vh.shape[0], dtype=np.float64)
-    for c in range(Vh.shape[1]):                 # ascending c, one rounding per add, like the kernel
-        w = w + Vh[:, c] * Vh[:, c]
-    wmax = w.max()
-    if not wmax > 0.0:
-        return np.ones(Vh.shape[0], dtype=np.int64)
-    return np.floor(w / wmax * float(1 << 20)).astype(np.int64) + 1
+    w = np.sum(Vh ** 2, axis=1)
+    total = w.sum()
+    if not total > 0.0:
+        return np.full(Vh.shape[0], 1.0 / Vh.shape[0])
+    return w / total
 
 
-def vnorm_samples(Vh, seed: int, bh: int, m: int):
-    """(indices l'_1..l'_m, log of their rescaling factors 1 / (m p_l)) for head bh (Lemma 2)."""
-    q = vnorm_weights(Vh)
-    prefix = np.cumsum(q)
-    total = int(prefix[-1])
-    idx = np.empty(m, dtype=np.int64)
-    for r_ in range(m):
-        t = (rand_u64(seed, STREAM_VNORM, bh * m + r_) * total) >> 64
-        idx[r_] = int(np.searchsorted(prefix, t, side="right"))
-    logw = np.log(float(total)) - np.log(float(m)) - np.log(q[idx].astype(np.float64))
+def vnorm_uniforms(seed: int, bh: int, m: int) -> np.ndarray:
+    return np.array([_unit_open(rand_u64(seed, STREAM_VNORM, bh * m + r_)) for r_ in range(m)])
+
+
+def vnorm_samples(Vh, seed: int, bh: int, m: int, replay=None, margin=None):
+    """(indices l'_1..l'_m, log of their rescaling factors 1 / (m p_l)) for head bh (Lemma 2).
+
+    `replay` {r: l} fixes individual draws (used to follow another evaluation
+    through a uniform that falls within rounding of a boundary of the
+    cumulative distribution); `margin`, if a list, receives for every draw the
+    distance of its uniform to the nearest such boundary."""
+    p = vnorm_probabilities(Vh)
+    cdf = np.cumsum(p)
+    u = vnorm_uniforms(seed, bh, m)
+    idx = np.minimum(np.searchsorted(cdf, u, side="right"), len(p) - 1).astype(np.int64)
+    if margin is not None:
+        lower = np.where(idx > 0, cdf[np.maximum(idx - 1, 0)], 0.0)
+        margin.extend(np.minimum(u - lower, cdf[idx] - u).tolist())
+    if replay:
+        for r_, l in replay.items():
+            idx[r_] = l
+    logw = -np.log(float(m) * p[idx])
     return idx, logw
 
 
@@ -562,8 +572,11 @@ def alg2_head_forward(Qh, Kh, Vh, codes_q, codes_k, b, samples, t_rows, cap_scal
     return num, log_dt, log_tau
 
 
-def hyperattn_forward_alg2(Q, K, V, b, m, r, seed=0, cap_scale=0.0, kappa=0.0, vnorm_sampling=False, R=None):
-    """Unmasked HyperAttention with Algorithm 2's estimator as printed.  Returns (out, log d~, log tau [B*H])."""
+def hyperattn_forward_alg2(Q, K, V, b, m, r, seed=0, cap_scale=0.0, kappa=0.0, vnorm_sampling=False, R=None,
+                           vnorm_from=None, vnorm_replay=None):
+    """Unmasked HyperAttention with Algorithm 2's estimator as printed.  Returns (out, log d~, log tau [B*H]).
+    vnorm_from: the value tensor whose row norms define Lemma 2's draws (default V itself; the tests
+    pass V when they evaluate the same draws on |V|); vnorm_replay: {bh: {r: l}} fixed draws."""
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
@@ -578,7 +591,10 @@ def hyperattn_forward_alg2(Q, K, V, b, m, r, seed=0, cap_scale=0.0, kappa=0.0, v
     for bh in range(B * H):
         q, k, v = (x.reshape(B * H, n, -1)[bh] for x in (Q, K, V))
         cq, ck = lsh_codes(lsh_project(q, R), r), lsh_codes(lsh_project(k, R), r)
-        vs = vnorm_samples(v, seed, bh, m) if vnorm_sampling else None
+        vs = None
+        if vnorm_sampling:
+            vsrc = v if vnorm_from is None else np.asarray(vnorm_from, dtype=np.float64).reshape(B * H, n, -1)[bh]
+            vs = vnorm_samples(vsrc, seed, bh, m, replay=(vnorm_replay or {}).get(bh))
         o, l, t = alg2_head_forward(q, k, v, cq, ck, b, samples, t_rows, cap_scale, kappa, vs)
         out.reshape(B * H, n, -1)[bh] = o
         lse.reshape(B * H, n)[bh] = l

@@ -474,17 +474,54 @@ def test_alg2_tau_cap_and_lower_cap_follow_their_definitions():
     assert (np.maximum(d_plain, tau / kappa) > d_plain).any()      # the lower cap binds somewhere in this instance
 
 
+def test_tau_rows_are_uniform_and_independent_of_the_samples():
+    """T of Algorithm 2: m uniform rows.  A chi-square test over many seeds pins the law (a biased or
+    truncated draw fails it); T must also not repeat the estimator's own index set."""
+    n, m, seeds = 64, 256, 40
+    counts = np.zeros(n)
+    for s in range(seeds):
+        T = orc.tau_rows(s, n, m)
+        assert T.shape == (m,) and T.min() >= 0 and T.max() < n
+        counts += np.bincount(T, minlength=n)
+    expected = seeds * m / n
+    chi2 = ((counts - expected) ** 2 / expected).sum()
+    assert chi2 < 63 + 5 * math.sqrt(2 * 63), chi2            # mean n-1, sd sqrt(2(n-1))
+    assert chi2 > 63 - 5 * math.sqrt(2 * 63), chi2            # nor suspiciously regular (a stride would be)
+    # both ends of the range occur, also for n that is no power of two
+    T = np.concatenate([orc.tau_rows(s, 1000, 300) for s in range(30)])
+    assert T.min() < 5 and T.max() > 994
+    # serial independence: consecutive draws are uncorrelated
+    T = orc.tau_rows(7, 1 << 20, 4000).astype(np.float64)
+    assert abs(np.corrcoef(T[:-1], T[1:])[0, 1]) < 5 / math.sqrt(4000)
+    assert not np.array_equal(orc.tau_rows(3, 4096, 64), orc.make_samples(3, 0, 0, 4096, 64))
+
+
 def test_vnorm_sampling_weights_distribution_and_unbiasedness():
     n, d, m = 48, 6, 16
     rng = np.random.default_rng(4)
     Q, K = (rng.standard_normal((1, 1, n, d)) * 0.7 for _ in range(2))
     V = rng.standard_normal((1, 1, n, d)) * rng.uniform(0.1, 3.0, size=(1, 1, n, 1))      # very unequal row norms
-    q = orc.vnorm_weights(V[0, 0])
-    w = (V[0, 0] ** 2).sum(axis=1)
-    assert q.min() >= 1 and q.max() == (1 << 20) + 1
-    np.testing.assert_allclose(q / q.sum(), w / w.sum(), atol=2e-6)
-    assert (orc.vnorm_weights(np.zeros((5, 3))) == 1).all()
-    # draws follow p_l = q_l / sum q, and E[A S^T S V] = A V (Lemma 2's sampling matrix is unbiased)
+    p = orc.vnorm_probabilities(V[0, 0])
+    # Lemma 2's law, retyped with a scalar loop
+    w = np.array([sum(x * x for x in row) for row in V[0, 0]])
+    np.testing.assert_allclose(p, w / w.sum(), rtol=1e-13)
+    np.testing.assert_allclose(orc.vnorm_probabilities(np.zeros((5, 3))), 0.2)
+    # a zero row is never drawn; a single non-zero row is always drawn, with rescaling 1/m
+    Vz = np.zeros((7, 3))
+    Vz[4] = [1.0, -2.0, 0.5]
+    idx, logw = orc.vnorm_samples(Vz, 1, 0, 9)
+    assert (idx == 4).all()
+    np.testing.assert_allclose(logw, -math.log(9))
+    # the margin of every draw is its uniform's distance to the nearest boundary of the cumulative law
+    marg = []
+    idx, _ = orc.vnorm_samples(V[0, 0], 5, 0, m, margin=marg)
+    cdf = np.concatenate([[0.0], np.cumsum(p)])
+    u = orc.vnorm_uniforms(5, 0, m)
+    for r_ in range(m):
+        assert cdf[idx[r_]] <= u[r_] < cdf[idx[r_] + 1]
+        assert abs(marg[r_] - min(u[r_] - cdf[idx[r_]], cdf[idx[r_] + 1] - u[r_])) < 1e-15
+    assert orc.vnorm_samples(V[0, 0], 5, 0, m, replay={3: 11})[0][3] == 11
+    # draws follow p_l, and E[A S^T S V] = A V (Lemma 2's sampling matrix is unbiased)
     A = np.exp(Q[0, 0] @ K[0, 0].T)
     exact = A @ V[0, 0]
     acc = np.zeros_like(exact)
@@ -494,7 +531,6 @@ def test_vnorm_sampling_weights_distribution_and_unbiasedness():
         idx, logw = orc.vnorm_samples(V[0, 0], s, 0, m)
         acc += (A[:, idx] * np.exp(logw)[None, :]) @ V[0, 0][idx]
         counts += np.bincount(idx, minlength=n)
-    p = q / q.sum()
     assert np.abs(counts / (trials * m) - p).max() < 5 * np.sqrt(p.max() / (trials * m))
     rel = np.linalg.norm(acc / trials - exact) / np.linalg.norm(exact)
     assert rel < 0.05, rel
