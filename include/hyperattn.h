@@ -276,9 +276,10 @@ size_t exact_attn_backward_workspace_bytes(const ha_shape* shape);
  *   out_i = (1/d~_i) sum_r exp<q_i,k_{l'_r}> v_{l'_r} / (m p_{l'_r}),  l'_r drawn with p_l ~ |V_l|^2   (vnorm_sampling)
  *        or (1/d~_i) (masked part + (n/m) sum_j (1 - M_{i,l_j}) exp<q_i,k_{l_j}> v_{l_j})             (otherwise)
  * lse receives log d~.  The constants the paper leaves open (the Theta of C_i,
- * kappa) are the caller's.  Squared row norms are quantised to 20 bits relative
- * to the largest (p_l = q_l / sum q, q_l = floor(2^20 |V_l|^2 / max) + 1) so that
- * the draws are integer decisions; the rescaling uses the same p_l.
+ * kappa) are the caller's.  Lemma 2's rows are drawn with p_l = |V_l|^2 / |V|_F^2
+ * by inverting the cumulative distribution in fp64 (draw r of head bh: first l
+ * whose inclusive prefix sum of squared norms exceeds u |V|_F^2, u in (0,1) from
+ * the top 53 bits of counter bh*m + r of stream 2).
  * workspace: device, 256-byte aligned, >= ha_alg2_workspace_bytes(); it starts
  * with the forward's layout (ha_workspace_layout) followed by the regions below.
  * Errors as hyperattn_forward, plus HA_ERR_SHAPE for causal params. */
@@ -295,9 +296,7 @@ typedef struct {
   size_t log_unmasked_t;     /* float [B*H][m]: log of their unmasked row sums */
   size_t log_tau;            /* float [B*H] */
   size_t vnorm_w;            /* double [B*H][n]: |V_l|^2 */
-  size_t vnorm_max;          /* uint64 [B*H]: bit pattern of the largest */
-  size_t vnorm_q;            /* uint32 [B*H][n]: q_l */
-  size_t vnorm_prefix;       /* uint64 [B*H][n]: inclusive prefix sums of q */
+  size_t vnorm_prefix;       /* double [B*H][n]: inclusive prefix sums of |V_l|^2 */
   size_t vnorm_samples;      /* int32 [B*H][m]: l'_r */
   size_t vnorm_logw;         /* float [B*H][m]: log(1 / (m p_{l'_r})) */
   size_t log_unmasked_parts; /* float [8][B*H][m]: scratch, the unmasked row sums of T over eight ranges of keys */

@@ -46,7 +46,7 @@ class HaAlg2Options(ctypes.Structure):
 
 class HaAlg2WsLayout(ctypes.Structure):
     _fields_ = [(k, c_size_t) for k in ("forward_bytes", "pos_q", "tau_rows", "log_unmasked_t", "log_tau", "vnorm_w",
-                                        "vnorm_max", "vnorm_q", "vnorm_prefix", "vnorm_samples", "vnorm_logw",
+                                        "vnorm_prefix", "vnorm_samples", "vnorm_logw",
                                         "log_unmasked_parts",
                                         "total_bytes")]
 
@@ -503,6 +503,6 @@ def alg2_workspace_views(workspace, shape: HaShape, params: HaParams):
     return {"layout": lay,
             "tau_rows": view(lay.tau_rows, m, torch.int32, (m,)),
             "log_tau": view(lay.log_tau, BH, torch.float32, (BH,)),
-            "vnorm_q": view(lay.vnorm_q, BH * n, torch.int32, (BH, n)),
+            "vnorm_w": view(lay.vnorm_w, BH * n, torch.float64, (BH, n)),
             "vnorm_samples": view(lay.vnorm_samples, BH * m, torch.int32, (BH, m)),
             "vnorm_logw": view(lay.vnorm_logw, BH * m, torch.float32, (BH, m))}

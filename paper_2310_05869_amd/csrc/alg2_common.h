@@ -25,10 +25,8 @@ struct Alg2Args {
   float* log_unm_parts;    // [kAlg2TauSplits][BH][m]: the same over ranges of keys (matrix-core form)
   int32_t tau_splits;      // 0: log_unm_t is final; else the number of key ranges to combine
   float* log_tau;          // [BH]
-  double* vw;              // [BH][n]
-  unsigned long long* vmax;     // [BH] bit pattern of the largest vw
-  uint32_t* vq;            // [BH][n]
-  unsigned long long* vprefix;  // [BH][n] inclusive
+  double* vw;              // [BH][n] squared norms of the value rows
+  double* vprefix;         // [BH][n] their inclusive prefix sums
   int32_t* vsamp;          // [BH][m]
   float* vlogw;            // [BH][m]
   uint64_t seed;

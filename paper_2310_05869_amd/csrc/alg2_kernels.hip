@@ -12,11 +12,10 @@
 // forms of the two heavy steps (alg2_mfma.hip) do not take; the draws, weights and prefix
 // sums are computed here for both.
 //
-// The draws by squared row norm are integer decisions so that they can be
-// reproduced exactly elsewhere: |V_l|^2 is summed in fp64 over ascending
-// columns, quantised to q_l = floor(2^20 |V_l|^2 / max |V|^2) + 1, and draw r of
-// head bh is the first l whose inclusive prefix sum of q exceeds
-// (u64 * sum q) >> 64, u64 being counter bh * m + r of stream 2.
+// Lemma 2's rows are drawn with p_l = |V_l|^2 / |V|_F^2 by inverting the
+// cumulative distribution in fp64: draw r of head bh takes the uniform u in
+// (0, 1) formed by the top 53 bits of counter bh * m + r of stream 2 and is the
+// first l whose inclusive prefix sum of squared norms exceeds u |V|_F^2.
 #include "attn_common.h"
 #include "alg2_common.h"
 
@@ -41,7 +40,6 @@ __global__ void alg2_prep_kernel(Alg2Args a) {
     const uint64_t hi = rand_u64(a.seed, kStreamTauRows, (uint64_t)t) >> 32;
     a.tau_rows[t] = (int32_t)((hi * (uint64_t)g.n) >> 32);
   }
-  if (t < g.BH) a.vmax[t] = 0ull;
   // pos_q = P_Q^-1
   if (t < (int64_t)g.BH * g.n) {
     const int64_t bh = t / g.n;
@@ -49,8 +47,8 @@ __global__ void alg2_prep_kernel(Alg2Args a) {
   }
 }
 
-// Squared row norms of V in fp64, summed over ascending columns (one thread per row, so the order
-// is fixed); 64 rows per workgroup come in through LDS so that the global loads are coalesced.
+// Squared row norms of V in fp64 (one thread per row); 64 rows per workgroup come in through LDS
+// so that the global loads are coalesced.
 constexpr int kVwRows = 64;
 
 template <typename T, int D>
@@ -74,56 +72,38 @@ __global__ __launch_bounds__(256) void vnorm_weight_kernel(Alg2Args a) {
   double w = 0.0;
   for (int c = 0; c < D; ++c) {
     const double x = (double)elem<T>(v + c);
-    w = w + x * x;  // one rounding per add (the product of two fp32-representable values is exact in fp64)
+    w = w + x * x;  // the product of two fp32-representable values is exact in fp64
   }
   const int64_t row = row0 + (active ? threadIdx.x : 0);
   if (active) a.vw[row] = w;
-  // largest weight of the head (non-negative doubles order like their bits): one atomic per
-  // workgroup when its rows share a head, else one per row
-  unsigned long long bits = active ? (unsigned long long)__double_as_longlong(w) : 0ull;
-  const int64_t head = row / g.n;
-  if (row0 / g.n == (row0 + nrows - 1) / g.n) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-      const unsigned long long other = __shfl_xor(bits, o);
-      bits = other > bits ? other : bits;
-    }
-    if (threadIdx.x == 0) atomicMax(&a.vmax[head], bits);
-  } else if (active) {
-    atomicMax(&a.vmax[head], bits);
-  }
 }
 
 constexpr int kScanThreads = 1024;
 
+// Inclusive prefix sums of the squared norms of one head, in fp64 and in a fixed order (a thread
+// sums its run of rows, the threads' sums are scanned, every thread then walks its run again).
 __global__ __launch_bounds__(kScanThreads) void vnorm_scan_kernel(Alg2Args a) {
-  __shared__ unsigned long long part[kScanThreads];
+  __shared__ double part[kScanThreads];
   const Geometry& g = a.g;
   const int bh = blockIdx.x;
   const int tid = threadIdx.x;
-  const double wmax = __longlong_as_double((long long)a.vmax[bh]);
   const int per = (g.n + kScanThreads - 1) / kScanThreads;
   const int lo = min(g.n, tid * per), hi = min(g.n, lo + per);
-  unsigned long long sum = 0;
-  for (int l = lo; l < hi; ++l) {
-    uint32_t q = 1u;
-    if (wmax > 0.0) q = (uint32_t)floor(a.vw[(int64_t)bh * g.n + l] / wmax * 1048576.0) + 1u;
-    a.vq[(int64_t)bh * g.n + l] = q;
-    sum += q;
-  }
+  const double* w = a.vw + (int64_t)bh * g.n;
+  double sum = 0.0;
+  for (int l = lo; l < hi; ++l) sum += w[l];
   part[tid] = sum;
   __syncthreads();
-  // exclusive prefix over the threads' sums (integers: any order gives the same result)
   for (int off = 1; off < kScanThreads; off <<= 1) {
-    unsigned long long v = 0;
+    double v = 0.0;
     if (tid >= off) v = part[tid - off];
     __syncthreads();
     part[tid] += v;
     __syncthreads();
   }
-  unsigned long long run = part[tid] - sum;
+  double run = tid > 0 ? part[tid - 1] : 0.0;
   for (int l = lo; l < hi; ++l) {
-    run += a.vq[(int64_t)bh * g.n + l];
+    run += w[l];
     a.vprefix[(int64_t)bh * g.n + l] = run;
   }
 }
@@ -133,17 +113,27 @@ __global__ void vnorm_sample_kernel(Alg2Args a) {
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= (int64_t)g.BH * g.m) return;
   const int bh = (int)(t / g.m);
-  const unsigned long long* prefix = a.vprefix + (int64_t)bh * g.n;
-  const unsigned long long total = prefix[g.n - 1];
-  const unsigned long long target = __umul64hi(rand_u64(a.seed, kStreamVnorm, (uint64_t)t), total);
-  int lo = 0, hi = g.n - 1;  // first l with prefix[l] > target
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if (prefix[mid] > target) hi = mid;
-    else lo = mid + 1;
+  const double* prefix = a.vprefix + (int64_t)bh * g.n;
+  const double total = prefix[g.n - 1];
+  const double u = ((double)(rand_u64(a.seed, kStreamVnorm, (uint64_t)t) >> 11) + 0.5) * 0x1.0p-53;
+  int lo;
+  double p;
+  if (total > 0.0) {
+    const double target = u * total;
+    int hi = g.n - 1;  // first l with prefix[l] > target
+    lo = 0;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (prefix[mid] > target) hi = mid;
+      else lo = mid + 1;
+    }
+    p = a.vw[(int64_t)bh * g.n + lo] / total;
+  } else {  // V = 0: every choice gives the same (zero) product; uniform
+    lo = min(g.n - 1, (int)(u * (double)g.n));
+    p = 1.0 / (double)g.n;
   }
   a.vsamp[t] = lo;
-  a.vlogw[t] = (float)(log((double)total) - log((double)g.m) - log((double)a.vq[(int64_t)bh * g.n + lo]));
+  a.vlogw[t] = (float)(-log((double)g.m * p));
 }
 
 // log of the unmasked row sum of the rows T_j: one workgroup per head and kTauRows of them.

@@ -442,8 +442,6 @@ static void fill_alg2_layout(const Geometry& g, const ha_ws_layout& fwd, ha_alg2
   l->log_unmasked_t = take((size_t)g.BH * g.m * 4);
   l->log_tau = take((size_t)g.BH * 4);
   l->vnorm_w = take(rows * 8);
-  l->vnorm_max = take((size_t)g.BH * 8);
-  l->vnorm_q = take(rows * 4);
   l->vnorm_prefix = take(rows * 8);
   l->vnorm_samples = take((size_t)g.BH * g.m * 4);
   l->vnorm_logw = take((size_t)g.BH * g.m * 4);
@@ -838,9 +836,7 @@ int hyperattn_forward_alg2(const void* Q, const void* K, const void* V, void* ou
   a.log_unm_t = (float*)(base + al.log_unmasked_t);
   a.log_tau = (float*)(base + al.log_tau);
   a.vw = (double*)(base + al.vnorm_w);
-  a.vmax = (unsigned long long*)(base + al.vnorm_max);
-  a.vq = (uint32_t*)(base + al.vnorm_q);
-  a.vprefix = (unsigned long long*)(base + al.vnorm_prefix);
+  a.vprefix = (double*)(base + al.vnorm_prefix);
   a.vsamp = (int32_t*)(base + al.vnorm_samples);
   a.vlogw = (float*)(base + al.vnorm_logw);
   a.log_unm_parts = (float*)(base + al.log_unmasked_parts);
