@@ -56,7 +56,8 @@ typedef enum {
   HA_ERR_SHAPE = -3,     /* shape or parameters outside what is supported (see each call) */
   HA_ERR_WORKSPACE = -4, /* workspace too small or not 256-byte aligned */
   HA_ERR_LAUNCH = -5,    /* the HIP runtime refused a launch (hipGetLastError) */
-  HA_ERR_ALIGN = -6      /* a tensor does not start at a 16-byte boundary, or a float / index array at a 4-byte one */
+  HA_ERR_ALIGN = -6,     /* a tensor does not start at a 16-byte boundary, or a float / index array at a 4-byte one */
+  HA_ERR_STATIC_LIMIT = -7 /* hyperattn_forward_static: the problem needs more than ha_static_scratch_bytes() of scratch */
 } ha_status;
 
 /* [B, H, n, d]; d must be 64 or 128; n <= 2^22; B*H <= 2^20. */
@@ -114,6 +115,24 @@ size_t ha_workspace_bytes(const ha_shape* shape, const ha_params* params);
 int hyperattn_forward(const void* Q, const void* K, const void* V, void* out, float* lse,
                       const ha_shape* shape, const ha_params* params,
                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* For callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): hyperattn_forward with the workspace taken from an array built
+ * into the library (device memory of the code object, ha_static_scratch_bytes()
+ * = 32 MiB per GPU, held until the process ends).  Same kernels, same results,
+ * bit for bit, as hyperattn_forward.  The call allocates and frees nothing; the
+ * array's device address is looked up once per device on the first call there.
+ * Problems whose ha_workspace_bytes() exceeds the array return
+ * HA_ERR_STATIC_LIMIT before anything is enqueued.  All calls on one GPU share
+ * the one array: calls that overlap in time on one GPU (different streams or
+ * host threads) race and must be serialised by the caller.  Nothing is kept in
+ * the array between calls. */
+int hyperattn_forward_static(const void* Q, const void* K, const void* V, void* out, float* lse,
+                             const ha_shape* shape, const ha_params* params, void* stream);
+
+/* Host only.  Size in bytes of the built-in array hyperattn_forward_static uses. */
+size_t ha_static_scratch_bytes(void);
 
 /* Same, with the random draws supplied by the caller: R_dev is float [d][r]
  * (NULL = derive from the seed); samples_dev is int32 [total_nodes][m] in heap

@@ -61,6 +61,8 @@ _SIGNATURES = {
     "ha_workspace_layout": (c_int, [POINTER(HaShape), POINTER(HaParams), POINTER(HaWsLayout)]),
     "ha_workspace_bytes": (c_size_t, [POINTER(HaShape), POINTER(HaParams)]),
     "hyperattn_forward": (c_int, [c_void_p] * 5 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_size_t, c_void_p]),
+    "hyperattn_forward_static": (c_int, [c_void_p] * 5 + [POINTER(HaShape), POINTER(HaParams), c_void_p]),
+    "ha_static_scratch_bytes": (c_size_t, []),
     "hyperattn_forward_ex": (c_int, [c_void_p] * 5 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_void_p,
                                                      c_void_p, c_size_t, c_void_p]),
     "hyperattn_forward_timed": (c_int, [c_void_p] * 5 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_size_t,
@@ -227,6 +229,22 @@ def hyperattn_forward(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0, R=None
                                         None if samples is None else _dev(samples, "samples"),
                                         workspace.data_ptr(), workspace.numel(), _stream(stream))
     _check(st, "hyperattn_forward")
+    return out, lse
+
+
+def ha_static_scratch_bytes() -> int:
+    return int(lib().ha_static_scratch_bytes())
+
+
+def hyperattn_forward_static(Q, K, V, out, lse, b, m, r, causal=False, n_min=4096, seed=0, stream=None):
+    """hyperattn_forward on the library's built-in scratch array: the call
+    allocates nothing, so the caller passes out and lse."""
+    B, H, n, d = Q.shape
+    shape = make_shape(B, H, n, d, _dtype_code(Q))
+    params = make_params(b, m, r, causal, n_min, seed)
+    st = lib().hyperattn_forward_static(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"), _dev(lse, "lse"),
+                                        ctypes.byref(shape), ctypes.byref(params), _stream(stream))
+    _check(st, "hyperattn_forward_static")
     return out, lse
 
 

@@ -137,6 +137,35 @@ static uint16_t projection_bits(uint64_t seed, int c, int k) {
 
 static bool use_mfma(const Geometry& g) { return g.dtype == HA_BF16; }
 
+// ---------------------------------------------------------------------------
+// Built-in scratch of hyperattn_forward_static: a fixed device array that takes
+// the place of the caller's workspace, for callers that may not allocate.  Every
+// GPU the library runs on holds its own copy until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; the device
+// address it returns (per device) is what kernels and copies get.
+// ---------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_addr[kMaxDevices];
+
+// Device address of `scratch` on the current device (looked up once per device).
+static int static_scratch(void** addr) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HA_ERR_LAUNCH;
+  void* p = g_scratch_addr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return HA_ERR_LAUNCH;
+    }
+    g_scratch_addr[dev].store(p, std::memory_order_release);
+  }
+  *addr = p;
+  return HA_OK;
+}
+
 static int run_attention(const AttnArgs& a, int mode, hipStream_t st) {
   return use_mfma(a.g) ? launch_attn_mfma(a, mode, st) : launch_attn_generic(a, mode, st);
 }
@@ -479,6 +508,25 @@ size_t ha_workspace_bytes(const ha_shape* shape, const ha_params* params) {
 int hyperattn_forward(const void* Q, const void* K, const void* V, void* out, float* lse, const ha_shape* shape,
                       const ha_params* params, void* workspace, size_t workspace_bytes, void* stream) {
   return forward_impl(Q, K, V, out, lse, shape, params, nullptr, nullptr, workspace, workspace_bytes, stream);
+}
+
+size_t ha_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int hyperattn_forward_static(const void* Q, const void* K, const void* V, void* out, float* lse,
+                             const ha_shape* shape, const ha_params* params, void* stream) {
+  Geometry g;
+  const int rc = make_geometry(shape, params, &g);
+  if (rc != HA_OK) return rc;
+  ha_ws_layout lay;
+  fill_layout(g, &lay);
+  if (lay.total_bytes > kStaticScratchBytes) return HA_ERR_STATIC_LIMIT;
+  if (g.BH == 0 || g.n == 0) return HA_OK;
+  void* ws = nullptr;
+  const int rs = static_scratch(&ws);
+  if (rs != HA_OK) return rs;
+  // every region the kernels read is written earlier in the same call, so
+  // nothing left over from the previous call has to be cleared
+  return forward_impl(Q, K, V, out, lse, shape, params, nullptr, nullptr, ws, kStaticScratchBytes, stream);
 }
 
 int hyperattn_forward_ex(const void* Q, const void* K, const void* V, void* out, float* lse,
@@ -855,6 +903,9 @@ const char* ha_strerror(int status) {
     case HA_ERR_SHAPE: return "unsupported shape or parameters";
     case HA_ERR_WORKSPACE: return "workspace too small or misaligned";
     case HA_ERR_LAUNCH: return "HIP launch failed";
+    case HA_ERR_STATIC_LIMIT:
+      return "the problem needs more scratch than the built-in array holds (ha_static_scratch_bytes): call "
+             "hyperattn_forward with a workspace";
     case HA_ERR_ALIGN: return "a tensor is not 16-byte aligned (or an index / float array not 4-byte aligned)";
     default: return "unknown status";
   }
