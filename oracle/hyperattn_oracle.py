@@ -40,6 +40,11 @@ algorithm's steps in the paper's order and notation:
   hyperattn_backward   the forward's vector-Jacobian product (Section 4.2 times
                        forward + backward), random draws held fixed, written
                        out part by part in the forward's structure
+  attention_matrix, alpha, kappa, spectral_error
+                       the quantities the guarantees are stated in, from the dense
+                       matrices: D^-1 A; Lemma 1's alpha = n max_j |D^-1 A e_j|^2
+                       and kappa = max / min unmasked row sum; the epsilon of
+                       Eq. (1), |Att~ - Att|_op / (|D^-1 A|_op |V|_op)
 
 Pins (tests/test_oracle_pins.py): brute-force equivalence in the degenerate
 cases (one block and no samples; causal base case; every key sampled exactly
@@ -348,11 +353,13 @@ def hyperattn_forward(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0,
 # with cotangents (dO, dL):  P = A / den,  dV = P^T dO,
 #   dS = P . (dO V^T - <dO, O>) + P dL,  dQ = dS K,  dK = dS^T Q.
 # --------------------------------------------------------------------------
-def _softmax_part_backward(Qs, Ks, Vs, S_mask, O, L, dO, dL):
+def _softmax_part_backward(Qs, Ks, Vs, S_mask, O, L, dO, dL, absolute=False):
     """Cotangents of one part.  Qs [a,d], Ks, Vs [c,*]; S_mask [a,c] boolean
     (True = entry present); O, L the part's outputs (L without additive
     constants matters only through P, which is recomputed here); returns
-    (dQs, dKs, dVs)."""
+    (dQs, dKs, dVs).  absolute: the bound described at hyperattn_backward; Vs and
+    dO are then non-negative and dL carries, per row, this part's share of
+    <|dO_i|, sum_j P_ij |v_j|> of the whole row."""
     S = Qs @ Ks.T
     S = np.where(S_mask, S, -np.inf)
     mx = S.max(axis=1, keepdims=True)
@@ -364,27 +371,33 @@ def _softmax_part_backward(Qs, Ks, Vs, S_mask, O, L, dO, dL):
     dP = dO @ Vs.T
     delta = (dO * O).sum(axis=1, keepdims=True)
     dLc = np.where(live, dL, 0.0)[:, None]
+    if absolute:
+        dS = P * (dP + dLc)
+        return dS @ np.abs(Ks), dS.T @ np.abs(Qs), P.T @ dO
     dS = P * (dP - delta + dLc)
     return dS @ Ks, dS.T @ Qs, P.T @ dO
 
 
-def _merge_backward(O1, L1, O2, L2, O, L, dO, dL):
+def _merge_backward(O1, L1, O2, L2, O, L, dO, dL, absolute=False):
     """Cotangents of merge_parts: returns (dO1, dL1, dO2, dL2)."""
     with np.errstate(invalid="ignore"):
         w1 = np.where(np.isfinite(L1), np.exp(L1 - L), 0.0)
         w2 = np.where(np.isfinite(L2), np.exp(L2 - L), 0.0)
+    if absolute:   # a part's weights are w times the row's final ones: everything scales by w
+        return w1[:, None] * dO, w1 * dL, w2[:, None] * dO, w2 * dL
     g = (dO * O).sum(axis=1)
     dL1 = w1 * (dL + (dO * O1).sum(axis=1) - g)
     dL2 = w2 * (dL + (dO * O2).sum(axis=1) - g)
     return w1[:, None] * dO, dL1, w2[:, None] * dO, dL2
 
 
-def node_backward(Qn, Kn, Vn, codes_q, codes_k, b, samples, dO, dL):
+def node_backward(Qn, Kn, Vn, codes_q, codes_k, b, samples, dO, dL, absolute=False):
     """Backward of node_forward; returns (dQn, dKn, dVn)."""
     s = Qn.shape[0]
     parts = {}
     O, L = node_forward(Qn, Kn, Vn, codes_q, codes_k, b, samples, parts)
-    dO_b, dL_b, dO_r, dL_r = _merge_backward(parts["O_b"], parts["L_b"], parts["O_r"], parts["L_r"], O, L, dO, dL)
+    dO_b, dL_b, dO_r, dL_r = _merge_backward(parts["O_b"], parts["L_b"], parts["O_r"], parts["L_r"], O, L, dO, dL,
+                                             absolute)
     dQ = np.zeros_like(Qn)
     dK = np.zeros_like(Kn)
     dV = np.zeros_like(Vn)
@@ -393,59 +406,74 @@ def node_backward(Qn, Kn, Vn, codes_q, codes_k, b, samples, dO, dL):
         I = perm_q[t * b:(t + 1) * b]
         J = perm_k[t * b:(t + 1) * b]
         full = np.ones((len(I), len(J)), dtype=bool)
-        gq, gk, gv = _softmax_part_backward(Qn[I], Kn[J], Vn[J], full, parts["O_b"][I], parts["L_b"][I], dO_b[I], dL_b[I])
+        gq, gk, gv = _softmax_part_backward(Qn[I], Kn[J], Vn[J], full, parts["O_b"][I], parts["L_b"][I], dO_b[I],
+                                            dL_b[I], absolute)
         dQ[I] += gq
         dK[J] += gk
         dV[J] += gv
     samples = np.asarray(samples, dtype=np.int64)
     if len(samples) > 0:                          # estimate: the same index set for every row
         keep = (pos_q[:, None] // b) != (pos_k[samples][None, :] // b)
-        gq, gk, gv = _softmax_part_backward(Qn, Kn[samples], Vn[samples], keep, parts["O_r"], parts["L_r"], dO_r, dL_r)
+        gq, gk, gv = _softmax_part_backward(Qn, Kn[samples], Vn[samples], keep, parts["O_r"], parts["L_r"], dO_r, dL_r,
+                                            absolute)
         dQ += gq
         np.add.at(dK, samples, gk)                # an index may be drawn more than once
         np.add.at(dV, samples, gv)
     return dQ, dK, dV
 
 
-def causal_backward(Q, K, V, codes_q, codes_k, b, n_min, sample_fn, dO, dL, level=0, node=0):
+def causal_backward(Q, K, V, codes_q, codes_k, b, n_min, sample_fn, dO, dL, level=0, node=0, absolute=False):
     """Backward of causal_forward; returns (dQ, dK, dV)."""
     n = Q.shape[0]
     if n <= n_min:
         O, L = exact_attention(Q, K, V, causal=True)
         i = np.arange(n)[:, None]
         j = np.arange(n)[None, :]
-        return _softmax_part_backward(Q, K, V, i >= j, O, L, dO, dL)
+        return _softmax_part_backward(Q, K, V, i >= j, O, L, dO, dL, absolute)
     h = n // 2
     O22, L22 = causal_forward(Q[h:], K[h:], V[h:], codes_q[h:], codes_k[h:], b, n_min, sample_fn, level + 1, 2 * node + 1)
     samples = sample_fn(level, node, h)
     O21, L21 = node_forward(Q[h:], K[:h], V[:h], codes_q[h:], codes_k[:h], b, samples)
     O2, L2 = merge_parts(O21, L21, O22, L22)
-    dO21, dL21, dO22, dL22 = _merge_backward(O21, L21, O22, L22, O2, L2, dO[h:], dL[h:])
+    dO21, dL21, dO22, dL22 = _merge_backward(O21, L21, O22, L22, O2, L2, dO[h:], dL[h:], absolute)
     dQ = np.zeros_like(Q)
     dK = np.zeros_like(K)
     dV = np.zeros_like(V)
-    g = causal_backward(Q[:h], K[:h], V[:h], codes_q[:h], codes_k[:h], b, n_min, sample_fn, dO[:h], dL[:h], level + 1, 2 * node)
+    g = causal_backward(Q[:h], K[:h], V[:h], codes_q[:h], codes_k[:h], b, n_min, sample_fn, dO[:h], dL[:h], level + 1,
+                        2 * node, absolute)
     dQ[:h] += g[0]
     dK[:h] += g[1]
     dV[:h] += g[2]
-    g = causal_backward(Q[h:], K[h:], V[h:], codes_q[h:], codes_k[h:], b, n_min, sample_fn, dO22, dL22, level + 1, 2 * node + 1)
+    g = causal_backward(Q[h:], K[h:], V[h:], codes_q[h:], codes_k[h:], b, n_min, sample_fn, dO22, dL22, level + 1,
+                        2 * node + 1, absolute)
     dQ[h:] += g[0]
     dK[h:] += g[1]
     dV[h:] += g[2]
-    g = node_backward(Q[h:], K[:h], V[:h], codes_q[h:], codes_k[:h], b, samples, dO21, dL21)
+    g = node_backward(Q[h:], K[:h], V[:h], codes_q[h:], codes_k[:h], b, samples, dO21, dL21, absolute)
     dQ[h:] += g[0]
     dK[:h] += g[1]
     dV[:h] += g[2]
     return dQ, dK, dV
 
 
-def hyperattn_backward(Q, K, V, dO, b, m, r, causal=False, n_min=4096, seed=0, R=None, sample_fn=None, flip=None):
+def hyperattn_backward(Q, K, V, dO, b, m, r, causal=False, n_min=4096, seed=0, R=None, sample_fn=None, flip=None,
+                       absolute=False):
     """Gradients (dQ, dK, dV) of sum(out * dO) for out = hyperattn_forward(Q, K, V, ...)[0],
-    all [B, H, n, d] in fp64; arguments as in hyperattn_forward."""
+    all [B, H, n, d] in fp64; arguments as in hyperattn_forward.
+
+    absolute=True returns instead, element by element, the sum of the magnitudes of the terms
+    a gradient element consists of.  With P_ij the final weight of key j in row i (all parts
+    under their shared normaliser) every pair contributes dV_j += P_ij dO_i,
+    dS_ij = P_ij (<dO_i, v_j> - <dO_i, O_i>), dQ_i += dS_ij k_j, dK_j += dS_ij q_i; the bound is
+    the same with |dO|, |v|, |k|, |q|, with sum_j P_ij |v_j| for O_i and a sum for the
+    difference.  An evaluation whose operands carry a relative rounding error eps is off by at
+    most eps times this bound; the tests scale their tolerance for the gradients by it."""
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
     dO = np.asarray(dO, dtype=np.float64)
+    if absolute:
+        V, dO = np.abs(V), np.abs(dO)
     B, H, n, d = Q.shape
     if R is None:
         R = make_projection(seed, d, r)
@@ -462,10 +490,16 @@ def hyperattn_backward(Q, K, V, dO, b, m, r, causal=False, n_min=4096, seed=0, R
                     bits[t][row, kk] = ~bits[t][row, kk]
         cq, ck = (codes_from_bits(bits[t], r) for t in range(2))
         zero = np.zeros(n)
+        if absolute:   # v = |V|, g = |dO|: the forward on |V| gives sum_j P_ij |v_j|
+            if causal:
+                o_abs, _ = causal_forward(q, k, v, cq, ck, b, n_min, sample_fn)
+            else:
+                o_abs, _ = node_forward(q, k, v, cq, ck, b, sample_fn(0, 0, n))
+            zero = (g * o_abs).sum(axis=1)
         if causal:
-            gq, gk, gv = causal_backward(q, k, v, cq, ck, b, n_min, sample_fn, g, zero)
+            gq, gk, gv = causal_backward(q, k, v, cq, ck, b, n_min, sample_fn, g, zero, absolute=absolute)
         else:
-            gq, gk, gv = node_backward(q, k, v, cq, ck, b, sample_fn(0, 0, n), g, zero)
+            gq, gk, gv = node_backward(q, k, v, cq, ck, b, sample_fn(0, 0, n), g, zero, absolute)
         dQ.reshape(B * H, n, -1)[bh] = gq
         dK.reshape(B * H, n, -1)[bh] = gk
         dV.reshape(B * H, n, -1)[bh] = gv
@@ -600,3 +634,42 @@ def hyperattn_forward_alg2(Q, K, V, b, m, r, seed=0, cap_scale=0.0, kappa=0.0, v
         lse.reshape(B * H, n)[bh] = l
         taus[bh] = t
     return out, lse, taus
+
+
+# --------------------------------------------------------------------------
+# The quantities the paper's guarantees are stated in (Section 1.1 Eq. (1),
+# Lemma 1, Section 4.3), from the dense matrices (small n only).
+# --------------------------------------------------------------------------
+def attention_matrix(Q, K, causal=False) -> np.ndarray:
+    """D^-1 A (causal: D_C^-1 (M^C . A)) as a dense n x n matrix."""
+    n = np.asarray(Q).shape[0]
+    return exact_attention(Q, K, np.eye(n), causal)[0]
+
+
+def alpha(Q, K) -> float:
+    """Lemma 1: alpha = n * max_j |D^-1 A e_j|_2^2, the largest squared column norm of the softmax matrix times n."""
+    P = attention_matrix(Q, K)
+    return float(P.shape[0] * (P ** 2).sum(axis=0).max())
+
+
+def kappa(Q, K, codes_q, codes_k, b) -> float:
+    """Lemma 1: ratio of the largest to the smallest unmasked row sum <1 - M^H_i, A_i>, with M^H of Algorithm 1."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    _, pos_q = sort_lsh(codes_q)
+    _, pos_k = sort_lsh(codes_k)
+    S = Q @ K.T
+    ref = S.max()
+    outside = (pos_q[:, None] // b) != (pos_k[None, :] // b)          # 1 - M^H
+    unmasked = np.where(outside, np.exp(S - ref), 0.0).sum(axis=1)
+    return float(unmasked.max() / unmasked.min())
+
+
+def spectral_error(att_approx, Q, K, V, causal=False) -> float:
+    """The epsilon Eq. (1) is satisfied with: |Att~ - Att|_op / (|D^-1 A|_op |V|_op), operator norms
+    being largest singular values."""
+    V = np.asarray(V, dtype=np.float64)
+    P = attention_matrix(Q, K, causal)
+    err = np.asarray(att_approx, dtype=np.float64) - P @ V
+    top = lambda M: float(np.linalg.svd(M, compute_uv=False)[0])
+    return top(err) / (top(P) * top(V))

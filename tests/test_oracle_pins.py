@@ -405,6 +405,97 @@ def test_backward_invariants_from_row_stochasticity():
     np.testing.assert_allclose(dK2, -2.0 * dK, rtol=1e-12, atol=1e-12)
 
 
+def test_backward_absolute_bound_is_what_its_definition_says():
+    """absolute=True: the dense closed form where the method is exact attention; a bound on
+    |gradient| everywhere; blind to the signs of V and dO; homogeneous in dO; and large enough
+    that perturbing every softmax weight by a relative eps moves no element by more than eps * bound."""
+    rng = np.random.default_rng(5)
+    n, d = 48, 6
+    Q, K, V, G = (rng.standard_normal((1, 1, n, d)) * 0.8 for _ in range(4))
+    q, k, v, g = Q[0, 0], K[0, 0], V[0, 0], G[0, 0]
+    bq, bk, bv = (x[0, 0] for x in orc.hyperattn_backward(Q, K, V, G, b=n, m=0, r=2, absolute=True))
+    S = q @ k.T
+    P = np.exp(S - S.max(axis=1, keepdims=True))
+    P /= P.sum(axis=1, keepdims=True)
+    absO = P @ np.abs(v)
+    dS = P * (np.abs(g) @ np.abs(v).T + (np.abs(g) * absO).sum(axis=1, keepdims=True))
+    np.testing.assert_allclose(bq, dS @ np.abs(k), rtol=1e-12)
+    np.testing.assert_allclose(bk, dS.T @ np.abs(q), rtol=1e-12)
+    np.testing.assert_allclose(bv, P.T @ np.abs(g), rtol=1e-12)
+    for kw in (dict(b=8, m=10, r=3, causal=False, seed=4), dict(b=4, m=5, r=3, causal=True, n_min=12, seed=4)):
+        grads = orc.hyperattn_backward(Q, K, V, G, **kw)
+        bounds = orc.hyperattn_backward(Q, K, V, G, absolute=True, **kw)
+        for gr, bd in zip(grads, bounds):
+            assert (bd >= 0).all() and (np.abs(gr) <= bd * (1 + 1e-12) + 1e-300).all()
+        flipped = orc.hyperattn_backward(Q, K, -V, G * rng.choice([-1.0, 1.0], size=G.shape), absolute=True, **kw)
+        scaled = orc.hyperattn_backward(Q, K, V, -3.0 * G, absolute=True, **kw)
+        for bd, fl, sc in zip(bounds, flipped, scaled):
+            np.testing.assert_allclose(fl, bd, rtol=1e-12)
+            np.testing.assert_allclose(sc, 3.0 * bd, rtol=1e-12)
+    # weights perturbed by a relative eps (what rounding them to fewer bits does), dense exact attention
+    eps = 1e-3
+    Pp = P * (1.0 + eps * rng.uniform(-1, 1, size=P.shape))
+    dP = g @ v.T
+    dSp = Pp * (dP - ((Pp @ v) * g).sum(axis=1, keepdims=True))
+    exact = orc.hyperattn_backward(Q, K, V, G, b=n, m=0, r=2)
+    for got, ref, bd in zip((dSp @ k, dSp.T @ q, Pp.T @ g), exact, (bq, bk, bv)):
+        assert (np.abs(got - ref[0, 0]) <= 2.0 * eps * bd).all()
+
+
+# --------------------------------------------------------------------------
+# alpha, kappa and the epsilon of Eq. (1): closed forms
+# --------------------------------------------------------------------------
+def test_alpha_kappa_and_spectral_error_closed_forms():
+    rng = np.random.default_rng(12)
+    n, d, b = 64, 8, 8
+    K = rng.standard_normal((n, d))
+    V = rng.standard_normal((n, d))
+    Z = np.zeros((n, d))
+    codes = rng.integers(0, 16, size=n)
+    # Q = 0: uniform attention, every entry of D^-1 A is 1/n, so alpha = n * n * (1/n)^2 = 1, the matrix
+    # is the rank-one projector (1/n) 1 1^T with norm 1, and every unmasked row sum is n - b: kappa = 1
+    np.testing.assert_allclose(orc.attention_matrix(Z, K), 1.0 / n, rtol=1e-14)
+    assert abs(orc.alpha(Z, K) - 1.0) < 1e-12
+    assert abs(orc.kappa(Z, K, codes, codes[::-1].copy(), b) - 1.0) < 1e-12
+    # one-hot attention (row i attends to key pi(i) only): D^-1 A is a permutation matrix, alpha = n
+    pi = rng.permutation(n)
+    E = np.eye(n)
+    assert abs(orc.alpha(50.0 * E[pi], E) - n) < 1e-6
+    # two keys share all the weight of every row equally: column norms^2 = n / 4 each, alpha = n * n / 4
+    Kt = np.zeros((n, 2))
+    Kt[3, 0] = Kt[9, 0] = 40.0
+    Qt = np.zeros((n, 2))
+    Qt[:, 0] = 1.0
+    assert abs(orc.alpha(Qt, Kt) - n * n / 4.0) < 1e-6 * n * n
+    # kappa on an instance with known row sums: scores 0 except one unmasked entry per row of size log(c_i)
+    Kk = np.zeros((n, 1))
+    Kk[0, 0] = 1.0
+    cq = np.arange(n) // b                      # sorted already: row i in block i // b, key 0 in block 0
+    c = rng.uniform(1.0, 9.0, size=n)
+    Qk = np.log(c)[:, None]                     # A_i0 = c_i, all other entries 1
+    sums = np.where(np.arange(n) < b, n - b, n - b - 1 + c)       # rows of block 0 have key 0 masked
+    assert abs(orc.kappa(Qk, Kk, cq, cq, b) - sums.max() / sums.min()) < 1e-12
+    # Eq. (1): zero for the exact product; for uniform attention (norm 1), orthonormal V (norm 1) and a
+    # rank-one perturbation c u w^T with unit u, w the achieved epsilon is c
+    Q = rng.standard_normal((n, d)) * 0.5
+    att = orc.exact_attention(Q, K, V)[0]
+    assert orc.spectral_error(att, Q, K, V) < 1e-14
+    Vo = np.linalg.qr(rng.standard_normal((n, d)))[0]
+    u = rng.standard_normal(n)
+    w = rng.standard_normal(d)
+    pert = 0.37 * np.outer(u / np.linalg.norm(u), w / np.linalg.norm(w))
+    exact_u = orc.exact_attention(Z, K, Vo)[0]
+    assert abs(orc.spectral_error(exact_u + pert, Z, K, Vo) - 0.37) < 1e-12
+    # causal form: D_C^-1 (M^C . A) is lower triangular with unit row sums
+    Pc = orc.attention_matrix(Q, K, causal=True)
+    assert np.allclose(np.triu(Pc, 1), 0.0) and np.allclose(Pc.sum(axis=1), 1.0)
+    assert orc.spectral_error(orc.exact_attention(Q, K, V, causal=True)[0], Q, K, V, causal=True) < 1e-14
+    # identity sampling makes the method exact: epsilon = 0 (up to rounding)
+    out, _ = orc.hyperattn_forward(Q[None, None], K[None, None], V[None, None], b=b, m=n, r=3,
+                                   sample_fn=lambda level, node, s: np.arange(s))
+    assert orc.spectral_error(out[0, 0], Q, K, V) < 1e-13
+
+
 # --------------------------------------------------------------------------
 # Frozen record of the oracle on tiny problems (tests/golden/, written by
 # tests/golden/make_golden.py from the oracle alone): guards against an
