@@ -81,6 +81,16 @@ def kappa_of(torch, lse_exact, lse_block):
     return kappa, torch.exp(gap[0]).mean(dim=1)
 
 
+def spectral_error_of(torch, ha, Q, K, V, out_approx, out_exact, lse_exact, causal, iters):
+    """The epsilon of Eq. (1) per head of batch 0: ||Att~ - Att||_op / (||D^-1 A||_op ||V||_op).
+    Returns (epsilon, ||Att~ - Att||_op, ||D^-1 A||_op, ||V||_op)."""
+    err = out_approx.float() - out_exact.float()
+    err_op = op_norm_tall(torch, err[0])
+    v_op = op_norm_tall(torch, V[0].float())
+    p_op = softmax_op_norm(torch, ha, Q, K, lse_exact, causal, iters)
+    return err_op / (p_op * v_op), err_op, p_op, v_op
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="cfg2_n32k", choices=sorted(synth_inputs.CONFIGS))
@@ -106,13 +116,9 @@ def main():
     out_h, lse_h = ha.hyperattn_forward(Q, K, V, cfg["b"], cfg["m"], cfg["r"], **kw)
     out_e, lse_e = ha.exact_attn_forward(Q, K, V, causal=causal)
     err = out_h.float() - out_e.float()
-    err_op = op_norm_tall(torch, err[0])                      # [H]
-    v_op = op_norm_tall(torch, V[0].float())
     rel_fro = (err[0].double().flatten(1).norm(dim=1) / out_e[0].double().flatten(1).norm(dim=1))
     max_abs = err[0].abs().flatten(1).max(dim=1).values
-
-    p_op = softmax_op_norm(torch, ha, Q, K, lse_e, causal, args.iters)
-    spectral = err_op / (p_op * v_op)
+    spectral, err_op, p_op, v_op = spectral_error_of(torch, ha, Q, K, V, out_h, out_e, lse_e, causal, args.iters)
 
     result = {"workload": args.workload, "heads": H, "n": n, "d": d, "causal": causal,
               "b": cfg["b"], "m": cfg["m"], "r": cfg["r"],

@@ -137,7 +137,11 @@ size_t ha_static_scratch_bytes(void);
 /* Same, with the random draws supplied by the caller: R_dev is float [d][r]
  * (NULL = derive from the seed); samples_dev is int32 [total_nodes][m] in heap
  * order, node-local key indices in [0, s) (NULL = derive from the seed).  Both
- * are device memory and are copied into the workspace on `stream`. */
+ * are device memory and are copied into the workspace on `stream`.  The call
+ * never reads device memory on the host, so it cannot reject an index outside
+ * [0, s): such an index is clamped into the node by the copying kernel (no
+ * access outside the node's keys can result); validate on the host beforehand
+ * if the indices come from elsewhere (the Python binding does). */
 int hyperattn_forward_ex(const void* Q, const void* K, const void* V, void* out, float* lse,
                          const ha_shape* shape, const ha_params* params,
                          const float* R_dev, const int32_t* samples_dev,
@@ -177,7 +181,11 @@ int ha_make_samples(uint64_t seed, int32_t level, int32_t node, int32_t n_keys, 
 
 /* sortLSH hashing (Definition 1; Algorithm 1 "hash rows of Q, K"): codes[i] =
  * Gray-sequence position of the sign word of X[i,:] R.  X: [rows][d] of dtype,
- * R_dev: float [d][r], codes: uint8 [rows].  Projections accumulate in fp64. */
+ * R_dev: float [d][r], codes: uint8 [rows].  The codes equal those of an fp64
+ * evaluation of the projections: bf16 rows are projected on the matrix cores in
+ * fp32 together with a bound on the accumulation error, and every row with a
+ * projection inside that bound is recomputed in fp64 (exact products); fp32 rows
+ * are accumulated in fp64 throughout. */
 int ha_lsh_hash(const void* X, uint8_t* codes, int64_t rows, int32_t d, int32_t dtype,
                 const float* R_dev, int32_t r, void* stream);
 

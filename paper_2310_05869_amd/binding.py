@@ -188,6 +188,59 @@ def _stream(stream):
     return (torch.cuda.current_stream() if stream is None else stream).cuda_stream
 
 
+def _expect(t, name, shape, dtype, like):
+    """The kernels take sizes from Q alone: every other tensor must have the shape, dtype and device they assume."""
+    if t is None:
+        return
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} has dtype {t.dtype}, expected {dtype}")
+    if t.device != like.device:
+        raise ValueError(f"{name} is on {t.device}, expected {like.device}")
+
+
+def _expect_qkv(Q, **others):
+    """others: name=tensor pairs that must match Q in shape, dtype and device (None entries are skipped)."""
+    if Q.dim() != 4:
+        raise ValueError(f"Q has shape {tuple(Q.shape)}, expected [B, H, n, d]")
+    for name, t in others.items():
+        _expect(t, name, Q.shape, Q.dtype, Q)
+
+
+def _expect_f32(Q, shape, **others):
+    torch = _torch()
+    for name, t in others.items():
+        _expect(t, name, shape, torch.float32, Q)
+
+
+def _on_stream(stream, *tensors):
+    """Memory this call allocated itself and lets go of on return must not be handed out again by the
+    caching allocator while kernels on a stream other than the current one still use it."""
+    torch = _torch()
+    if stream is not None and stream != torch.cuda.current_stream():
+        for t in tensors:
+            if t is not None:
+                t.record_stream(stream)
+
+
+def _check_samples(samples, shape: HaShape, params: HaParams, Q):
+    """int32 [total_nodes, m], every index inside its node (the C call can only clamp: it never reads
+    device memory on the host)."""
+    torch = _torch()
+    lay = ha_workspace_layout(shape, params)
+    _expect(samples, "samples", (lay.total_nodes, params.m), torch.int32, Q)
+    if samples.numel() == 0:
+        return
+    if params.causal:
+        level = torch.floor(torch.log2(torch.arange(1, lay.total_nodes + 1, device=samples.device).float())).long()
+        size = (shape.n >> (level + 1)).to(torch.int32)[:, None]
+    else:
+        size = shape.n
+    if bool((samples < 0).any()) or bool((samples >= size).any()):
+        raise HyperAttnError(-3, "hyperattn_forward: a sample index lies outside its node")
+
+
 def alloc_workspace(shape: HaShape, params: HaParams, device="cuda"):
     torch = _torch()
     nbytes = ha_workspace_bytes(shape, params)
@@ -205,15 +258,23 @@ def hyperattn_forward(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0, R=None
     [B, H, n, d]), if given, receives the output before its rounding to bf16
     (hyperattn_forward_train): pass it on to hyperattn_backward."""
     torch = _torch()
+    _expect_qkv(Q, K=K, V=V, out=out)
     B, H, n, d = Q.shape
     shape = make_shape(B, H, n, d, _dtype_code(Q))
     params = make_params(b, m, r, causal, n_min, seed)
-    if workspace is None:
+    _expect_f32(Q, (B, H, n), lse=lse)
+    _expect_f32(Q, (B, H, n, d), out_f32=out_f32)
+    _expect_f32(Q, (d, r), R=R)
+    if samples is not None:
+        _check_samples(samples, shape, params, Q)
+    own_ws = workspace is None
+    if own_ws:
         workspace = alloc_workspace(shape, params, Q.device)
     if out is None:
         out = torch.empty_like(Q)
     if lse is None:
         lse = torch.empty((B, H, n), dtype=torch.float32, device=Q.device)
+    _on_stream(stream, workspace if own_ws else None)
     ptrs = [_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"), _dev(lse, "lse")]
     if out_f32 is not None:
         if R is not None or samples is not None:
@@ -239,6 +300,8 @@ def ha_static_scratch_bytes() -> int:
 def hyperattn_forward_static(Q, K, V, out, lse, b, m, r, causal=False, n_min=4096, seed=0, stream=None):
     """hyperattn_forward on the library's built-in scratch array: the call
     allocates nothing, so the caller passes out and lse."""
+    _expect_qkv(Q, K=K, V=V, out=out)
+    _expect_f32(Q, tuple(Q.shape[:3]), lse=lse)
     B, H, n, d = Q.shape
     shape = make_shape(B, H, n, d, _dtype_code(Q))
     params = make_params(b, m, r, causal, n_min, seed)
@@ -256,6 +319,8 @@ def hyperattn_forward_timed(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0, 
     """As hyperattn_forward, but waits for the result and also returns the
     per-stage milliseconds (dict keyed by STAGE_NAMES) from HIP events."""
     torch = _torch()
+    _expect_qkv(Q, K=K, V=V, out=out)
+    _expect_f32(Q, tuple(Q.shape[:3]), lse=lse)
     B, H, n, d = Q.shape
     shape = make_shape(B, H, n, d, _dtype_code(Q))
     params = make_params(b, m, r, causal, n_min, seed)
@@ -275,6 +340,9 @@ def hyperattn_forward_timed(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0, 
 
 def exact_attn_forward(Q, K, V, causal=False, out=None, lse=None, stream=None, out_f32=None):
     torch = _torch()
+    _expect_qkv(Q, K=K, V=V, out=out)
+    _expect_f32(Q, tuple(Q.shape[:3]), lse=lse)
+    _expect_f32(Q, tuple(Q.shape), out_f32=out_f32)
     B, H, n, d = Q.shape
     shape = make_shape(B, H, n, d, _dtype_code(Q))
     if out is None:
@@ -421,12 +489,17 @@ def alloc_backward_workspace(shape: HaShape, params: HaParams, device="cuda"):
 def _backward_call(timed, Q, K, V, out, lse, d_out, b, m, r, causal, n_min, seed, fwd_workspace, bwd_workspace,
                    grads, stream, out_f32=None):
     torch = _torch()
+    dQ, dK, dV = grads if grads is not None else (torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V))
+    _expect_qkv(Q, K=K, V=V, out=out, d_out=d_out, dQ=dQ, dK=dK, dV=dV)
+    _expect_f32(Q, tuple(Q.shape[:3]), lse=lse)
+    _expect_f32(Q, tuple(Q.shape), out_f32=out_f32)
     B, H, n, d = Q.shape
     shape = make_shape(B, H, n, d, _dtype_code(Q))
     params = make_params(b, m, r, causal, n_min, seed)
-    if bwd_workspace is None:
+    own_ws = bwd_workspace is None
+    if own_ws:
         bwd_workspace = alloc_backward_workspace(shape, params, Q.device)
-    dQ, dK, dV = grads if grads is not None else (torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V))
+    _on_stream(stream, bwd_workspace if own_ws else None)
     args = [_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"),
             None if out_f32 is None else _dev(out_f32, "out_f32"), _dev(lse, "lse"), _dev(d_out, "d_out"),
             _dev(dQ, "dQ"), _dev(dK, "dK"), _dev(dV, "dV"), ctypes.byref(shape), ctypes.byref(params),
@@ -463,12 +536,17 @@ def hyperattn_backward_timed(Q, K, V, out, lse, d_out, b, m, r, causal=False, n_
 
 def exact_attn_backward(Q, K, V, out, lse, d_out, causal=False, workspace=None, grads=None, stream=None, out_f32=None):
     torch = _torch()
+    dQ, dK, dV = grads if grads is not None else (torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V))
+    _expect_qkv(Q, K=K, V=V, out=out, d_out=d_out, dQ=dQ, dK=dK, dV=dV)
+    _expect_f32(Q, tuple(Q.shape[:3]), lse=lse)
+    _expect_f32(Q, tuple(Q.shape), out_f32=out_f32)
     B, H, n, d = Q.shape
     shape = make_shape(B, H, n, d, _dtype_code(Q))
-    if workspace is None:
+    own_ws = workspace is None
+    if own_ws:
         workspace = torch.empty(int(lib().exact_attn_backward_workspace_bytes(ctypes.byref(shape))), dtype=torch.uint8,
                                 device=Q.device)
-    dQ, dK, dV = grads if grads is not None else (torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V))
+    _on_stream(stream, workspace if own_ws else None)
     _check(lib().exact_attn_backward(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"),
                                      None if out_f32 is None else _dev(out_f32, "out_f32"), _dev(lse, "lse"),
                                      _dev(d_out, "d_out"), _dev(dQ, "dQ"), _dev(dK, "dK"), _dev(dV, "dV"),
@@ -490,6 +568,8 @@ def hyperattn_forward_alg2(Q, K, V, b, m, r, seed=0, cap_scale=0.0, kappa=0.0, v
     """Unmasked HyperAttention with Algorithm 2's caps and, optionally, Lemma 2's value
     sampling by squared row norm.  Returns (out, log d~, workspace)."""
     torch = _torch()
+    _expect_qkv(Q, K=K, V=V, out=out)
+    _expect_f32(Q, tuple(Q.shape[:3]), lse=lse)
     B, H, n, d = Q.shape
     shape = make_shape(B, H, n, d, _dtype_code(Q))
     params = make_params(b, m, r, False, 4096, seed)

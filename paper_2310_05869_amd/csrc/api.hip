@@ -331,7 +331,7 @@ static void fill_bwd_layout(const Geometry& g, ha_bwd_ws_layout* l) {
   l->total_bytes = off < 256 ? 256 : off;
 }
 
-// ev, when non-null, receives 9 events: start, after delta, dQ of the nodes, dQ of the base case,
+// ev, when non-null, receives 8 events: start, after delta, dQ of the nodes, dQ of the base case,
 // dK/dV of the block keys, of the sampled keys (with their reduction), of the base case, after the final sums.
 static int backward_impl(const void* Q, const void* K, const void* V, const void* out, const float* out_f32,
                          const float* lse, const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* sh,

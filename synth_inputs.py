@@ -109,3 +109,27 @@ def make_qkv(cfg: dict, seed=DATA_SEED, B=None, H=None, n=None):
     n = cfg["n"] if n is None else n
     gen = iid_qkv if cfg["law"] == "iid" else mixture_qkv
     return gen(B, H, n, cfg["d"], cfg["dtype"], seed)
+
+
+def device_qkv(cfg: dict, torch, generator, B=None, H=None):
+    """Q, K, V of a CONFIGS entry drawn on the GPU from the same law (torch's generator: not the
+    same numbers as the host generators above), in the configuration's dtype.  For heads that no
+    CPU reference is computed for."""
+    B = cfg["B"] if B is None else B
+    H = cfg["H"] if H is None else H
+    n, d = cfg["n"], cfg["d"]
+    dt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+    randn = lambda *shape: torch.randn(shape, generator=generator, device="cuda", dtype=torch.float32)
+    if cfg["law"] == "iid":
+        return [(randn(B, H, n, d) * d ** -0.25).to(dt).contiguous() for _ in range(3)]
+    centres, centre_sigma, within_sigma, zipf_s = 64, 2.0, 0.5, 1.1
+    C = centre_sigma * randn(B * H, centres, d)
+    pk = torch.arange(1, centres + 1, device="cuda", dtype=torch.float32) ** (-zipf_s)
+    out = []
+    for _ in range(2):
+        which = torch.multinomial((pk / pk.sum()).expand(B * H, centres), n, replacement=True, generator=generator)
+        rows = torch.gather(C, 1, which[:, :, None].expand(B * H, n, d))
+        rows += within_sigma * randn(B * H, n, d)
+        out.append(rows.view(B, H, n, d).to(dt).contiguous())
+    out.append(randn(B, H, n, d).to(dt).contiguous())
+    return out

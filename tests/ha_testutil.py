@@ -55,10 +55,21 @@ def out_tolerance(ref: np.ndarray, dtype: str, absv=None) -> np.ndarray:
 LSE_TOL = {"bf16": 1e-3, "fp32": 2e-5}
 
 
-def assert_close(got, ref, dtype, what, absv=None):
+def assert_close(got, ref, dtype, what, absv=None, max_plain_frac=0.0):
+    """Element-wise comparison.  Without `absv` the criterion is the plain one of out_tolerance().
+    With `absv` (bf16 only; the caller says in its docstring why the case needs it) an element may
+    also use the operand-rounding allowance 2^-8 sum_j p_j |v_j|; the number of elements that
+    fail the plain criterion is printed and must not exceed max_plain_frac of all elements."""
     err = np.abs(got - ref)
-    tol = out_tolerance(ref, dtype, absv)
-    bad = err > tol
+    plain = err > out_tolerance(ref, dtype)
+    if absv is None:
+        bad = plain
+    else:
+        bad = err > out_tolerance(ref, dtype, absv)
+        frac = plain.mean() if plain.size else 0.0
+        print(f"  {what}: {int(plain.sum())} of {plain.size} elements ({frac:.3%}) exceed the plain criterion "
+              f"(allowed {max_plain_frac:.3%}); worst excess {float((err - out_tolerance(ref, dtype)).max()):.2e}", flush=True)
+        assert frac <= max_plain_frac, f"{what}: {frac:.3%} of the elements need the operand-rounding allowance"
     assert not bad.any(), (f"{what}: {bad.sum()} of {bad.size} elements out of tolerance; "
                            f"max abs err {err.max():.3e} (|ref| there {np.abs(ref).ravel()[err.argmax()]:.3e})")
     return float(err.max())

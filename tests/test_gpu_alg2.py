@@ -3,9 +3,11 @@ oracle's dense evaluation: the rows of T bit-exact; the rows drawn by squared va
 (Lemma 2, inverse of the cumulative law in fp64 on both sides) equal except where the
 oracle's uniform lies within 1e-9 of a boundary of that law (counted, and replayed in the
 oracle like a projection too close to zero); log tau and log d~ within fp32 accuracy, outputs
-within the forward's tolerance (bf16: 2e-3 + half an ulp + 2^-8 sum_j w_j |v_j|, the
-weights being rounded to bf16 as matrix-core operands exactly as in the forward; that sum
-is the oracle run on |V|, which leaves every draw and weight as it is; fp32: 1e-5 + 1e-5 |ref|)."""
+within the forward's tolerance (bf16: 2e-3 + half an ulp; fp32: 1e-5 + 1e-5 |ref|).  Where
+fewer than 16 sampled rows carry a row's whole value product (Lemma 2 with a small m) the
+rounding of the weights to bf16 as matrix-core operands does not average out and an element
+may also use 2^-8 sum_j w_j |v_j| (the oracle run on |V| with the draws of V); the share of
+the elements that need it is printed and must stay below 0.5 %."""
 import numpy as np
 import pytest
 
@@ -85,10 +87,10 @@ def test_alg2_options_match_the_oracle(ha, torch, dtype, d, n, b, m, r, cap_scal
     np.testing.assert_allclose(views["log_tau"].cpu().numpy(), ref_tau, rtol=2e-5, atol=2e-5)
     np.testing.assert_allclose(to_host(lse), ref_lse, rtol=3e-5, atol=3e-5)
     absv = None
-    if dtype == "bf16":   # squared row norms, hence the draws, are those of V
+    if dtype == "bf16" and 0 < m < 16:   # squared row norms, hence the draws, are those of V
         absv = orc.hyperattn_forward_alg2(Q, K, np.abs(V), b=b, m=m, r=r, seed=seed, cap_scale=cap_scale, kappa=kappa,
                                           vnorm_sampling=vnorm, vnorm_from=V, vnorm_replay=replay)[0]
-    assert_close(to_host(out), ref_out, dtype, "out", absv)
+    assert_close(to_host(out), ref_out, dtype, "out", absv, 0.005)
 
 
 def test_alg2_rejects_causal_and_bad_workspace(ha, torch):

@@ -3,41 +3,38 @@
 same seeded inputs, hash codes first (sign bits the GPU resolved differently on
 a vanishing projection are replayed in the oracle, as in the forward tests).
 
-Tolerance (derived from the arithmetic; the paper states none for gradients):
-every term P_ij x or dS_ij x of a gradient element reaches the fp32 accumulator
-with a relative error of at most 2^-8 (P or dS rounded to bf16 as matrix-core
-operand: 2^-9; delta_i built from the bf16 output: 2^-9), the terms' errors are
-independent, and the result is rounded to bf16 once more.  So the error of a
-tensor is about 2^-9 .. 2^-8 of its size in the root-mean-square sense and a
-few times that at its worst element:
-    ||got - ref||_F <= 5e-3 ||ref||_F   and   max|got - ref| <= 1e-2 max|ref|
-(measured: 2.3e-3 .. 2.6e-3 and 2e-3 .. 5e-3 when a row has hundreds of keys, up to 3.3e-3 and 7e-3 when it has
-five and the operand roundings do not average out; rounding the fp64 result to bf16 alone gives 2.3e-3).
-A dropped term, a wrong mask, sign or weight moves both by O(1).
-
-Peaked rows are the exception.  dS_ij = P_ij (<dO_i, v_j> - delta_i) with delta_i =
-<dO_i, O_i> is a difference that cancels when a row's weight sits on few keys, and delta
-inherits two errors of the forward: the rounding of the output to bf16 (avoided by
-hyperattn_forward_train's fp32 copy, used here) and the rounding of the softmax weights
-to bf16 as matrix operands (inherent to the forward; std of delta's error about
-2^-9/sqrt(3) * sqrt(sum_j P_ij^2 <dO_i,v_j>^2)).  dQ_i and dK_j pick that error up times
-sum_j P_ij k_j resp. q_i, with no small factor in front.  On the 64-centre mixture
-(scores up to +-250) dQ is off by 1.2e-2 in the Frobenius sense (2.6e-2 with delta from
-the bf16 output) and dK by 4e-3; that law is tested against 3e-2 / 5e-2, and the seeded
-random cases avoid the regime (no m in 1..15, whose sample weight s/m puts a row's
-weight on a handful of sampled keys).  dV carries no such difference and keeps the
-tight bound everywhere."""
+Tolerance (derived from the arithmetic; the paper states none for gradients),
+per element, as for the forward's outputs: a gradient element is a sum of terms
+P_ij x or dS_ij x; on the matrix cores P and dS = P (dP - delta) enter as bf16
+operands (relative rounding error at most 2^-9 each), delta = <dO, O> inherits
+the forward's own operand rounding (at most 2^-9 <|dO|, sum_j P_ij |v_j|>), and
+the result is rounded to bf16 once.  So
+    |got - ref| <= 2^-8 * bound + half a bf16 ulp of |ref|,
+where `bound` is the oracle's backward evaluated on absolute values
+(hyperattn_backward(..., absolute=True): the sum of the magnitudes of the terms,
+differences turned into sums) and 2^-8 = 2 * 2^-9 covers the two roundings that
+can meet in one term.  The bound scales with what a row actually holds, so it
+needs no exceptions: rows whose weight sits on a handful of keys (tiny blocks,
+m of a few samples weighted s/m, the 64-centre mixture with scores up to +-250)
+are compared under the same formula as the flat iid rows.  The relative
+Frobenius error of each tensor is printed as well and, for the iid inputs,
+asserted against 4e-3 (rounding the fp64 gradient to bf16 alone gives 2.3e-3; measured at
+most 3.1e-3).  Gradient values below 2^-100 are flushed to zero by the GPU's arithmetic and
+are allowed that much absolute error.
+A dropped term, a wrong mask, sign or weight moves an element by the size of
+the term, hundreds of times the tolerance."""
 import numpy as np
 import pytest
 
 import synth_inputs
 from oracle import hyperattn_oracle as orc
-from ha_testutil import compare_codes, have_gpu, to_device, to_host
+from ha_testutil import compare_codes, half_ulp_bf16, have_gpu, to_device, to_host
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not have_gpu(), reason="needs a GPU")]
 
-FRO_TOL = 5e-3
-MAX_TOL = 1e-2
+EPS_OPERANDS = 2.0 ** -8
+FRO_TOL = 4e-3            # iid inputs only (measured: at most 3.1e-3)
+TINY = 2.0 ** -100        # values below the smallest normal number are flushed to zero on the GPU
 
 
 @pytest.fixture(scope="module")
@@ -53,13 +50,19 @@ def torch():
     return t
 
 
-def _assert_grad_close(got, ref, what, fro_tol=FRO_TOL, max_tol=MAX_TOL):
+def _assert_grad_close(got, ref, bound, what, fro_tol=None):
+    err = np.abs(got - ref)
+    tol = EPS_OPERANDS * bound + half_ulp_bf16(ref) + TINY
     fro = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
-    mx = np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30)
-    print(f"  {what}: relative Frobenius error {fro:.2e}, worst element / max|ref| {mx:.2e}", flush=True)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        ratio = np.where(tol > 0, err / tol, np.where(err > 0, np.inf, 0.0))
+    print(f"  {what}: worst error / tolerance {ratio.max():.2f}, relative Frobenius error {fro:.2e}", flush=True)
     assert np.isfinite(got).all(), what
-    assert fro <= fro_tol, (what, fro)
-    assert mx <= max_tol, (what, mx)
+    bad = err > tol
+    assert not bad.any(), (f"{what}: {int(bad.sum())} of {bad.size} elements out of tolerance; worst error "
+                           f"{err.max():.3e} at |ref| {np.abs(ref).ravel()[err.argmax()]:.3e}")
+    if fro_tol is not None:
+        assert fro <= fro_tol, (what, fro)
 
 
 def _cotangent(shape, seed):
@@ -67,12 +70,7 @@ def _cotangent(shape, seed):
     return synth_inputs.round_to_bf16(g)
 
 
-# Peaked rows (the mixture law): see the module docstring.
-PEAKED_FRO_TOL = 3e-2
-PEAKED_MAX_TOL = 5e-2
-
-
-def _run_case(ha, torch, cfg, seed_data=77, peaked=False):
+def _run_case(ha, torch, cfg, seed_data=77):
     B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
     Q, K, V = synth_inputs.make_qkv(cfg, seed=seed_data)
     G = _cotangent(Q.shape, seed_data + 1)
@@ -96,12 +94,14 @@ def _run_case(ha, torch, cfg, seed_data=77, peaked=False):
                               n_min=cfg["n_min"], seed=cfg["seed"], stages=stages)
         gpu_codes = np.stack([views["codes_q"].cpu().numpy(), views["codes_k"].cpu().numpy()])
         flips = compare_codes(gpu_codes, stages, cfg["r"])
-    rq, rk, rv = orc.hyperattn_backward(Q, K, V, G, b=cfg["b"], m=cfg["m"], r=cfg["r"], causal=bool(cfg["causal"]),
-                                        n_min=cfg["n_min"], seed=cfg["seed"], flip=flips or None)
-    tols = (PEAKED_FRO_TOL, PEAKED_MAX_TOL) if peaked else (FRO_TOL, MAX_TOL)
-    _assert_grad_close(to_host(gq), rq, "dQ", *tols)
-    _assert_grad_close(to_host(gk), rk, "dK", *tols)
-    _assert_grad_close(to_host(gv), rv, "dV")      # dV has no cancelling difference
+    okw = dict(b=cfg["b"], m=cfg["m"], r=cfg["r"], causal=bool(cfg["causal"]), n_min=cfg["n_min"], seed=cfg["seed"],
+               flip=flips or None)
+    rq, rk, rv = orc.hyperattn_backward(Q, K, V, G, **okw)
+    bq, bk, bv = orc.hyperattn_backward(Q, K, V, G, absolute=True, **okw)
+    fro = FRO_TOL if cfg["law"] == "iid" else None
+    _assert_grad_close(to_host(gq), rq, bq, "dQ", fro)
+    _assert_grad_close(to_host(gk), rk, bk, "dK", fro)
+    _assert_grad_close(to_host(gv), rv, bv, "dV", fro)
     return (gq, gk, gv), (dQ_, dK_, dV_, out, lse, dG_, ws, out32)
 
 
@@ -136,19 +136,21 @@ def test_exact_attn_backward(ha, torch, d, n, causal):
     gq, gk, gv = ha.exact_attn_backward(tq, tk, tv, out, lse, tg, causal=causal, out_f32=out32)
     torch.cuda.synchronize()
     if causal:   # the recursion that never splits is exact causal attention
-        ref = orc.hyperattn_backward(Q, K, V, G, b=1, m=0, r=1, causal=True, n_min=n)
+        okw = dict(b=1, m=0, r=1, causal=True, n_min=n)
     else:        # one block and no samples is exact attention
-        ref = orc.hyperattn_backward(Q, K, V, G, b=n, m=0, r=1, causal=False)
-    for got, r_, name in zip((gq, gk, gv), ref, ("dQ", "dK", "dV")):
-        _assert_grad_close(to_host(got), r_, name)
+        okw = dict(b=n, m=0, r=1, causal=False)
+    ref = orc.hyperattn_backward(Q, K, V, G, **okw)
+    bnd = orc.hyperattn_backward(Q, K, V, G, absolute=True, **okw)
+    for got, r_, b_, name in zip((gq, gk, gv), ref, bnd, ("dQ", "dK", "dV")):
+        _assert_grad_close(to_host(got), r_, b_, name, FRO_TOL)
 
 
 def test_backward_on_the_mixture_law(ha, torch):
-    """Peaked attention rows (scores up to +-250): dQ and dK against the looser bound the
-    cancellation in dP - delta calls for, dV against the tight one."""
+    """Peaked attention rows (scores up to +-250), where dS = P (dP - delta) cancels: the same
+    per-element criterion as everywhere, whose bound grows with sum_j P_ij |dP_ij| + |delta_i|."""
     print("backward mixture", flush=True)
     cfg = dict(B=1, H=2, n=4096, d=64, dtype="bf16", law="mixture", b=256, m=512, r=7, causal=0, n_min=4096, seed=0)
-    _run_case(ha, torch, cfg, peaked=True)
+    _run_case(ha, torch, cfg)
 
 
 def test_backward_with_delta_from_the_bf16_output(ha, torch):
@@ -164,8 +166,10 @@ def test_backward_with_delta_from_the_bf16_output(ha, torch):
     grads = ha.hyperattn_backward(tq, tk, tv, out, lse, tg, 256, 256, 7, fwd_workspace=ws, **kw)
     torch.cuda.synchronize()
     ref = orc.hyperattn_backward(Q, K, V, G, b=256, m=256, r=7, causal=True, n_min=512, seed=0)
-    for got, r_, what in zip(grads, ref, ("dQ", "dK", "dV")):
-        _assert_grad_close(to_host(got), r_, what)
+    bnd = orc.hyperattn_backward(Q, K, V, G, b=256, m=256, r=7, causal=True, n_min=512, seed=0, absolute=True)
+    # delta = <dO, bf16(O)> adds at most 2^-9 <|dO|, |O|> to delta's error: still inside the 2^-8 of the criterion
+    for got, r_, b_, what in zip(grads, ref, bnd, ("dQ", "dK", "dV")):
+        _assert_grad_close(to_host(got), r_, b_, what, FRO_TOL)
 
 
 def test_backward_is_deterministic_and_leaves_inputs_alone(ha, torch):
@@ -235,8 +239,9 @@ def test_backward_full_size_sampled_head(ha, torch, name):
     gpu_codes = np.stack([views["codes_q"][:1].cpu().numpy(), views["codes_k"][:1].cpu().numpy()])
     flips = compare_codes(gpu_codes, stages, cfg["r"])
     ref = orc.hyperattn_backward(*host, Gh, flip=flips or None, **okw)
-    for got, r_, what in zip(grads, ref, ("dQ", "dK", "dV")):
-        _assert_grad_close(to_host(got[0, :1])[None], r_, what)
+    bnd = orc.hyperattn_backward(*host, Gh, flip=flips or None, absolute=True, **okw)
+    for got, r_, b_, what in zip(grads, ref, bnd, ("dQ", "dK", "dV")):
+        _assert_grad_close(to_host(got[0, :1])[None], r_, b_, what, FRO_TOL)
         assert torch.isfinite(got.float()).all()
 
 
@@ -270,7 +275,7 @@ def _random_cases(count, seed):
         causal = int(rng.integers(0, 2))
         b = int(rng.choice([8, 16, 24, 32, 48, 64, 96, 128, 256]))
         r = int(rng.integers(1, 9))
-        m = int(rng.choice([0, 16, 33, 64, 100, 256]))
+        m = int(rng.choice([0, 1, 2, 5, 11, 16, 33, 64, 100, 256]))
         if causal:
             n_min = b * int(rng.integers(1, 5))
             n = n_min * (1 << int(rng.integers(0, 5)))
@@ -299,7 +304,8 @@ def test_forward_and_backward_on_random_small_problems(ha, torch, d, n, n_min, b
         stages = {}
         run_oracle(Q, K, V, cfg, stages=stages)
         flips = compare_codes(np.stack([views["codes_q"].cpu().numpy(), views["codes_k"].cpu().numpy()]), stages, r)
-    # rows with few keys average little: the operand-rounding term 2^-8 sum_j p_j |v_j| is passed explicitly
+    # a single sampled key with the weight s/m can carry a row: only then may an element use the
+    # operand-rounding allowance 2^-8 sum_j p_j |v_j| (see tests/test_gpu_parity.py)
     ref_out, ref_lse, absv = run_oracle(Q, K, V, cfg, flip=flips or None, with_absv=True)
-    assert_close(to_host(out), ref_out, "bf16", "out", absv)
+    assert_close(to_host(out), ref_out, "bf16", "out", absv if 0 < m < 16 else None, 0.005)
     assert_lse_close(to_host(lse), ref_lse, "bf16", "lse")

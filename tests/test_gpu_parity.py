@@ -1,7 +1,16 @@
 """GPU parity: the HIP library (through its C ABI) against the CPU oracle on the
 same seeded inputs.  Integer stages (bucket codes, permutations, gathers) must
 be bit-exact; floating point outputs must be within the stated tolerance
-(bf16: 2e-3 + half a bf16 ulp of the result; fp32: 1e-5 + 1e-5 |result|)."""
+(bf16: 2e-3 + half a bf16 ulp of the result; fp32: 1e-5 + 1e-5 |result|).
+
+Only where a row's weight can sit on a handful of keys, so that the rounding of
+the softmax weights to bf16 (matrix-core operands, relative error up to 2^-9)
+does not average out, may an element also use the allowance
+2^-8 sum_j p_j |v_j| (the oracle run on |V|): the 64-centre mixture law, and
+0 < m < 16, where a single sampled key carries the weight s/m.  There the
+number of elements that need the allowance is printed and must stay below
+0.5 % (measured: at most 0.17 %); everywhere else the plain criterion is the
+assertion."""
 import numpy as np
 import pytest
 
@@ -144,8 +153,15 @@ def test_exact_attn_matches_definition(ha, torch, dtype, d, n, causal):
 
 
 # ------------------------------------------------------------------ whole forward
-def _forward_and_compare(ha, torch, cfg, Q, K, V, R=None, samples=None, sample_fn=None, p_rounding_term=False):
-    """p_rounding_term: widen the bf16 tolerance by 2^-8 sum_j p_j|v_j| (inputs with large |V|)."""
+PLAIN_FRAC = 0.005   # share of the elements that may need the operand-rounding allowance where it applies
+
+
+def _few_keys_carry_a_row(cfg):
+    return cfg["dtype"] == "bf16" and (cfg["law"] == "mixture" or 0 < cfg["m"] < 16)
+
+
+def _forward_and_compare(ha, torch, cfg, Q, K, V, R=None, samples=None, sample_fn=None, plain_frac=PLAIN_FRAC):
+    p_rounding_term = _few_keys_carry_a_row(cfg)
     dtype = cfg["dtype"]
     B, H, n, d = Q.shape
     shape = ha.make_shape(B, H, n, d, ha.HA_BF16 if dtype == "bf16" else ha.HA_FP32)
@@ -193,7 +209,7 @@ def _forward_and_compare(ha, torch, cfg, Q, K, V, R=None, samples=None, sample_f
                         np.testing.assert_array_equal(sblk[bh, heap], rposk[smp[heap]] // cfg["b"])
     # stage 3: outputs
     got = to_host(out)
-    err = assert_close(got, ref_out, dtype, "out", absv if p_rounding_term else None)
+    err = assert_close(got, ref_out, dtype, "out", absv if p_rounding_term else None, plain_frac)
     assert_lse_close(to_host(lse), ref_lse, dtype, "lse")
     over = int((np.abs(got - ref_out) > 2e-3).sum())
     print(f"  max abs err {err:.3e}; elements over 2e-3: {over} of {got.size}; sign flips {len(flips)}", flush=True)
@@ -214,7 +230,7 @@ def test_forward_unmasked_bf16(ha, torch, d, n, b, m, law):
     print(f"forward bf16 d={d} n={n} b={b} m={m} {law}", flush=True)
     cfg = dict(B=1, H=2, n=n, d=d, dtype="bf16", law=law, b=b, m=m, r=7, causal=0, n_min=4096, seed=0)
     Q, K, V = synth_inputs.make_qkv(cfg)
-    _forward_and_compare(ha, torch, cfg, Q, K, V, p_rounding_term=(law == "mixture"))
+    _forward_and_compare(ha, torch, cfg, Q, K, V)
 
 
 @pytest.mark.parametrize("dtype,d,n,n_min,b,m", [("bf16", 128, 2048, 256, 128, 64), ("bf16", 64, 4096, 1024, 256, 256),
@@ -296,6 +312,28 @@ def test_empty_and_error_paths(ha, torch):
     with pytest.raises(ha.HyperAttnError) as e:
         ha.hyperattn_forward(q, q, q, 64, 8, 4, workspace=small)
     assert e.value.status == -4
+    # the binding takes every size from Q: tensors that do not match are refused before the call
+    with pytest.raises(ValueError):
+        ha.hyperattn_forward(q, q[:, :, :64], q, 64, 8, 4)
+    with pytest.raises(TypeError):
+        ha.hyperattn_forward(q, q, q.float(), 64, 8, 4)
+    with pytest.raises(TypeError):
+        ha.hyperattn_forward(q, q, q, 64, 8, 4, lse=torch.zeros((1, 1, 128), dtype=torch.float64, device="cuda"))
+    with pytest.raises(ValueError):
+        ha.exact_attn_forward(q, q, q, out=torch.zeros((1, 1, 64, 64), dtype=torch.bfloat16, device="cuda"))
+    # caller-supplied sample indices outside their node
+    bad = torch.full((1, 8), 128, dtype=torch.int32, device="cuda")
+    with pytest.raises(ha.HyperAttnError) as e:
+        ha.hyperattn_forward(q, q, q, 64, 8, 4, samples=bad)
+    assert e.value.status == -3
+    ok = torch.full((1, 8), 127, dtype=torch.int32, device="cuda")
+    ha.hyperattn_forward(q, q, q, 64, 8, 4, samples=ok)
+    qc = torch.zeros((1, 1, 256, 64), dtype=torch.bfloat16, device="cuda")   # causal: nodes of 128, 64, 64 rows
+    with pytest.raises(ha.HyperAttnError):
+        ha.hyperattn_forward(qc, qc, qc, 64, 2, 4, causal=True, n_min=64,
+                             samples=torch.tensor([[127, 0], [64, 0], [0, 0]], dtype=torch.int32, device="cuda"))
+    ha.hyperattn_forward(qc, qc, qc, 64, 2, 4, causal=True, n_min=64,
+                         samples=torch.tensor([[127, 0], [63, 0], [0, 63]], dtype=torch.int32, device="cuda"))
 
 
 # ------------------------------------------------------------------ hash: the uncertified-sign path
@@ -330,37 +368,36 @@ def test_lsh_hash_bf16_rows_with_unrepresentable_R(ha, torch):
 
 
 # ------------------------------------------------------------------ full benchmark sizes, sampled heads
-def _full_size_inputs(torch, cfg, host_heads):
+def _full_size_inputs(torch, cfg, checked):
     """All heads drawn on the device from the configuration's law; the checked
-    heads (batch 0, heads < host_heads) come from the seeded host generator."""
+    (batch, head) pairs come from the seeded host generator, one host head each."""
     B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
     g = torch.Generator(device="cuda")
     g.manual_seed(99)
-    host = synth_inputs.make_qkv(cfg, B=1, H=host_heads)
-    dev = []
+    host = synth_inputs.make_qkv(cfg, B=1, H=len(checked))
+    dev = synth_inputs.device_qkv(cfg, torch, g)
     for i in range(3):
-        t = torch.randn((B, H, n, d), generator=g, device="cuda", dtype=torch.float32)
-        if cfg["law"] == "iid" or i == 2:
-            t.mul_(d ** -0.25 if cfg["law"] == "iid" else 1.0)
-        t = t.to(torch.bfloat16)
-        t[0, :host_heads] = to_device(host[i][0], "bf16")
-        dev.append(t.contiguous())
+        for j, (bi, hi) in enumerate(checked):
+            dev[i][bi, hi] = to_device(host[i][0, j], "bf16")
     return dev, host
 
 
-@pytest.mark.parametrize("name,host_heads", [("cfg2_n32k", 2), ("cfg3_n32k_causal", 1), ("cfg4_n131k_causal", 1),
-                                             ("cfg5_n65k_mixture", 1),
-                                             # the 12-head, d = 64 sweep shape: shortest, a middle and the longest length
-                                             ("sweep_h12_d64_n4096", 2), ("sweep_h12_d64_n4096_causal", 2),
-                                             ("sweep_h12_d64_n16384_causal", 2), ("sweep_h12_d64_n131072", 1),
-                                             ("sweep_h12_d64_n131072_causal", 1)])
-def test_full_size_configuration_sampled_heads(ha, torch, name, host_heads):
+@pytest.mark.parametrize("name,checked", [
+    ("cfg2_n32k", [(0, 0), (0, 11), (0, 21), (0, 31)]),
+    ("cfg3_n32k_causal", [(0, 0), (0, 7), (0, 19), (0, 31)]),
+    ("cfg4_n131k_causal", [(0, 0), (0, 13), (0, 22), (0, 31)]),
+    ("cfg5_n65k_mixture", [(0, 0), (1, 17)]),             # one head of each batch
+    # the 12-head, d = 64 sweep shape: shortest, a middle and the longest length
+    ("sweep_h12_d64_n4096", [(0, 0), (0, 11)]), ("sweep_h12_d64_n4096_causal", [(0, 0), (0, 11)]),
+    ("sweep_h12_d64_n16384_causal", [(0, 0), (0, 5)]), ("sweep_h12_d64_n131072", [(0, 3)]),
+    ("sweep_h12_d64_n131072_causal", [(0, 8)])])
+def test_full_size_configuration_sampled_heads(ha, torch, name, checked):
     """The benchmark configurations at full size, in the launch configuration
-    bench.py times; the heads fed from the host generator are compared with the
+    bench.py times; the (batch, head) pairs fed from the host generator are compared with the
     oracle element by element (codes first, then outputs)."""
     cfg = synth_inputs.CONFIGS[name]
-    print(f"full size {name}: checking {host_heads} head(s) against the oracle", flush=True)
-    (Q, K, V), host = _full_size_inputs(torch, cfg, host_heads)
+    print(f"full size {name}: checking (batch, head) {checked} against the oracle", flush=True)
+    (Q, K, V), host = _full_size_inputs(torch, cfg, checked)
     B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
     shape = ha.make_shape(B, H, n, d, ha.HA_BF16)
     params = ha.make_params(cfg["b"], cfg["m"], cfg["r"], cfg["causal"], cfg["n_min"], cfg["seed"])
@@ -369,18 +406,20 @@ def test_full_size_configuration_sampled_heads(ha, torch, name, host_heads):
                                     seed=cfg["seed"], workspace=ws)
     torch.cuda.synchronize()
     views = ha.workspace_views(ws, shape, params)
+    rows = [bi * H + hi for bi, hi in checked]
     stages = {}
     ref_out, ref_lse, absv = run_oracle(*host, cfg, stages=stages, with_absv=True)
     flips = []
     if ha.ha_workspace_layout(shape, params).levels > 0:  # else the call is one exact causal block: nothing is hashed
-        gpu_codes = np.stack([views["codes_q"][:host_heads].cpu().numpy(), views["codes_k"][:host_heads].cpu().numpy()])
+        gpu_codes = np.stack([views["codes_q"][rows].cpu().numpy(), views["codes_k"][rows].cpu().numpy()])
         flips = compare_codes(gpu_codes, stages, cfg["r"])
     if flips:
         print(f"  replaying {len(flips)} near-zero sign bits in the oracle", flush=True)
         ref_out, ref_lse, absv = run_oracle(*host, cfg, flip=flips, with_absv=True)
-    got = to_host(out[0, :host_heads])[None]
-    err = assert_close(got, ref_out, "bf16", "out", absv if cfg["law"] == "mixture" else None)
-    assert_lse_close(to_host(lse[0, :host_heads])[None], ref_lse, "bf16", "lse")
+    got = np.stack([to_host(out[bi, hi]) for bi, hi in checked])[None]
+    got_lse = np.stack([to_host(lse[bi, hi]) for bi, hi in checked])[None]
+    err = assert_close(got, ref_out, "bf16", "out", absv if _few_keys_carry_a_row(cfg) else None, PLAIN_FRAC)
+    assert_lse_close(got_lse, ref_lse, "bf16", "lse")
     over = int((np.abs(got - ref_out) > 2e-3).sum())
     print(f"  max abs err {err:.3e}; elements over 2e-3: {over} of {got.size}; sign flips {len(flips)}", flush=True)
     # the unchecked heads: rows are normalised and finite
@@ -403,37 +442,40 @@ def test_measurement_aids(ha, torch):
         ha.ha_measure_hbm_rate(small)
 
 
-def test_diagnostics_against_dense_definitions(ha, torch):
-    """alpha, ||D^-1 A||_op and kappa as diagnostics.py obtains them from the library's entry
-    points, against their definitions evaluated densely in fp64 (Lemma 1) at a small size."""
+@pytest.mark.parametrize("causal", [0, 1])
+def test_diagnostics_against_the_oracle(ha, torch, causal):
+    """The epsilon of Eq. (1), alpha and kappa (Lemma 1) as diagnostics.py obtains them from the
+    library's entry points, against the oracle's dense fp64 definitions at a small size.  The
+    library's figures come from bf16 tensors: about two significant digits."""
     import diagnostics
-    print("diagnostics", flush=True)
-    cfg = dict(B=1, H=2, n=768, d=64, dtype="bf16", law="iid", b=64, m=32, r=5, causal=0, n_min=4096, seed=0)
+    print(f"diagnostics causal={causal}", flush=True)
+    cfg = dict(B=1, H=2, n=768, d=64, dtype="bf16", law="iid", b=64, m=32, r=5, causal=causal, n_min=192, seed=0)
     Q, K, V = synth_inputs.make_qkv(cfg, seed=21)
     tq, tk, tv = (to_device(x, "bf16") for x in (Q, K, V))
-    _, lse_e = ha.exact_attn_forward(tq, tk, tv, causal=False)
-    alpha = diagnostics.alpha_of(torch, ha, tq, tk, lse_e).cpu().numpy()
-    p_op = diagnostics.softmax_op_norm(torch, ha, tq, tk, lse_e, False, 25).cpu().numpy()
-    _, lse_b = ha.hyperattn_forward(tq, tk, tv, cfg["b"], 0, cfg["r"])
-    kappa, _ = diagnostics.kappa_of(torch, lse_e, lse_b)
+    kw = dict(causal=bool(causal), n_min=cfg["n_min"], seed=cfg["seed"])
+    out_h, _ = ha.hyperattn_forward(tq, tk, tv, cfg["b"], cfg["m"], cfg["r"], **kw)
+    out_e, lse_e = ha.exact_attn_forward(tq, tk, tv, causal=bool(causal))
+    eps, err_op, p_op, v_op = (x.cpu().numpy() for x in
+                               diagnostics.spectral_error_of(torch, ha, tq, tk, tv, out_h, out_e, lse_e, bool(causal), 25))
+    ref_out, _ = run_oracle(Q, K, V, cfg)
     stages = {}
-    orc.hyperattn_forward(Q, K, V, b=cfg["b"], m=0, r=cfg["r"], causal=False, stages=stages)
+    if not causal:
+        alpha = diagnostics.alpha_of(torch, ha, tq, tk, lse_e).cpu().numpy()
+        _, lse_b = ha.hyperattn_forward(tq, tk, tv, cfg["b"], 0, cfg["r"], **kw)
+        kappa, _ = diagnostics.kappa_of(torch, lse_e, lse_b)
+        orc.hyperattn_forward(Q, K, V, b=cfg["b"], m=0, r=cfg["r"], causal=False, stages=stages)
     for hd in range(2):
-        S = Q[0, hd].astype(np.float64) @ K[0, hd].astype(np.float64).T
-        P = np.exp(S - S.max(axis=1, keepdims=True))
-        D = P.sum(axis=1, keepdims=True)
-        P /= D
-        a_ref = cfg["n"] * (P ** 2).sum(axis=0).max()
-        s_ref = np.linalg.svd(P, compute_uv=False)[0]
-        parts = stages["parts"][hd]
-        mask = (parts["pos_q"][:, None] // cfg["b"]) == (parts["pos_k"][None, :] // cfg["b"])
-        unmasked = np.where(mask, 0.0, np.exp(S)).sum(axis=1)
-        k_ref = unmasked.max() / unmasked.min()
-        print(f"  head {hd}: alpha {alpha[hd]:.3f} vs {a_ref:.3f}; ||P|| {p_op[hd]:.4f} vs {s_ref:.4f}; "
-              f"kappa {float(kappa[hd]):.3f} vs {k_ref:.3f}", flush=True)
-        assert abs(alpha[hd] - a_ref) <= 0.03 * a_ref          # bf16 weights squared: about 1 %
+        e_ref = orc.spectral_error(ref_out[0, hd], Q[0, hd], K[0, hd], V[0, hd], bool(causal))
+        s_ref = np.linalg.svd(orc.attention_matrix(Q[0, hd], K[0, hd], bool(causal)), compute_uv=False)[0]
+        print(f"  head {hd}: epsilon {eps[hd]:.4f} vs {e_ref:.4f}; ||D^-1 A|| {p_op[hd]:.4f} vs {s_ref:.4f}", flush=True)
         assert abs(p_op[hd] - s_ref) <= 0.02 * s_ref
-        assert abs(float(kappa[hd]) - k_ref) <= 0.05 * k_ref
+        assert abs(eps[hd] - e_ref) <= 0.05 * e_ref            # both outputs carry bf16 rounding (2e-3 of 0.1 .. 1)
+        if not causal:
+            a_ref = orc.alpha(Q[0, hd], K[0, hd])
+            k_ref = orc.kappa(Q[0, hd], K[0, hd], stages["codes"][0, hd], stages["codes"][1, hd], cfg["b"])
+            print(f"          alpha {alpha[hd]:.3f} vs {a_ref:.3f}; kappa {float(kappa[hd]):.3f} vs {k_ref:.3f}", flush=True)
+            assert abs(alpha[hd] - a_ref) <= 0.03 * a_ref      # bf16 weights squared: about 1 %
+            assert abs(float(kappa[hd]) - k_ref) <= 0.05 * k_ref
 
 
 def test_forward_on_a_side_stream_and_under_graph_capture(ha, torch):
@@ -506,7 +548,7 @@ def test_forward_with_segments_longer_than_a_sort_chunk(ha, torch, H, n, n_min, 
     print(f"chunked sort H={H} n={n} n_min={n_min} b={b} m={m} r={r} causal={causal}", flush=True)
     cfg = dict(B=1, H=H, n=n, d=64, dtype="bf16", law="iid", b=b, m=m, r=r, causal=causal, n_min=n_min, seed=n + r)
     Q, K, V = synth_inputs.make_qkv(cfg, seed=900 + n)
-    _forward_and_compare(ha, torch, cfg, Q, K, V, p_rounding_term=True)
+    _forward_and_compare(ha, torch, cfg, Q, K, V)
 
 
 def _random_forward_cases(count, seed):
@@ -538,4 +580,4 @@ def test_forward_on_random_small_problems(ha, torch, dtype, d, n, n_min, b, m, r
     print(f"random forward {dtype} d={d} n={n} n_min={n_min} b={b} m={m} r={r} causal={causal}", flush=True)
     cfg = dict(B=1, H=2, n=n, d=d, dtype=dtype, law="iid", b=b, m=m, r=r, causal=causal, n_min=n_min, seed=3 * n + m)
     Q, K, V = synth_inputs.make_qkv(cfg, seed=500 + n + b)
-    _forward_and_compare(ha, torch, cfg, Q, K, V, p_rounding_term=(dtype == "bf16"))
+    _forward_and_compare(ha, torch, cfg, Q, K, V)
