@@ -266,6 +266,38 @@ def backward_bench(args, torch, ha):
     print(json.dumps(result), flush=True)
 
 
+def probes(args, torch, ha):
+    """The issue-rate probes of the library (measurement aid): cycles per instruction of what the
+    attention loop consists of, and what that makes of one 64-key tile of the d = 128 kernel."""
+    buf = torch.zeros(4 << 20, dtype=torch.uint8, device="cuda")
+    ha.ha_measure_issue_rates(buf)                      # warm-up
+    raw = ha.ha_measure_issue_rates(buf)
+    r = {k: round(max(v), 1) for k, v in raw.items()}   # the slower half of the workgroup
+    per = {"v_exp_f32": r["exp_x64"] / 64, "v_fma_f32": r["fma_x64"] / 64, "v_cvt_pk_bf16_f32": r["cvt_pk_bf16_x64"] / 64,
+           "v_max3_f32": r["max3_x64"] / 64, "v_mfma_f32_32x32x16_bf16": r["mfma_x16"] / 16}
+    # two waves per SIMD issue the same loop, so a trip of both takes the printed cycles: per wave half of it
+    per = {k: round(v / 2, 2) for k, v in per.items()}
+    lds = {"ds_read_b128_B_per_clk_per_CU": round(65536 / r["lds_read_b128_64KiB"], 1),
+           "ds_read_b64_tr_b16_B_per_clk_per_CU": round(32768 / r["lds_read_tr_b64_32KiB"], 1),
+           "ds_write_b128_B_per_clk_per_CU": round(65536 / r["lds_write_b128_64KiB"], 1)}
+    # one 64-key tile of one wave at d = 128: 32 MFMAs; 32 fma + 32 exp + 32 add + 16 cvt + 17 max3 + ~12 others;
+    # 16 KiB of K fragments (b128 reads), 16 KiB of V^T fragments (transposing b64 reads), and 1/4 (four-wave
+    # workgroups) of the 32 KiB tile written.  Per CU and round of eight wave-tiles (two per SIMD):
+    mfma = 2 * 32 * per["v_mfma_f32_32x32x16_bf16"]
+    valu = 2 * (32 * per["v_exp_f32"] + 16 * per["v_cvt_pk_bf16_f32"] + 17 * per["v_max3_f32"] +
+                (32 + 32 + 12) * per["v_fma_f32"])
+    lds_cyc = 8 * (16384 / lds["ds_read_b128_B_per_clk_per_CU"] + 16384 / lds["ds_read_b64_tr_b16_B_per_clk_per_CU"] +
+                   8192 / lds["ds_write_b128_B_per_clk_per_CU"])
+    tile = {"mfma_pipe_cycles_per_SIMD": round(mfma), "vector_issue_cycles_per_SIMD": round(valu),
+            "lds_cycles_per_CU": round(lds_cyc)}
+    log(f"[bench] cycles per instruction and wave: {per}")
+    log(f"[bench] LDS: {lds}")
+    log(f"[bench] one round of eight 64-key wave-tiles (d = 128): {tile}")
+    print(json.dumps({"metric": "issue-rate probes", "unit": "shader cycles", "n_gpus": 1,
+                      "cycles_per_trip": raw, "cycles_per_instruction_per_wave": per, "lds": lds,
+                      "round_of_eight_wave_tiles_d128": tile}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -277,6 +309,7 @@ def main():
     ap.add_argument("--backward", action="store_true", help="time forward + backward instead of the forward alone")
     ap.add_argument("--sweep", action="store_true", help="time the 12-head d=64 sweep shape at every length instead")
     ap.add_argument("--alg2", action="store_true", help="time Algorithm 2 as printed / Lemma 2's value sampling instead")
+    ap.add_argument("--probes", action="store_true", help="run the library's issue-rate probes instead")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (heads would shard over GPUs with no communication); "
@@ -288,6 +321,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
 
+    if args.probes:
+        return probes(args, torch, ha)
     if args.sweep:
         return sweep(args, torch, ha)
     if args.alg2:

@@ -353,6 +353,19 @@ int hyperattn_forward_alg2(const void* Q, const void* K, const void* V, void* ou
 int ha_measure_mfma_rate(void* buf, size_t bytes, int32_t iters, float* tflops, void* stream);
 int ha_measure_hbm_rate(void* buf, size_t bytes, float* read_gbs, float* copy_gbs, void* stream);
 
+/* Issue-rate probes (measurement aid): what one trip of small instruction loops costs in
+ * shader-clock cycles on this GPU, every CU running the same loop in one workgroup of eight
+ * waves (two per SIMD).  cycles_host (host memory) receives 2 * ha_issue_probe_count() floats:
+ * for probe p, [2p] is the first wave of the workgroup's first half, [2p+1] of its second half.
+ * A trip holds, in this order of p: 64 v_exp_f32; 64 v_fma_f32; 64 v_cvt_pk_bf16_f32; 64
+ * v_max3_f32; 16 v_mfma_f32_32x32x16_bf16; 16 MFMAs with 4 fma each; with 7 fma each; with 1 exp
+ * + 3 fma each; with 1 exp + 4 fma each; waves 0-3 16 MFMAs while waves 4-7 issue 16 exp + 48 fma;
+ * 8 ds_read_b128 per wave (64 KiB read per trip and workgroup); 8 ds_read_b64_tr_b16 (32 KiB);
+ * 8 ds_write_b128 (64 KiB).  buf: device memory, 16-byte aligned, >= 1 MiB, overwritten.
+ * WAITS for the stream.  Errors: HA_ERR_NULL, HA_ERR_WORKSPACE, HA_ERR_LAUNCH. */
+int32_t ha_issue_probe_count(void);
+int ha_measure_issue_rates(void* buf, size_t bytes, float* cycles_host, void* stream);
+
 /* Text for an ha_status value. */
 const char* ha_strerror(int status);
 

@@ -93,6 +93,8 @@ _SIGNATURES = {
                                                        c_void_p, c_size_t, c_void_p]),
     "ha_measure_mfma_rate": (c_int, [c_void_p, c_size_t, c_int32, POINTER(c_float), c_void_p]),
     "ha_measure_hbm_rate": (c_int, [c_void_p, c_size_t, POINTER(c_float), POINTER(c_float), c_void_p]),
+    "ha_issue_probe_count": (c_int32, []),
+    "ha_measure_issue_rates": (c_int, [c_void_p, c_size_t, POINTER(c_float), c_void_p]),
     "ha_strerror": (c_char_p, [c_int]),
 }
 
@@ -469,6 +471,25 @@ def ha_measure_hbm_rate(buf, stream=None):
     _check(lib().ha_measure_hbm_rate(_dev(buf, "buf"), buf.numel() * buf.element_size(), ctypes.byref(rd),
                                      ctypes.byref(cp), _stream(stream)), "ha_measure_hbm_rate")
     return float(rd.value), float(cp.value)
+
+
+ISSUE_PROBES = ("exp_x64", "fma_x64", "cvt_pk_bf16_x64", "max3_x64", "mfma_x16", "mfma_x16_fma4", "mfma_x16_fma7",
+                "mfma_x16_exp1_fma3", "mfma_x16_exp1_fma4", "split_mfma16_vs_exp16_fma48", "lds_read_b128_64KiB",
+                "lds_read_tr_b64_32KiB", "lds_write_b128_64KiB")
+
+
+def ha_issue_probe_count() -> int:
+    return int(lib().ha_issue_probe_count())
+
+
+def ha_measure_issue_rates(buf, stream=None):
+    """{probe: (cycles per trip of the first wave of waves 0-3, of waves 4-7)}; see include/hyperattn.h."""
+    n = ha_issue_probe_count()
+    assert n == len(ISSUE_PROBES)
+    vals = (c_float * (2 * n))()
+    _check(lib().ha_measure_issue_rates(_dev(buf, "buf"), buf.numel() * buf.element_size(), vals, _stream(stream)),
+           "ha_measure_issue_rates")
+    return {name: (float(vals[2 * i]), float(vals[2 * i + 1])) for i, name in enumerate(ISSUE_PROBES)}
 
 
 # ---------------------------------------------------------------- backward pass

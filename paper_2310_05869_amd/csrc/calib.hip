@@ -83,6 +83,115 @@ __global__ __launch_bounds__(256) void copy_rate_kernel(const u32x4* __restrict_
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// ---------------------------------------------------------------------------
+// Issue-rate probes: shader cycles per instruction of what the attention loop is
+// made of, alone and next to each other, read from the shader clock by one wave
+// while every CU runs the same code.  They answer which of the three things a
+// 64-key tile needs per wave -- 32 MFMAs, about 140 vector instructions of
+// softmax work, 32 KiB of operand fragments from LDS -- the loop runs out of
+// first.
+// ---------------------------------------------------------------------------
+enum IssueProbe : int {
+  kProbeExp, kProbeFma, kProbeCvtPk, kProbeMax3, kProbeMfma, kProbeMfmaFma4, kProbeMfmaFma7, kProbeMfmaExpFma3,
+  kProbeMfmaExpFma4, kProbeSplitMfmaValu, kProbeLdsRead128, kProbeLdsReadTr64, kProbeLdsWrite128, kProbeCount
+};
+
+#define HA_REP8(x) x x x x x x x x
+#define HA_EXP(r) asm volatile("v_exp_f32 %0, %0" : "+v"(r));
+#define HA_FMA(r) asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(r) : "v"(k1), "v"(k2));
+#define HA_MAX3(r) asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(r) : "v"(k1), "v"(k2));
+#define HA_CVT(r) asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(k1), "v"(k2));
+#define HA_MFMA(acc) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+
+constexpr int kProbeIters = 1000;
+
+// 8 waves per workgroup (two per SIMD), one workgroup per CU.  out[probe * 2 + 0 / 1] = cycles the
+// first wave of each half of workgroup 0 took for kProbeIters trips.
+template <int P>
+__global__ __launch_bounds__(512) void issue_probe_kernel(long long* out, float* sink) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[65536];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float r[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r[i] = threadIdx.x * 0.001f + i * 0.01f - 0.5f;
+  float k1 = 0.999f, k2 = -0.001f;
+  asm volatile("" : "+v"(k1), "+v"(k2));
+  f32x16 acc0, acc1;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    acc0[i] = 0.f;
+    acc1[i] = 0.f;
+  }
+  bf16x8 a, b;
+  {
+    u32x4 xb, yb;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      xb[i] = rate_operand_bits((threadIdx.x * 8u + i) * 2654435761u);
+      yb[i] = rate_operand_bits((threadIdx.x * 8u + i + 4u) * 2246822519u);
+    }
+    a = __builtin_bit_cast(bf16x8, xb);
+    b = __builtin_bit_cast(bf16x8, yb);
+  }
+  for (int i = threadIdx.x; i < 16384; i += 512) reinterpret_cast<uint32_t*>(lds)[i] = i * 2654435761u;
+  __syncthreads();
+  u32x4 lacc = {0, 0, 0, 0};
+  const unsigned char* lp = lds + wave * 8192 + lane * 16;
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+  const long long c0 = clock64();
+  for (int it = 0; it < kProbeIters; ++it) {
+    if (P == kProbeExp) { HA_REP8(HA_EXP(r[0]) HA_EXP(r[1]) HA_EXP(r[2]) HA_EXP(r[3]) HA_EXP(r[4]) HA_EXP(r[5]) HA_EXP(r[6]) HA_EXP(r[7])) }
+    if (P == kProbeFma) { HA_REP8(HA_FMA(r[0]) HA_FMA(r[1]) HA_FMA(r[2]) HA_FMA(r[3]) HA_FMA(r[4]) HA_FMA(r[5]) HA_FMA(r[6]) HA_FMA(r[7])) }
+    if (P == kProbeCvtPk) { HA_REP8(HA_CVT(r[0]) HA_CVT(r[1]) HA_CVT(r[2]) HA_CVT(r[3]) HA_CVT(r[4]) HA_CVT(r[5]) HA_CVT(r[6]) HA_CVT(r[7])) }
+    if (P == kProbeMax3) { HA_REP8(HA_MAX3(r[0]) HA_MAX3(r[1]) HA_MAX3(r[2]) HA_MAX3(r[3]) HA_MAX3(r[4]) HA_MAX3(r[5]) HA_MAX3(r[6]) HA_MAX3(r[7])) }
+    if (P == kProbeMfma) { HA_REP8(HA_MFMA(acc0) HA_MFMA(acc1)) }
+    if (P == kProbeMfmaFma4) { HA_REP8(HA_MFMA(acc0) HA_FMA(r[0]) HA_FMA(r[1]) HA_FMA(r[2]) HA_FMA(r[3]) HA_MFMA(acc1) HA_FMA(r[4]) HA_FMA(r[5]) HA_FMA(r[6]) HA_FMA(r[7])) }
+    if (P == kProbeMfmaFma7) { HA_REP8(HA_MFMA(acc0) HA_FMA(r[0]) HA_FMA(r[1]) HA_FMA(r[2]) HA_FMA(r[3]) HA_FMA(r[4]) HA_FMA(r[5]) HA_FMA(r[6]) HA_MFMA(acc1) HA_FMA(r[7]) HA_FMA(r[0]) HA_FMA(r[1]) HA_FMA(r[2]) HA_FMA(r[3]) HA_FMA(r[4]) HA_FMA(r[5])) }
+    if (P == kProbeMfmaExpFma3) { HA_REP8(HA_MFMA(acc0) HA_EXP(r[0]) HA_FMA(r[1]) HA_FMA(r[2]) HA_FMA(r[3]) HA_MFMA(acc1) HA_EXP(r[4]) HA_FMA(r[5]) HA_FMA(r[6]) HA_FMA(r[7])) }
+    if (P == kProbeMfmaExpFma4) { HA_REP8(HA_MFMA(acc0) HA_EXP(r[0]) HA_FMA(r[1]) HA_FMA(r[2]) HA_FMA(r[3]) HA_FMA(r[4]) HA_MFMA(acc1) HA_EXP(r[5]) HA_FMA(r[6]) HA_FMA(r[7]) HA_FMA(r[1]) HA_FMA(r[2])) }
+    if (P == kProbeSplitMfmaValu) {  // waves 0-3: 16 MFMAs; waves 4-7: the vector work of half a tile (16 exp + 48 others)
+      if (wave < 4) { HA_REP8(HA_MFMA(acc0) HA_MFMA(acc1)) }
+      else { HA_REP8(HA_EXP(r[0]) HA_FMA(r[1]) HA_FMA(r[2]) HA_FMA(r[3]) HA_EXP(r[4]) HA_FMA(r[5]) HA_FMA(r[6]) HA_FMA(r[7])) }
+    }
+    if (P == kProbeLdsRead128) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) lacc ^= *reinterpret_cast<const u32x4*>(lp + u * 1024);
+      asm volatile("" : "+v"(lacc));
+    }
+    if (P == kProbeLdsReadTr64) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + wave * 8192 + u * 512 + lane * 8));
+        lacc.x ^= (uint32_t)(unsigned short)v.x | ((uint32_t)(unsigned short)v.y << 16);
+        lacc.y ^= (uint32_t)(unsigned short)v.z | ((uint32_t)(unsigned short)v.w << 16);
+      }
+      asm volatile("" : "+v"(lacc));
+    }
+    if (P == kProbeLdsWrite128) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) *reinterpret_cast<u32x4*>(lds + wave * 8192 + u * 1024 + lane * 16) = lacc;
+      asm volatile("" : "+v"(lacc)::"memory");
+    }
+  }
+  const long long c1 = clock64();
+  __syncthreads();
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) s += r[i];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += acc0[i] + acc1[i];
+  s += (float)(lacc.x ^ lacc.y ^ lacc.z ^ lacc.w) + (float)lds[threadIdx.x];
+  sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+  if (blockIdx.x == 0 && lane == 0 && (wave == 0 || wave == 4)) out[P * 2 + (wave >> 2)] = c1 - c0;
+}
+
+template <int P>
+static void launch_issue_probe(long long* out, float* sink, hipStream_t st) {
+  hipLaunchKernelGGL(issue_probe_kernel<P>, dim3(256), dim3(512), 0, st, out, sink);
+  if constexpr (P + 1 < kProbeCount) launch_issue_probe<P + 1>(out, sink, st);
+}
+
 struct EventPair {
   hipEvent_t a = nullptr, b = nullptr;
   bool ok;
@@ -146,4 +255,23 @@ extern "C" int ha_measure_hbm_rate(void* buf, size_t bytes, float* read_gbs, flo
   }
   *copy_gbs = (float)((double)half16 * 32 / (best * 1e-3) / 1e9);
   return check_launch();
+}
+
+extern "C" int32_t ha_issue_probe_count(void) { return kProbeCount; }
+
+extern "C" int ha_measure_issue_rates(void* buf, size_t bytes, float* cycles_host, void* stream) {
+  if (!buf || !cycles_host) return HA_ERR_NULL;
+  const size_t need = 4096 + (size_t)256 * 512 * sizeof(float);
+  if (bytes < need || (reinterpret_cast<uintptr_t>(buf) & 15u)) return HA_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  long long* out = static_cast<long long*>(buf);
+  float* sink = reinterpret_cast<float*>(static_cast<unsigned char*>(buf) + 4096);
+  launch_issue_probe<0>(out, sink, st);
+  if (check_launch() != HA_OK) return HA_ERR_LAUNCH;
+  long long host[kProbeCount * 2];
+  if (hipMemcpyAsync(host, out, sizeof(host), hipMemcpyDeviceToHost, st) != hipSuccess) return HA_ERR_LAUNCH;
+  if (hipStreamSynchronize(st) != hipSuccess) return HA_ERR_LAUNCH;
+  // cycles per loop trip of the first wave of each half of the workgroup
+  for (int i = 0; i < kProbeCount * 2; ++i) cycles_host[i] = (float)((double)host[i] / kProbeIters);
+  return HA_OK;
 }

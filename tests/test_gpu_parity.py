@@ -435,7 +435,14 @@ def test_measurement_aids(ha, torch):
     print(f"  MFMA {tf:.0f} TFLOP/s, read {rd:.0f} GB/s, copy {cp:.0f} GB/s", flush=True)
     assert 200.0 < tf < 2600.0          # below the 2.5 PFLOP/s peak, far above the vector rate
     assert 500.0 < rd < 8200.0 and 500.0 < cp < 8200.0
+    probes = ha.ha_measure_issue_rates(buf)
+    print("  issue probes: " + ", ".join(f"{k} {max(v):.0f}" for k, v in probes.items()), flush=True)
+    assert set(probes) == set(ha.binding.ISSUE_PROBES)
+    assert 400 < max(probes["mfma_x16"]) < 2000                     # 16 MFMAs of 32 cycles, two waves per SIMD
+    assert all(20 < max(v) < 20000 for v in probes.values())
     small = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    with pytest.raises(ha.HyperAttnError):
+        ha.ha_measure_issue_rates(small)
     with pytest.raises(ha.HyperAttnError):
         ha.ha_measure_mfma_rate(small)
     with pytest.raises(ha.HyperAttnError):
