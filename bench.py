@@ -310,6 +310,9 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="time the 12-head d=64 sweep shape at every length instead")
     ap.add_argument("--alg2", action="store_true", help="time Algorithm 2 as printed / Lemma 2's value sampling instead")
     ap.add_argument("--probes", action="store_true", help="run the library's issue-rate probes instead")
+    ap.add_argument("--heads", type=int, default=0, help="override the workload's head count (profiling runs whose "
+                                                          "32-bit hardware counters a full workload would overflow)")
+    ap.add_argument("--seq", type=int, default=0, help="override the workload's sequence length (same purpose)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (heads would shard over GPUs with no communication); "
@@ -331,6 +334,10 @@ def main():
         return backward_bench(args, torch, ha)
 
     cfg = dict(synth_inputs.CONFIGS[args.workload])
+    if args.heads > 0 or args.seq > 0:
+        cfg["H"] = args.heads if args.heads > 0 else cfg["H"]
+        cfg["n"] = args.seq if args.seq > 0 else cfg["n"]
+        args.workload += f"_H{cfg['H']}_n{cfg['n']}"
     B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
     log(f"[bench] workload {args.workload}: B{B} H{H} n{n} d{d} {cfg['dtype']} b{cfg['b']} m{cfg['m']} r{cfg['r']} "
         f"causal={cfg['causal']} n_min={cfg['n_min']}")
