@@ -509,7 +509,10 @@ def hyperattn_backward(Q, K, V, dO, b, m, r, causal=False, n_min=4096, seed=0, R
 # --------------------------------------------------------------------------
 # Algorithm 2 as printed (caps) and Lemma 2 / Algorithm 3 (value sampling by
 # squared row norms): the estimator variants that Section 4's implementation
-# paragraph leaves out.  Unmasked problems only.
+# paragraph leaves out.  Causal problems run them at every off-diagonal node, as
+# Algorithm 4 does ("run the unmasked algorithm on Q_2, K_1"), each node with its
+# own subset T, index set and value rows (counters offset by the node's heap
+# index 2^level - 1 + node, so the unmasked problem is node 0).
 #
 # Readings: the constant in C_i = Theta(eps^2 m / (n log n) * (masked row sum +
 # tau / kappa)) is a caller's number `cap_scale` (natural log; cap_scale <= 0: no
@@ -525,9 +528,10 @@ STREAM_TAU_ROWS = 0
 STREAM_VNORM = 2
 
 
-def tau_rows(seed: int, n: int, m: int) -> np.ndarray:
-    """The rows of Algorithm 2's subset T."""
-    return np.array([((rand_u64(seed, STREAM_TAU_ROWS, j) >> 32) * n) >> 32 for j in range(m)], dtype=np.int64)
+def tau_rows(seed: int, n: int, m: int, heap: int = 0) -> np.ndarray:
+    """The rows of Algorithm 2's subset T for a node of n rows (node-local indices)."""
+    return np.array([((rand_u64(seed, STREAM_TAU_ROWS, heap * m + j) >> 32) * n) >> 32 for j in range(m)],
+                    dtype=np.int64)
 
 
 def vnorm_probabilities(Vh) -> np.ndarray:
@@ -540,11 +544,11 @@ def vnorm_probabilities(Vh) -> np.ndarray:
     return w / total
 
 
-def vnorm_uniforms(seed: int, bh: int, m: int) -> np.ndarray:
-    return np.array([_unit_open(rand_u64(seed, STREAM_VNORM, bh * m + r_)) for r_ in range(m)])
+def vnorm_uniforms(seed: int, bh: int, m: int, heap: int = 0, n_heads: int = 1) -> np.ndarray:
+    return np.array([_unit_open(rand_u64(seed, STREAM_VNORM, (heap * n_heads + bh) * m + r_)) for r_ in range(m)])
 
 
-def vnorm_samples(Vh, seed: int, bh: int, m: int, replay=None, margin=None):
+def vnorm_samples(Vh, seed: int, bh: int, m: int, replay=None, margin=None, heap: int = 0, n_heads: int = 1):
     """(indices l'_1..l'_m, log of their rescaling factors 1 / (m p_l)) for head bh (Lemma 2).
 
     `replay` {r: l} fixes individual draws (used to follow another evaluation
@@ -553,7 +557,7 @@ def vnorm_samples(Vh, seed: int, bh: int, m: int, replay=None, margin=None):
     distance of its uniform to the nearest such boundary."""
     p = vnorm_probabilities(Vh)
     cdf = np.cumsum(p)
-    u = vnorm_uniforms(seed, bh, m)
+    u = vnorm_uniforms(seed, bh, m, heap, n_heads)
     idx = np.minimum(np.searchsorted(cdf, u, side="right"), len(p) - 1).astype(np.int64)
     if margin is not None:
         lower = np.where(idx > 0, cdf[np.maximum(idx - 1, 0)], 0.0)
@@ -606,33 +610,75 @@ def alg2_head_forward(Qh, Kh, Vh, codes_q, codes_k, b, samples, t_rows, cap_scal
     return num, log_dt, log_tau
 
 
+def causal_forward_alg2(Q, K, V, codes_q, codes_k, b, n_min, node_draws, cap_scale, kappa, taus, level=0, node=0):
+    """Algorithm 4 with Algorithm 2 as printed at every off-diagonal node.  node_draws(level, node, s, V1)
+    returns (samples, rows of T, value draws or None) of the node; taus[heap] receives its log tau.
+    Returns (out, log D~) like causal_forward."""
+    n = Q.shape[0]
+    if n <= n_min:
+        return exact_attention(Q, K, V, causal=True)
+    h = n // 2
+    O1, L1 = causal_forward_alg2(Q[:h], K[:h], V[:h], codes_q[:h], codes_k[:h], b, n_min, node_draws, cap_scale, kappa,
+                                 taus, level + 1, 2 * node)
+    O22, L22 = causal_forward_alg2(Q[h:], K[h:], V[h:], codes_q[h:], codes_k[h:], b, n_min, node_draws, cap_scale,
+                                   kappa, taus, level + 1, 2 * node + 1)
+    samples, t_rows, vsamp = node_draws(level, node, h, V[:h])
+    O21, L21, log_tau = alg2_head_forward(Q[h:], K[:h], V[:h], codes_q[h:], codes_k[:h], b, samples, t_rows, cap_scale,
+                                          kappa, vsamp)
+    taus[(1 << level) - 1 + node] = log_tau
+    O2, L2 = merge_parts(O21, L21, O22, L22)                       # D~_21 + D~_C22
+    return np.concatenate([O1, O2]), np.concatenate([L1, L2])
+
+
 def hyperattn_forward_alg2(Q, K, V, b, m, r, seed=0, cap_scale=0.0, kappa=0.0, vnorm_sampling=False, R=None,
-                           vnorm_from=None, vnorm_replay=None):
-    """Unmasked HyperAttention with Algorithm 2's estimator as printed.  Returns (out, log d~, log tau [B*H]).
+                           vnorm_from=None, vnorm_replay=None, causal=False, n_min=4096):
+    """HyperAttention with Algorithm 2's estimator as printed.  Returns (out, log d~, log tau); log tau is
+    [B*H] for the unmasked problem and [B*H, nodes] (heap order) for the causal one, where every
+    off-diagonal node of Algorithm 4 runs Algorithm 2 with its own draws.
     vnorm_from: the value tensor whose row norms define Lemma 2's draws (default V itself; the tests
-    pass V when they evaluate the same draws on |V|); vnorm_replay: {bh: {r: l}} fixed draws."""
+    pass V when they evaluate the same draws on |V|); vnorm_replay: {(bh, heap): {r: l}} fixed draws
+    ({bh: {r: l}} is accepted for the unmasked problem)."""
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
     B, H, n, d = Q.shape
     if R is None:
         R = make_projection(seed, d, r)
-    samples = make_samples(seed, 0, 0, n, m)
-    t_rows = tau_rows(seed, n, m)
+    replay = vnorm_replay or {}
     out = np.empty_like(V)
     lse = np.empty((B, H, n))
-    taus = np.empty(B * H)
+    levels = 0
+    if causal:
+        while (n >> levels) > n_min:
+            levels += 1
+    taus = np.full((B * H, (1 << levels) - 1), -np.inf) if causal else np.empty(B * H)
+    Vsrc = V if vnorm_from is None else np.asarray(vnorm_from, dtype=np.float64)
     for bh in range(B * H):
         q, k, v = (x.reshape(B * H, n, -1)[bh] for x in (Q, K, V))
+        vsrc = Vsrc.reshape(B * H, n, -1)[bh]
         cq, ck = lsh_codes(lsh_project(q, R), r), lsh_codes(lsh_project(k, R), r)
-        vs = None
-        if vnorm_sampling:
-            vsrc = v if vnorm_from is None else np.asarray(vnorm_from, dtype=np.float64).reshape(B * H, n, -1)[bh]
-            vs = vnorm_samples(vsrc, seed, bh, m, replay=(vnorm_replay or {}).get(bh))
-        o, l, t = alg2_head_forward(q, k, v, cq, ck, b, samples, t_rows, cap_scale, kappa, vs)
+        if not causal:
+            vs = None
+            if vnorm_sampling:
+                vs = vnorm_samples(vsrc, seed, bh, m, replay=replay.get((bh, 0), replay.get(bh)))
+            o, l, t = alg2_head_forward(q, k, v, cq, ck, b, make_samples(seed, 0, 0, n, m), tau_rows(seed, n, m),
+                                        cap_scale, kappa, vs)
+            taus[bh] = t
+        else:
+            def node_draws(level, node, s, V1, bh=bh, vsrc=vsrc):
+                heap = (1 << level) - 1 + node
+                vs = None
+                if vnorm_sampling:
+                    k0 = 2 * node * s                              # the node's keys are rows [2 node s, (2 node + 1) s)
+                    vs = vnorm_samples(vsrc[k0:k0 + s], seed, bh, m, replay=replay.get((bh, heap)), heap=heap,
+                                       n_heads=B * H)
+                return make_samples(seed, level, node, s, m), tau_rows(seed, s, m, heap), vs
+            node_taus = {}
+            o, l = causal_forward_alg2(q, k, v, cq, ck, b, n_min, node_draws, cap_scale, kappa, node_taus)
+            for heap, t in node_taus.items():
+                taus[bh, heap] = t
         out.reshape(B * H, n, -1)[bh] = o
         lse.reshape(B * H, n)[bh] = l
-        taus[bh] = t
     return out, lse, taus
 
 

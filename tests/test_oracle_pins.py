@@ -565,6 +565,51 @@ def test_alg2_tau_cap_and_lower_cap_follow_their_definitions():
     assert (np.maximum(d_plain, tau / kappa) > d_plain).any()      # the lower cap binds somewhere in this instance
 
 
+def test_causal_alg2_is_algorithm4_over_algorithm2():
+    """Causal problems: with the caps off the result is the Section 4 causal forward (dense per-node
+    evaluation here, part by part there); at n <= n_min it is exact causal attention; the row sum of a
+    lower-half row is the node's D~ (a direct call of the node with that node's draws) plus the
+    diagonal block's; every node has its own T."""
+    n, d, b, m, r, n_min, seed = 128, 8, 8, 12, 4, 32, 6
+    Q, K, V = _alg2_inputs(n=n, d=d, seed=3)
+    plain = orc.hyperattn_forward(Q, K, V, b=b, m=m, r=r, causal=True, n_min=n_min, seed=seed)
+    got = orc.hyperattn_forward_alg2(Q, K, V, b=b, m=m, r=r, seed=seed, causal=True, n_min=n_min)
+    np.testing.assert_allclose(got[0], plain[0], rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(got[1], plain[1], rtol=1e-11, atol=1e-12)
+    assert got[2].shape == (1, 3) and np.isfinite(got[2]).all()          # two levels: nodes 0, 1, 2 in heap order
+    ex = orc.exact_attention(Q[0, 0], K[0, 0], V[0, 0], causal=True)
+    small = orc.hyperattn_forward_alg2(Q, K, V, b=b, m=m, r=r, seed=seed, causal=True, n_min=n, cap_scale=3.0, kappa=1.5)
+    np.testing.assert_allclose(small[0][0, 0], ex[0], rtol=1e-12)
+    assert small[2].shape == (1, 0)
+    # with caps: top split.  Lower half = node (Q_2, K_1, V_1) with the draws of (level 0, node 0), merged with
+    # the causal result of the lower-right block, itself the recursion on (Q_2, K_2, V_2) as nodes (1, 1), ...
+    cap_scale, kappa = 6.0, 1.3
+    out, lse, taus = orc.hyperattn_forward_alg2(Q, K, V, b=b, m=m, r=r, seed=seed, causal=True, n_min=n_min,
+                                                cap_scale=cap_scale, kappa=kappa, vnorm_sampling=True)
+    h = n // 2
+    q, k, v = Q[0, 0], K[0, 0], V[0, 0]
+    R = orc.make_projection(seed, d, r)
+    cq, ck = orc.lsh_codes(orc.lsh_project(q, R), r), orc.lsh_codes(orc.lsh_project(k, R), r)
+    vs = orc.vnorm_samples(v[:h], seed, 0, m, heap=0, n_heads=1)
+    O21, L21, t21 = orc.alg2_head_forward(q[h:], k[:h], v[:h], cq[h:], ck[:h], b, orc.make_samples(seed, 0, 0, h, m),
+                                          orc.tau_rows(seed, h, m, heap=0), cap_scale, kappa, vs)
+    assert abs(taus[0, 0] - t21) < 1e-12
+    # lower-right block on its own is a causal problem whose root is heap node 2 of the full problem: rebuild it
+    # from the full result by subtraction of row sums
+    L22 = np.log(np.exp(lse[0, 0, h:]) - np.exp(L21))
+    w21 = np.exp(L21 - lse[0, 0, h:])
+    O22 = (out[0, 0, h:] - w21[:, None] * O21) / (1.0 - w21)[:, None]
+    # its first quarter (rows h .. h + n_min) is an exact causal base block
+    ex22 = orc.exact_attention(q[h:h + n_min], k[h:h + n_min], v[h:h + n_min], causal=True)
+    np.testing.assert_allclose(L22[:n_min], ex22[1], rtol=1e-9, atol=1e-9)
+    np.testing.assert_allclose(O22[:n_min], ex22[0], rtol=1e-7, atol=1e-9)
+    # the caps act in this instance, and the nodes' subsets T differ
+    plain_v = orc.hyperattn_forward_alg2(Q, K, V, b=b, m=m, r=r, seed=seed, causal=True, n_min=n_min)
+    assert np.abs(plain_v[1] - lse).max() > 1e-3
+    assert not np.array_equal(orc.tau_rows(seed, 32, m, heap=1), orc.tau_rows(seed, 32, m, heap=2))
+    assert np.array_equal(orc.tau_rows(seed, 64, m, heap=0), orc.tau_rows(seed, 64, m))
+
+
 def test_tau_rows_are_uniform_and_independent_of_the_samples():
     """T of Algorithm 2: m uniform rows.  A chi-square test over many seeds pins the law (a biased or
     truncated draw fails it); T must also not repeat the estimator's own index set."""
