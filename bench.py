@@ -141,32 +141,39 @@ def sweep(args, torch, ha):
 
 def alg2_bench(args, torch, ha):
     """Algorithm 2 as printed (caps, tau) and Lemma 2's value sampling, the options beside the
-    Section 4 form, at the unmasked 32-head workload: time of each next to the main path's."""
-    name = "cfg2_n32k"
-    cfg = dict(synth_inputs.CONFIGS[name])
-    (Q, K, V), _ = device_inputs(cfg, torch)
-    B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
-    b, m, r = cfg["b"], cfg["m"], cfg["r"]
-    out, lse = torch.empty_like(Q), torch.empty((B, H, n), dtype=torch.float32, device="cuda")
-    shape = ha.make_shape(B, H, n, d, ha.HA_BF16)
-    ws = ha.alloc_workspace(shape, ha.make_params(b, m, r, False, cfg["n_min"], cfg["seed"]))
-    main_ms = time_call(torch, lambda: ha.hyperattn_forward(Q, K, V, b, m, r, seed=cfg["seed"], workspace=ws, out=out,
-                                                            lse=lse), args.warmup, args.steps)
-    res = {}
-    ws2 = None
-    for key, vn in (("caps_ms", False), ("caps_and_value_sampling_ms", True)):
-        kw = dict(seed=cfg["seed"], cap_scale=8.0, kappa=1.2, vnorm_sampling=vn, out=out, lse=lse)
-        _, _, ws2 = ha.hyperattn_forward_alg2(Q, K, V, b, m, r, workspace=ws2, **kw)
-        res[key] = round(time_call(torch, lambda: ha.hyperattn_forward_alg2(Q, K, V, b, m, r, workspace=ws2, **kw),
-                                   args.warmup, args.steps), 4)
-        log(f"[bench] {key}: {res[key]:.3f} ms (Section 4 form: {main_ms:.3f} ms)")
+    Section 4 form, at the unmasked 32-head workload and at the causal one of the same length (where
+    Algorithm 4 runs them at every off-diagonal node): time of each next to the main path's."""
+    points = {}
+    for name in ("cfg2_n32k", "cfg3_n32k_causal"):
+        cfg = dict(synth_inputs.CONFIGS[name])
+        (Q, K, V), _ = device_inputs(cfg, torch)
+        B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
+        b, m, r = cfg["b"], cfg["m"], cfg["r"]
+        out, lse = torch.empty_like(Q), torch.empty((B, H, n), dtype=torch.float32, device="cuda")
+        shape = ha.make_shape(B, H, n, d, ha.HA_BF16)
+        ckw = dict(causal=bool(cfg["causal"]), n_min=cfg["n_min"])
+        ws = ha.alloc_workspace(shape, ha.make_params(b, m, r, cfg["causal"], cfg["n_min"], cfg["seed"]))
+        main_ms = time_call(torch, lambda: ha.hyperattn_forward(Q, K, V, b, m, r, seed=cfg["seed"], workspace=ws, out=out,
+                                                                lse=lse, **ckw), args.warmup, args.steps)
+        res = {"section4_form_ms": round(main_ms, 4)}
+        ws2 = None
+        for key, vn in (("caps_ms", False), ("caps_and_value_sampling_ms", True)):
+            kw = dict(seed=cfg["seed"], cap_scale=8.0, kappa=1.2, vnorm_sampling=vn, out=out, lse=lse, **ckw)
+            _, _, ws2 = ha.hyperattn_forward_alg2(Q, K, V, b, m, r, workspace=ws2, **kw)
+            res[key] = round(time_call(torch, lambda: ha.hyperattn_forward_alg2(Q, K, V, b, m, r, workspace=ws2, **kw),
+                                       args.warmup, args.steps), 4)
+            log(f"[bench] {name} {key}: {res[key]:.3f} ms (Section 4 form: {main_ms:.3f} ms)")
+        points[name] = res
+        del Q, K, V, out, lse, ws, ws2
+    cfg = synth_inputs.CONFIGS["cfg2_n32k"]
     print(json.dumps({
-        "metric": "HyperAttention fwd ms", "value": res["caps_ms"], "unit": "ms", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": res["caps_ms"], "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": name, "B": B, "H": H, "n": n, "d": d, "b": b, "m": m, "r": r, "causal": False,
+        "metric": "HyperAttention fwd ms", "value": points["cfg2_n32k"]["caps_ms"], "unit": "ms", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": points["cfg2_n32k"]["caps_ms"],
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg2_n32k", "B": cfg["B"], "H": cfg["H"], "n": cfg["n"], "d": cfg["d"], "b": cfg["b"],
+                   "m": cfg["m"], "r": cfg["r"], "causal": False,
                    "estimator": "Algorithm 2 as printed: cap_scale 8, kappa 1.2"},
-        "section4_form_ms": round(main_ms, 4), **res}), flush=True)
+        **points["cfg2_n32k"], "also_cfg3_n32k_causal": points["cfg3_n32k_causal"]}), flush=True)
 
 
 def backward_bench(args, torch, ha):

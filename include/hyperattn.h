@@ -293,9 +293,13 @@ size_t exact_attn_backward_workspace_bytes(const ha_shape* shape);
 
 /* ------------------------------------------------------------------------
  * Algorithm 2 as printed and Lemma 2 / Algorithm 3, as options (the Section 4
- * form above leaves them out).  Unmasked problems only (params->causal must be
- * 0); both dtypes (bf16 tensors on the matrix cores, weights rounded to bf16
- * as operands like in the forward; fp32 tensors in plain fp32 arithmetic).
+ * form above leaves them out); both dtypes (bf16 tensors on the matrix cores,
+ * weights rounded to bf16 as operands like in the forward; fp32 tensors in
+ * plain fp32 arithmetic).  Causal problems run them at every off-diagonal node of
+ * Algorithm 4 ("the unmasked algorithm on Q_2, K_1"): below, n is then the
+ * node's size s, every node has its own subset T, index set and value rows
+ * (counters offset by the node's heap index 2^level - 1 + node), the diagonal
+ * blocks are exact and the results are added up as in hyperattn_forward.
  *   tau   = max over m rows drawn uniformly (with replacement) of the unmasked row sum
  *   C_i   = cap_scale * m / (n ln n) * (masked row sum_i + tau / kappa)     cap_scale <= 0: no cap
  *   d_i   = (n/m) sum_j (1 - M_{i,l_j}) min(exp<q_i,k_{l_j}>, C_i)
@@ -306,10 +310,13 @@ size_t exact_attn_backward_workspace_bytes(const ha_shape* shape);
  * kappa) are the caller's.  Lemma 2's rows are drawn with p_l = |V_l|^2 / |V|_F^2
  * by inverting the cumulative distribution in fp64 (draw r of head bh: first l
  * whose inclusive prefix sum of squared norms exceeds u |V|_F^2, u in (0,1) from
- * the top 53 bits of counter bh*m + r of stream 2).
+ * the top 53 bits of counter (heap * B*H + bh) * m + r of stream 2; T uses counter
+ * heap * m + j of stream 0).
  * workspace: device, 256-byte aligned, >= ha_alg2_workspace_bytes(); it starts
- * with the forward's layout (ha_workspace_layout) followed by the regions below.
- * Errors as hyperattn_forward, plus HA_ERR_SHAPE for causal params. */
+ * with the forward's layout (ha_workspace_layout) followed by the regions below
+ * ("per level": sized for the largest level and reused from level to level, so
+ * after the call they hold the last, deepest level; "per node": every node of
+ * every level, nodes in heap order).  Errors as hyperattn_forward. */
 typedef struct {
   float cap_scale;
   float kappa;
@@ -318,15 +325,15 @@ typedef struct {
 
 typedef struct {
   size_t forward_bytes;      /* the forward's regions come first */
-  size_t pos_q;              /* int32 [B*H][n]: inverse of perm_q */
-  size_t tau_rows;           /* int32 [m]: the rows of T */
-  size_t log_unmasked_t;     /* float [B*H][m]: log of their unmasked row sums */
-  size_t log_tau;            /* float [B*H] */
-  size_t vnorm_w;            /* double [B*H][n]: |V_l|^2 */
-  size_t vnorm_prefix;       /* double [B*H][n]: inclusive prefix sums of |V_l|^2 */
-  size_t vnorm_samples;      /* int32 [B*H][m]: l'_r */
-  size_t vnorm_logw;         /* float [B*H][m]: log(1 / (m p_{l'_r})) */
-  size_t log_unmasked_parts; /* float [8][B*H][m]: scratch, the unmasked row sums of T over eight ranges of keys */
+  size_t pos_q;              /* per level, int32 [B*H][n_cov]: inverse of perm_q within the node */
+  size_t tau_rows;           /* per node, int32 [total_nodes][m]: the rows of T (node-local) */
+  size_t log_unmasked_t;     /* per level, float [B*H * nodes][m]: log of their unmasked row sums */
+  size_t log_tau;            /* per node, float [B*H][total_nodes] */
+  size_t vnorm_w;            /* per level, double [B*H][n_cov]: |V_l|^2 of the nodes' value rows */
+  size_t vnorm_prefix;       /* per level, double [B*H][n_cov]: inclusive prefix sums within the node */
+  size_t vnorm_samples;      /* per node, int32 [B*H][total_nodes][m]: l'_r (node-local) */
+  size_t vnorm_logw;         /* per node, float [B*H][total_nodes][m]: log(1 / (m p_{l'_r})) */
+  size_t log_unmasked_parts; /* per level, float [8][B*H * nodes][m]: scratch, the unmasked row sums of T over eight ranges of keys */
   size_t total_bytes;
 } ha_alg2_ws_layout;
 

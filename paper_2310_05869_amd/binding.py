@@ -585,15 +585,15 @@ def ha_alg2_workspace_layout(shape: HaShape, params: HaParams) -> HaAlg2WsLayout
 
 
 def hyperattn_forward_alg2(Q, K, V, b, m, r, seed=0, cap_scale=0.0, kappa=0.0, vnorm_sampling=False, workspace=None,
-                           out=None, lse=None, stream=None):
-    """Unmasked HyperAttention with Algorithm 2's caps and, optionally, Lemma 2's value
-    sampling by squared row norm.  Returns (out, log d~, workspace)."""
+                           out=None, lse=None, stream=None, causal=False, n_min=4096):
+    """HyperAttention with Algorithm 2's caps and, optionally, Lemma 2's value sampling by squared
+    row norm (at every off-diagonal node of Algorithm 4 when causal).  Returns (out, log d~, workspace)."""
     torch = _torch()
     _expect_qkv(Q, K=K, V=V, out=out)
     _expect_f32(Q, tuple(Q.shape[:3]), lse=lse)
     B, H, n, d = Q.shape
     shape = make_shape(B, H, n, d, _dtype_code(Q))
-    params = make_params(b, m, r, False, 4096, seed)
+    params = make_params(b, m, r, causal, n_min, seed)
     if workspace is None:
         workspace = torch.empty(int(ha_alg2_workspace_layout(shape, params).total_bytes), dtype=torch.uint8,
                                 device=Q.device)
@@ -610,18 +610,20 @@ def hyperattn_forward_alg2(Q, K, V, b, m, r, seed=0, cap_scale=0.0, kappa=0.0, v
 
 
 def alg2_workspace_views(workspace, shape: HaShape, params: HaParams):
-    """Typed views of the option kernels' regions after hyperattn_forward_alg2."""
+    """Typed views of the option kernels' regions after hyperattn_forward_alg2: the per-node regions
+    (nodes in heap order), and vnorm_w of the last level processed (the only level of an unmasked problem)."""
     torch = _torch()
     lay = ha_alg2_workspace_layout(shape, params)
-    BH, n, m = shape.B * shape.H, shape.n, params.m
+    fwd = ha_workspace_layout(shape, params)
+    BH, m, nodes = shape.B * shape.H, params.m, fwd.total_nodes
 
     def view(off, count, dtype, shp):
         nbytes = count * torch.empty((), dtype=dtype).element_size()
         return workspace[off:off + nbytes].view(dtype).view(shp)
 
     return {"layout": lay,
-            "tau_rows": view(lay.tau_rows, m, torch.int32, (m,)),
-            "log_tau": view(lay.log_tau, BH, torch.float32, (BH,)),
-            "vnorm_w": view(lay.vnorm_w, BH * n, torch.float64, (BH, n)),
-            "vnorm_samples": view(lay.vnorm_samples, BH * m, torch.int32, (BH, m)),
-            "vnorm_logw": view(lay.vnorm_logw, BH * m, torch.float32, (BH, m))}
+            "tau_rows": view(lay.tau_rows, nodes * m, torch.int32, (nodes, m)),
+            "log_tau": view(lay.log_tau, BH * nodes, torch.float32, (BH, nodes)),
+            "vnorm_w": view(lay.vnorm_w, BH * fwd.n_cov, torch.float64, (BH, fwd.n_cov)),
+            "vnorm_samples": view(lay.vnorm_samples, BH * nodes * m, torch.int32, (BH, nodes, m)),
+            "vnorm_logw": view(lay.vnorm_logw, BH * nodes * m, torch.float32, (BH, nodes, m))}

@@ -7,15 +7,16 @@
 //   out_i    = (1 / d~_i) sum_r exp<q_i,k_{l'_r}> v_{l'_r} / (m p_{l'_r}),  l'_r ~ p_l ~ |V_l|^2   (Lemma 2)
 //         or = (1 / d~_i) (masked part + (n/m) sum_j (1 - M) exp<q_i,k_{l_j}> v_{l_j})                (Section 4)
 // The constants the paper leaves open (the Theta in C_i, kappa) are the caller's.
-// Unmasked problems only.  The kernels here are plain fp32 FMA code (one thread per query row,
+// A launch sequence handles one level of nodes (alg2_common.h): the unmasked problem, or one
+// level of Algorithm 4's off-diagonal nodes, every node with its own draws.  The kernels here are plain fp32 FMA code (one thread per query row,
 // K / V rows staged through LDS): they serve fp32 tensors and whatever the bf16 matrix-core
 // forms of the two heavy steps (alg2_mfma.hip) do not take; the draws, weights and prefix
 // sums are computed here for both.
 //
-// Lemma 2's rows are drawn with p_l = |V_l|^2 / |V|_F^2 by inverting the
-// cumulative distribution in fp64: draw r of head bh takes the uniform u in
-// (0, 1) formed by the top 53 bits of counter bh * m + r of stream 2 and is the
-// first l whose inclusive prefix sum of squared norms exceeds u |V|_F^2.
+// Lemma 2's rows are drawn with p_l = |V_l|^2 / |V|_F^2 (V the node's value rows) by inverting
+// the cumulative distribution in fp64: draw r of head bh at the node with heap index h takes the
+// uniform u in (0, 1) formed by the top 53 bits of counter (h * heads + bh) * m + r of stream 2
+// and is the first l whose inclusive prefix sum of squared norms exceeds u |V|_F^2.
 #include "attn_common.h"
 #include "alg2_common.h"
 
@@ -36,14 +37,18 @@ __device__ inline float elem<uint16_t>(const uint16_t* p) { return __uint_as_flo
 __global__ void alg2_prep_kernel(Alg2Args a) {
   const Geometry& g = a.g;
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (t < g.m) {
-    const uint64_t hi = rand_u64(a.seed, kStreamTauRows, (uint64_t)t) >> 32;
-    a.tau_rows[t] = (int32_t)((hi * (uint64_t)g.n) >> 32);
+  // rows of T of every node of this level: counter heap * m + j of the stream
+  if (t < (int64_t)a.nodes * g.m) {
+    const int node = (int)(t / g.m), j = (int)(t % g.m);
+    const int heap = (1 << a.level) - 1 + node;
+    const uint64_t hi = rand_u64(a.seed, kStreamTauRows, (uint64_t)heap * g.m + j) >> 32;
+    a.tau_rows[(int64_t)heap * g.m + j] = (int32_t)((hi * (uint64_t)g.n) >> 32);
   }
-  // pos_q = P_Q^-1
+  // pos_q = P_Q^-1, node-local
   if (t < (int64_t)g.BH * g.n) {
-    const int64_t bh = t / g.n;
-    a.pos_q[bh * g.n + a.perm_q[t]] = (int32_t)(t % g.n);
+    const int vh = (int)(t / g.n);
+    const Alg2Node nd = alg2_node(a, vh);
+    a.pos_q[(int64_t)vh * g.n + (a.perm_q[t] - nd.q_start)] = (int32_t)(t % g.n);
   }
 }
 
@@ -57,10 +62,15 @@ __global__ __launch_bounds__(256) void vnorm_weight_kernel(Alg2Args a) {
   constexpr int kStride = kRowBytes + 4;  // odd number of words: the 64 row readers hit 64 banks
   __shared__ __attribute__((aligned(16))) unsigned char tile[kVwRows * kStride];
   const Geometry& g = a.g;
-  const int64_t rows = (int64_t)g.BH * g.n;
-  const int64_t row0 = (int64_t)blockIdx.x * kVwRows;
-  const int nrows = (int)min((int64_t)kVwRows, rows - row0);
-  const unsigned char* src = reinterpret_cast<const unsigned char*>(a.V) + row0 * kRowBytes;
+  // one workgroup per 64 consecutive keys of one node (g.n need not be a multiple of 64)
+  const int per_node = (g.n + kVwRows - 1) / kVwRows;
+  const int vh = blockIdx.x / per_node;
+  const int l0 = (blockIdx.x % per_node) * kVwRows;
+  const Alg2Node nd = alg2_node(a, vh);
+  const int nrows = min(kVwRows, g.n - l0);
+  const int64_t row0 = (int64_t)vh * g.n + l0;   // in the view
+  const unsigned char* src = reinterpret_cast<const unsigned char*>(a.V) +
+                             ((int64_t)nd.head * a.n_full + nd.k_start + l0) * kRowBytes;
   for (int e = threadIdx.x; e < nrows * (kRowBytes / 4); e += 256) {
     const int r = e / (kRowBytes / 4), w = e % (kRowBytes / 4);
     *reinterpret_cast<uint32_t*>(tile + r * kStride + 4 * w) = *reinterpret_cast<const uint32_t*>(src + (int64_t)e * 4);
@@ -112,10 +122,12 @@ __global__ void vnorm_sample_kernel(Alg2Args a) {
   const Geometry& g = a.g;
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= (int64_t)g.BH * g.m) return;
-  const int bh = (int)(t / g.m);
-  const double* prefix = a.vprefix + (int64_t)bh * g.n;
+  const int vh = (int)(t / g.m), r = (int)(t % g.m);
+  const Alg2Node nd = alg2_node(a, vh);
+  const double* prefix = a.vprefix + (int64_t)vh * g.n;
   const double total = prefix[g.n - 1];
-  const double u = ((double)(rand_u64(a.seed, kStreamVnorm, (uint64_t)t) >> 11) + 0.5) * 0x1.0p-53;
+  const uint64_t ctr = ((uint64_t)nd.heap * a.heads + nd.head) * g.m + r;
+  const double u = ((double)(rand_u64(a.seed, kStreamVnorm, ctr) >> 11) + 0.5) * 0x1.0p-53;
   int lo;
   double p;
   if (total > 0.0) {
@@ -127,13 +139,14 @@ __global__ void vnorm_sample_kernel(Alg2Args a) {
       if (prefix[mid] > target) hi = mid;
       else lo = mid + 1;
     }
-    p = a.vw[(int64_t)bh * g.n + lo] / total;
+    p = a.vw[(int64_t)vh * g.n + lo] / total;
   } else {  // V = 0: every choice gives the same (zero) product; uniform
     lo = min(g.n - 1, (int)(u * (double)g.n));
     p = 1.0 / (double)g.n;
   }
-  a.vsamp[t] = lo;
-  a.vlogw[t] = (float)(-log((double)g.m * p));
+  const int64_t at = ((int64_t)nd.head * a.total_nodes + nd.heap) * g.m + r;
+  a.vsamp[at] = lo;
+  a.vlogw[at] = (float)(-log((double)g.m * p));
 }
 
 // log of the unmasked row sum of the rows T_j: one workgroup per head and kTauRows of them.
@@ -156,15 +169,17 @@ __global__ __launch_bounds__(256) void alg2_tau_kernel(Alg2Args a) {
   const int groups_per_head = (g.m + kTauRows - 1) / kTauRows;
   const int bh = blockIdx.x / groups_per_head, j0 = (blockIdx.x % groups_per_head) * kTauRows;
   const int nr = min(kTauRows, g.m - j0);
-  const int64_t hb = (int64_t)bh * g.n;
-  const T* Qh = reinterpret_cast<const T*>(a.Q) + hb * D;
-  const unsigned char* Kh = reinterpret_cast<const unsigned char*>(a.K) + hb * kRowBytes;
+  const int64_t hb = (int64_t)bh * g.n;   // bh: view head (one node)
+  const Alg2Node nd = alg2_node(a, bh);
+  const int32_t* trows = a.tau_rows + (int64_t)nd.heap * g.m;
+  const T* Qh = reinterpret_cast<const T*>(a.Q) + ((int64_t)nd.head * a.n_full + nd.q_start) * D;
+  const unsigned char* Kh = reinterpret_cast<const unsigned char*>(a.K) + ((int64_t)nd.head * a.n_full + nd.k_start) * kRowBytes;
   const int tid = threadIdx.x;
   for (int e = tid; e < kTauRows * D; e += 256) {
     const int r = e / D, c = e % D;
-    qs[r][c] = r < nr ? elem<T>(Qh + (int64_t)a.tau_rows[j0 + r] * D + c) : 0.f;
+    qs[r][c] = r < nr ? elem<T>(Qh + (int64_t)trows[j0 + r] * D + c) : 0.f;
   }
-  if (tid < kTauRows) blk_of[tid] = tid < nr ? a.pos_q[hb + a.tau_rows[j0 + tid]] / g.b : -1;
+  if (tid < kTauRows) blk_of[tid] = tid < nr ? a.pos_q[hb + trows[j0 + tid]] / g.b : -1;
   const int k = tid % kKeys, grp = tid / kKeys;
   float mx[kRpt], sum[kRpt];
 #pragma unroll
@@ -269,7 +284,10 @@ __global__ __launch_bounds__(256) void alg2_tau_max_kernel(Alg2Args a) {
     if ((int)threadIdx.x < s) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + s]);
     __syncthreads();
   }
-  if (threadIdx.x == 0) a.log_tau[bh] = red[0];
+  if (threadIdx.x == 0) {
+    const Alg2Node nd = alg2_node(a, bh);
+    a.log_tau[(int64_t)nd.head * a.total_nodes + nd.heap] = red[0];
+  }
 }
 
 constexpr int kA2Rows = 64;  // query rows (threads) per workgroup
@@ -290,11 +308,13 @@ __global__ __launch_bounds__(kA2Rows) void alg2_main_kernel(Alg2Args a) {
   const int t = tile / tpb, chunk = tile % tpb;
   const int p0 = t * g.b + chunk * kA2Rows;
   const bool valid = chunk * kA2Rows + tid < g.b;
-  const int64_t hb = (int64_t)bh * g.n;
+  const int64_t hb = (int64_t)bh * g.n;   // bh: view head (one node); perm values are rows of the real head
+  const Alg2Node nd = alg2_node(a, bh);
   const int qrow = a.perm_q[hb + (valid ? p0 + tid : p0)];
-  const T* Qh = reinterpret_cast<const T*>(a.Q) + hb * D;
-  const T* Kh = reinterpret_cast<const T*>(a.K) + hb * D;
-  const T* Vh = reinterpret_cast<const T*>(a.V) + hb * D;
+  const T* Qh = reinterpret_cast<const T*>(a.Q) + (int64_t)nd.head * a.n_full * D;
+  const T* Kh = reinterpret_cast<const T*>(a.K) + (int64_t)nd.head * a.n_full * D;
+  const T* Vh = reinterpret_cast<const T*>(a.V) + (int64_t)nd.head * a.n_full * D;
+  const int64_t draws = ((int64_t)nd.head * a.total_nodes + nd.heap) * g.m;   // this node's entries of the per-node arrays
 
   float q[D], o[D];
 #pragma unroll
@@ -306,7 +326,7 @@ __global__ __launch_bounds__(kA2Rows) void alg2_main_kernel(Alg2Args a) {
   float msum = 0.f;         // masked row sum / e^M
   float dsum = 0.f;         // sum of (capped) kept samples / e^M
   const float ratio = g.m > 0 ? (float)g.n / (float)g.m : 0.f;
-  const float log_tau = a.log_tau[bh];
+  const float log_tau = a.log_tau[(int64_t)nd.head * a.total_nodes + nd.heap];
   const float floor_term = a.kappa > 0.f ? log_tau - logf(a.kappa) : -INFINITY;
 
   auto rescale_to = [&](float m_new) {
@@ -359,8 +379,8 @@ __global__ __launch_bounds__(kA2Rows) void alg2_main_kernel(Alg2Args a) {
     const int cnt = min(kA2Tile, g.m - j0);
     __syncthreads();
     if (tid < cnt) {
-      rows[tid] = a.samples[j0 + tid];
-      bias[tid] = (a.samp_blk[(int64_t)bh * g.m + j0 + tid] == t) ? -INFINITY : 0.f;  // factor 1 - M_{i,l_j}
+      rows[tid] = nd.k_start + a.samples[(int64_t)nd.heap * g.m + j0 + tid];
+      bias[tid] = (a.samp_blk[draws + j0 + tid] == t) ? -INFINITY : 0.f;  // factor 1 - M_{i,l_j}
     }
     __syncthreads();
     stage(cnt, !a.vnorm);
@@ -386,8 +406,8 @@ __global__ __launch_bounds__(kA2Rows) void alg2_main_kernel(Alg2Args a) {
       const int cnt = min(kA2Tile, g.m - j0);
       __syncthreads();
       if (tid < cnt) {
-        rows[tid] = a.vsamp[(int64_t)bh * g.m + j0 + tid];
-        bias[tid] = a.vlogw[(int64_t)bh * g.m + j0 + tid];
+        rows[tid] = nd.k_start + a.vsamp[draws + j0 + tid];
+        bias[tid] = a.vlogw[draws + j0 + tid];
       }
       __syncthreads();
       stage(cnt, true);
@@ -408,7 +428,7 @@ __global__ __launch_bounds__(kA2Rows) void alg2_main_kernel(Alg2Args a) {
   const float log_dt = logaddexpf(log_masked, fmaxf(log_d, floor_term));
   const float f = (M == -INFINITY || log_dt == -INFINITY) ? 0.f : expf(M - log_dt);
   if (!valid) return;
-  const int64_t orow = hb + qrow;
+  const int64_t orow = hb + (qrow - nd.q_start);
   a.lse[orow] = log_dt;
   if (sizeof(T) == 4) {
     float* op = reinterpret_cast<float*>(a.out) + orow * D;
@@ -428,11 +448,10 @@ static int launch_alg2_t(const Alg2Args& a_in, hipStream_t st) {
   const bool mfma = alg2_mfma_supported(a);
   a.tau_splits = mfma ? kAlg2TauSplits : 0;
   const int64_t rows = (int64_t)g.BH * g.n;
-  int64_t prep = rows > g.m ? rows : g.m;
-  if (prep < g.BH) prep = g.BH;
+  int64_t prep = rows > (int64_t)a.nodes * g.m ? rows : (int64_t)a.nodes * g.m;
   hipLaunchKernelGGL(alg2_prep_kernel, dim3((unsigned)((prep + 255) / 256)), dim3(256), 0, st, a);
   if (a.vnorm && g.m > 0) {
-    const unsigned vw_grid = (unsigned)((rows + kVwRows - 1) / kVwRows);
+    const unsigned vw_grid = (unsigned)((int64_t)g.BH * ((g.n + kVwRows - 1) / kVwRows));
     if (g.d == 128) hipLaunchKernelGGL((vnorm_weight_kernel<T, 128>), dim3(vw_grid), dim3(256), 0, st, a);
     else hipLaunchKernelGGL((vnorm_weight_kernel<T, 64>), dim3(vw_grid), dim3(256), 0, st, a);
     hipLaunchKernelGGL(vnorm_scan_kernel, dim3((unsigned)g.BH), dim3(kScanThreads), 0, st, a);

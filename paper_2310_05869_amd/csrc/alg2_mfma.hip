@@ -112,17 +112,22 @@ __global__ __launch_bounds__(kA2NT, 2) void alg2_mfma_kernel(Alg2Args a) {
     j0 = (rest % per_head) * kA2QT;
     rows_valid = min(kA2QT, g.m - j0);
   }
+  // bh is a view head: one node of the level (alg2_common.h).  Row indices below are rows of the
+  // real head (permutation entries already are; node-local draws get the node's first row added).
   const int64_t hb = (int64_t)bh * g.n;
-  const uint16_t* Qh = reinterpret_cast<const uint16_t*>(a.Q) + hb * D;
-  const uint16_t* Kh = reinterpret_cast<const uint16_t*>(a.K) + hb * D;
-  const uint16_t* Vh = reinterpret_cast<const uint16_t*>(a.V) + hb * D;
+  const Alg2Node nd = alg2_node(a, bh);
+  const int64_t draws = ((int64_t)nd.head * a.total_nodes + nd.heap) * g.m;
+  const uint16_t* Qh = reinterpret_cast<const uint16_t*>(a.Q) + (int64_t)nd.head * a.n_full * D;
+  const uint16_t* Kh = reinterpret_cast<const uint16_t*>(a.K) + (int64_t)nd.head * a.n_full * D;
+  const uint16_t* Vh = reinterpret_cast<const uint16_t*>(a.V) + (int64_t)nd.head * a.n_full * D;
 
   // ---- this lane's query row: B operand of S^T = K Q^T, kept in registers ----
   const int r_in_tile = wave * 32 + lq;
   const bool valid = r_in_tile < rows_valid;
   const int r_use = valid ? r_in_tile : 0;
-  const int qrow = (ROLE == kA2Main) ? a.perm_q[hb + p0 + r_use] : a.tau_rows[j0 + r_use];
-  const int my_blk = (ROLE == kA2Tau) ? a.pos_q[hb + qrow] / g.b : 0;
+  const int qrow = (ROLE == kA2Main) ? a.perm_q[hb + p0 + r_use]
+                                     : nd.q_start + a.tau_rows[(int64_t)nd.heap * g.m + j0 + r_use];
+  const int my_blk = (ROLE == kA2Tau) ? a.pos_q[hb + (qrow - nd.q_start)] / g.b : 0;
   bf16x8 qreg[KS];
   {
     const u32x4* qp = reinterpret_cast<const u32x4*>(Qh + (int64_t)qrow * D + 8 * h);
@@ -150,24 +155,25 @@ __global__ __launch_bounds__(kA2NT, 2) void alg2_mfma_kernel(Alg2Args a) {
     for (int j = tid; j < nB * kA2KT; j += kA2NT) {
       int e = ~0;
       if (j < g.m) {
-        const int row = a.samples[j];
-        e = (a.samp_blk[(int64_t)bh * g.m + j] == t) ? ~row : row;  // factor 1 - M_{i,l_j}
+        const int row = nd.k_start + a.samples[(int64_t)nd.heap * g.m + j];
+        e = (a.samp_blk[draws + j] == t) ? ~row : row;  // factor 1 - M_{i,l_j}
       }
       lb[j] = e;
     }
     for (int j = tid; j < nC * kA2KT; j += kA2NT) {
-      lc[j] = (j < g.m) ? a.vsamp[(int64_t)bh * g.m + j] : ~0;
-      bc[j] = (j < g.m) ? a.vlogw[(int64_t)bh * g.m + j] * kLog2e : 0.f;
+      lc[j] = (j < g.m) ? nd.k_start + a.vsamp[draws + j] : ~0;
+      bc[j] = (j < g.m) ? a.vlogw[draws + j] * kLog2e : 0.f;
     }
     __syncthreads();
   }
   const float ratio = g.m > 0 ? (float)g.n / (float)g.m : 1.f;
   const float log2ratio = log2f(ratio);
-  const float floor_term = (ROLE == kA2Main && a.kappa > 0.f) ? a.log_tau[bh] - logf(a.kappa) : -INFINITY;
+  const float floor_term = (ROLE == kA2Main && a.kappa > 0.f)
+                               ? a.log_tau[(int64_t)nd.head * a.total_nodes + nd.heap] - logf(a.kappa) : -INFINITY;
   auto need_v = [&](int kt) -> bool { return ROLE == kA2Main && (a.vnorm ? kt >= nA + nB : true); };
 
   // ---- tile movers (buffer loads: rows past the head read as zeros and are left out by their entries) ----
-  const uint32_t head_bytes = (uint32_t)(g.n * (D * 2));
+  const uint32_t head_bytes = (uint32_t)(a.n_full * (D * 2));
   const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc((void*)Kh, 0, (int)head_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t vrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)Vh, 0, (int)head_bytes, 0x00020000);
   u32x4 kreg[NKC], vreg[NKC];
@@ -185,7 +191,7 @@ __global__ __launch_bounds__(kA2NT, 2) void alg2_mfma_kernel(Alg2Args a) {
         soff = 0;
       } else {
         voff = key * (D * 2) + col * 16;
-        soff = (kt * kA2KT) * (D * 2);
+        soff = (nd.k_start + kt * kA2KT) * (D * 2);   // keys past the node's end are left out through kblk
       }
       kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krsrc, voff, soff, 0);
       if (with_v) vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vrsrc, voff, soff, 0);
@@ -352,7 +358,7 @@ __global__ __launch_bounds__(kA2NT, 2) void alg2_mfma_kernel(Alg2Args a) {
   const float log_d = (dt_ > 0.f) ? (m_run + log2f(dt_)) * kLn2 : -INFINITY;
   const float log_dt = a2_logaddexp(log_masked, fmaxf(log_d, floor_term));   // d~_i = masked + max(d_i, tau / kappa)
   const float f = (m_run == -INFINITY || log_dt == -INFINITY) ? 0.f : expf(m_run * kLn2 - log_dt);
-  const int64_t out_row = hb + qrow;
+  const int64_t out_row = hb + (qrow - nd.q_start);
   if (valid && h == 0) a.lse[out_row] = log_dt;
 
   // the wave's 32 rows leave through an fp32 LDS transpose as whole 16-byte pieces

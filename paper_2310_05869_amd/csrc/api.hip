@@ -170,6 +170,31 @@ static int run_attention(const AttnArgs& a, int mode, hipStream_t st) {
   return use_mfma(a.g) ? launch_attn_mfma(a, mode, st) : launch_attn_generic(a, mode, st);
 }
 
+// Algorithm 4's diagonal blocks: exact causal attention on every block of base_len rows, whose
+// epilogue adds the row sums and outputs of the off-diagonal nodes (part_o / part_l of every level).
+static int run_base_case(const void* Q, const void* K, const void* V, void* out, float* lse, float* out_f32,
+                         const Geometry& g, void* part_o, float* part_l, hipStream_t st) {
+  const int64_t head_stride = (int64_t)g.n * g.d;
+  AttnArgs a{};
+  a.Q = Q;
+  a.K = K;
+  a.V = V;
+  a.q_bh_stride = a.k_bh_stride = head_stride;
+  a.out = out;
+  a.lse = lse;
+  a.out_f32 = out_f32;
+  a.out_bh_stride = head_stride;
+  a.part_o = part_o;
+  a.part_l = part_l;
+  a.part_bf16 = g.dtype == HA_BF16;
+  a.g = g;
+  a.exact_rows_q = a.exact_rows_k = g.n;
+  a.exact_block = g.base_len;
+  a.exact_causal = 1;
+  a.merge_levels = g.levels;
+  return run_attention(a, kModeExact, st);
+}
+
 // ev, when non-null, receives 6 events recorded on the stream: start, after
 // prep, after hashing, after sorting, after the node attention, after the base case.
 static int forward_impl(const void* Q, const void* K, const void* V, void* out, float* lse, const ha_shape* sh,
@@ -254,24 +279,7 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
   }
   mark(4);
   if (g.causal) {
-    AttnArgs a{};
-    a.Q = Q;
-    a.K = K;
-    a.V = V;
-    a.q_bh_stride = a.k_bh_stride = head_stride;
-    a.out = out;
-    a.lse = lse;
-    a.out_f32 = out_f32;
-    a.out_bh_stride = head_stride;
-    a.part_o = part_o;
-    a.part_l = part_l;
-    a.part_bf16 = g.dtype == HA_BF16;
-    a.g = g;
-    a.exact_rows_q = a.exact_rows_k = g.n;
-    a.exact_block = g.base_len;
-    a.exact_causal = 1;
-    a.merge_levels = g.levels;
-    rc = run_attention(a, kModeExact, st);
+    rc = run_base_case(Q, K, V, out, lse, out_f32, g, part_o, part_l, st);
     if (rc != HA_OK) return rc;
   }
   mark(5);
@@ -464,25 +472,22 @@ static void fill_alg2_layout(const Geometry& g, const ha_ws_layout& fwd, ha_alg2
     off = align256(off + bytes);
     return at;
   };
-  const size_t rows = (size_t)g.BH * g.n;
+  // per-level regions are sized for the largest level and reused from level to level;
+  // per-node regions hold every node of every level
+  const size_t view = (size_t)g.BH * g.n_cov;                                   // rows of one level
+  const size_t max_nodes = g.levels > 0 ? ((size_t)1 << (g.causal ? g.levels - 1 : 0)) : 0;
+  const size_t nodes_all = (size_t)g.BH * g.total_nodes;
   l->forward_bytes = fwd.total_bytes;
-  l->pos_q = take(rows * 4);
-  l->tau_rows = take((size_t)g.m * 4);
-  l->log_unmasked_t = take((size_t)g.BH * g.m * 4);
-  l->log_tau = take((size_t)g.BH * 4);
-  l->vnorm_w = take(rows * 8);
-  l->vnorm_prefix = take(rows * 8);
-  l->vnorm_samples = take((size_t)g.BH * g.m * 4);
-  l->vnorm_logw = take((size_t)g.BH * g.m * 4);
-  l->log_unmasked_parts = take((size_t)kAlg2TauSplits * g.BH * g.m * 4);
+  l->pos_q = take(view * 4);
+  l->tau_rows = take((size_t)g.total_nodes * g.m * 4);
+  l->log_unmasked_t = take((size_t)g.BH * max_nodes * g.m * 4);
+  l->log_tau = take(nodes_all * 4);
+  l->vnorm_w = take(view * 8);
+  l->vnorm_prefix = take(view * 8);
+  l->vnorm_samples = take(nodes_all * g.m * 4);
+  l->vnorm_logw = take(nodes_all * g.m * 4);
+  l->log_unmasked_parts = take((size_t)kAlg2TauSplits * g.BH * max_nodes * g.m * 4);
   l->total_bytes = off;
-}
-
-static int alg2_geometry(const ha_shape* sh, const ha_params* p, Geometry* g) {
-  const int rc = make_geometry(sh, p, g);
-  if (rc != HA_OK) return rc;
-  if (g->causal) return HA_ERR_SHAPE;  // Algorithms 2 and 3 are stated for the unmasked problem
-  return HA_OK;
 }
 
 }  // namespace ha
@@ -819,7 +824,7 @@ size_t exact_attn_backward_workspace_bytes(const ha_shape* sh) {
 int ha_alg2_workspace_layout(const ha_shape* shape, const ha_params* params, ha_alg2_ws_layout* layout) {
   if (!layout) return HA_ERR_NULL;
   Geometry g;
-  const int rc = alg2_geometry(shape, params, &g);
+  const int rc = make_geometry(shape, params, &g);
   if (rc != HA_OK) return rc;
   ha_ws_layout fwd;
   fill_layout(g, &fwd);
@@ -837,7 +842,7 @@ int hyperattn_forward_alg2(const void* Q, const void* K, const void* V, void* ou
                            size_t workspace_bytes, void* stream) {
   if (!opt) return HA_ERR_NULL;
   Geometry g;
-  int rc = alg2_geometry(shape, params, &g);
+  int rc = make_geometry(shape, params, &g);
   if (rc != HA_OK) return rc;
   if (g.BH == 0 || g.n == 0) return HA_OK;
   if (!Q || !K || !V || !out || !lse || !workspace) return HA_ERR_NULL;
@@ -849,50 +854,74 @@ int hyperattn_forward_alg2(const void* Q, const void* K, const void* V, void* ou
   if (workspace_bytes < al.total_bytes || ((uintptr_t)workspace & 255) != 0) return HA_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   unsigned char* base = (unsigned char*)workspace;
-  // hash, sort and draws exactly as the forward does them
-  uint16_t Rb[1024];
-  for (int c = 0; c < g.d; ++c)
-    for (int k = 0; k < g.r; ++k) Rb[c * g.r + k] = projection_bits(params->seed, c, k);
-  float* proj = (float*)(base + lay.proj);
-  int32_t* samples = (int32_t*)(base + lay.samples);
-  rc = launch_prep(proj, nullptr, Rb, samples, nullptr, g, params->seed, st);
-  if (rc != HA_OK) return rc;
-  uint8_t* codes_q = base + lay.codes_q;
-  uint8_t* codes_k = base + lay.codes_k;
-  rc = launch_lsh_hash(Q, codes_q, (int64_t)g.BH * g.n, g.d, g.dtype, proj, g.r, st);
-  if (rc != HA_OK) return rc;
-  rc = launch_lsh_hash(K, codes_k, (int64_t)g.BH * g.n, g.d, g.dtype, proj, g.r, st);
-  if (rc != HA_OK) return rc;
-  rc = launch_seg_sort_nodes(codes_q, codes_k, (int32_t*)(base + lay.perm_q), (int32_t*)(base + lay.perm_k),
-                             (int32_t*)(base + lay.pos_k), g.m > 0 ? samples : nullptr,
-                             (int32_t*)(base + lay.samp_blk), (uint32_t*)(base + lay.sort_hist), g, st);
-  if (rc != HA_OK) return rc;
-  Alg2Args a{};
-  a.Q = Q;
-  a.K = K;
-  a.V = V;
-  a.out = out;
-  a.lse = lse;
-  a.g = g;
-  a.perm_q = (const int32_t*)(base + lay.perm_q);
-  a.perm_k = (const int32_t*)(base + lay.perm_k);
-  a.pos_k = (const int32_t*)(base + lay.pos_k);
-  a.samples = samples;
-  a.samp_blk = (const int32_t*)(base + lay.samp_blk);
-  a.pos_q = (int32_t*)(base + al.pos_q);
-  a.tau_rows = (int32_t*)(base + al.tau_rows);
-  a.log_unm_t = (float*)(base + al.log_unmasked_t);
-  a.log_tau = (float*)(base + al.log_tau);
-  a.vw = (double*)(base + al.vnorm_w);
-  a.vprefix = (double*)(base + al.vnorm_prefix);
-  a.vsamp = (int32_t*)(base + al.vnorm_samples);
-  a.vlogw = (float*)(base + al.vnorm_logw);
-  a.log_unm_parts = (float*)(base + al.log_unmasked_parts);
-  a.seed = params->seed;
-  a.cap_scale = opt->cap_scale;
-  a.kappa = opt->kappa;
-  a.vnorm = opt->vnorm_sampling ? 1 : 0;
-  return launch_alg2(a, st);
+  void* part_o = (void*)(base + lay.part_o);
+  float* part_l = (float*)(base + lay.part_l);
+  if (g.levels > 0) {
+    // hash, sort and draws exactly as the forward does them
+    uint16_t Rb[1024];
+    for (int c = 0; c < g.d; ++c)
+      for (int k = 0; k < g.r; ++k) Rb[c * g.r + k] = projection_bits(params->seed, c, k);
+    float* proj = (float*)(base + lay.proj);
+    int32_t* samples = (int32_t*)(base + lay.samples);
+    rc = launch_prep(proj, nullptr, Rb, samples, nullptr, g, params->seed, st);
+    if (rc != HA_OK) return rc;
+    uint8_t* codes_q = base + lay.codes_q;
+    uint8_t* codes_k = base + lay.codes_k;
+    rc = launch_lsh_hash(Q, codes_q, (int64_t)g.BH * g.n, g.d, g.dtype, proj, g.r, st);
+    if (rc != HA_OK) return rc;
+    rc = launch_lsh_hash(K, codes_k, (int64_t)g.BH * g.n, g.d, g.dtype, proj, g.r, st);
+    if (rc != HA_OK) return rc;
+    rc = launch_seg_sort_nodes(codes_q, codes_k, (int32_t*)(base + lay.perm_q), (int32_t*)(base + lay.perm_k),
+                               (int32_t*)(base + lay.pos_k), g.m > 0 ? samples : nullptr,
+                               (int32_t*)(base + lay.samp_blk), (uint32_t*)(base + lay.sort_hist), g, st);
+    if (rc != HA_OK) return rc;
+    // Algorithm 2 on every node, one level at a time: the unmasked problem is its own single node;
+    // a causal problem's level l holds 2^l off-diagonal nodes per head (Algorithm 4), whose results
+    // go to the per-level partial outputs that the base case adds up below
+    const size_t esz = g.dtype == HA_BF16 ? 2 : 4;
+    for (int level = 0; level < g.levels; ++level) {
+      const int nodes = g.causal ? (1 << level) : 1;
+      const int s_rows = g.causal ? (g.n >> (level + 1)) : g.n;
+      const size_t lvl = (size_t)level * g.BH * g.n_cov;   // first entry of the level in the per-level arrays
+      Alg2Args a{};
+      a.Q = Q;
+      a.K = K;
+      a.V = V;
+      a.out = g.causal ? (void*)((unsigned char*)part_o + lvl * g.d * esz) : out;
+      a.lse = g.causal ? part_l + lvl : lse;
+      a.g = g;
+      a.g.BH = g.BH * nodes;
+      a.g.n = s_rows;
+      a.n_full = g.n;
+      a.nodes = nodes;
+      a.level = level;
+      a.causal = g.causal;
+      a.heads = g.BH;
+      a.total_nodes = g.total_nodes;
+      a.perm_q = (const int32_t*)(base + lay.perm_q) + lvl;
+      a.perm_k = (const int32_t*)(base + lay.perm_k) + lvl;
+      a.pos_k = (const int32_t*)(base + lay.pos_k) + lvl;
+      a.samples = samples;
+      a.samp_blk = (const int32_t*)(base + lay.samp_blk);
+      a.pos_q = (int32_t*)(base + al.pos_q);
+      a.tau_rows = (int32_t*)(base + al.tau_rows);
+      a.log_unm_t = (float*)(base + al.log_unmasked_t);
+      a.log_tau = (float*)(base + al.log_tau);
+      a.vw = (double*)(base + al.vnorm_w);
+      a.vprefix = (double*)(base + al.vnorm_prefix);
+      a.vsamp = (int32_t*)(base + al.vnorm_samples);
+      a.vlogw = (float*)(base + al.vnorm_logw);
+      a.log_unm_parts = (float*)(base + al.log_unmasked_parts);
+      a.seed = params->seed;
+      a.cap_scale = opt->cap_scale;
+      a.kappa = opt->kappa;
+      a.vnorm = opt->vnorm_sampling ? 1 : 0;
+      rc = launch_alg2(a, st);
+      if (rc != HA_OK) return rc;
+    }
+  }
+  if (g.causal) return run_base_case(Q, K, V, out, lse, nullptr, g, part_o, part_l, st);
+  return HA_OK;
 }
 
 const char* ha_strerror(int status) {
