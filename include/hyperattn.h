@@ -227,7 +227,8 @@ int ha_merge_unpermute(const float* o_b, const float* lse_b, const float* o_r, c
 /* ------------------------------------------------------------------------
  * Backward pass (Section 4.2 times forward + backward; the backward is the
  * derivative of the forward above with the random draws, and so the
- * permutations, held fixed).  bf16 tensors only (HA_ERR_DTYPE otherwise).
+ * permutations, held fixed).  bf16 tensors run on the matrix cores; fp32 tensors
+ * take the same passes in fp32 FMA arithmetic.
  *
  * Because every output row is one softmax over the union of its parts (block
  * keys, kept samples weighted s/m, base-case keys; Algorithms 1, 2, 4), with
@@ -243,8 +244,9 @@ int ha_merge_unpermute(const float* o_b, const float* lse_b, const float* o_r, c
  * exact_attn_forward_train: the same for exact attention.
  *
  * hyperattn_backward: Q, K, V, out, d_out, dQ, dK, dV are device pointers to
- * contiguous [B][H][n][d] bf16; lse device fp32 [B][H][n]; out_f32 as written
- * by hyperattn_forward_train, or NULL (delta then comes from out).  out and lse are the
+ * contiguous [B][H][n][d] of shape->dtype; lse device fp32 [B][H][n]; out_f32 as written
+ * by hyperattn_forward_train, or NULL (delta then comes from out; fp32 tensors:
+ * must be NULL, HA_ERR_DTYPE otherwise).  out and lse are the
  * results of hyperattn_forward on the same Q, K, V, shape and params, and
  * fwd_workspace is that call's workspace, unmodified since (it holds the sort
  * permutations and sample indices; only read here).  bwd_workspace: device,

@@ -537,9 +537,9 @@ def _backward_call(timed, Q, K, V, out, lse, d_out, b, m, r, causal, n_min, seed
 def hyperattn_backward(Q, K, V, out, lse, d_out, b, m, r, causal=False, n_min=4096, seed=0, fwd_workspace=None,
                        bwd_workspace=None, grads=None, stream=None, out_f32=None):
     """dQ, dK, dV of sum(out * d_out).  out, lse and fwd_workspace are what
-    hyperattn_forward produced / used for the same arguments (bf16 tensors);
-    out_f32, if the forward wrote one, makes delta = <d_out, out> free of the
-    output's bf16 rounding."""
+    hyperattn_forward produced / used for the same arguments (bf16 or fp32 tensors);
+    out_f32 (bf16 tensors only), if the forward wrote one, makes delta = <d_out, out>
+    free of the output's bf16 rounding."""
     if fwd_workspace is None:
         raise ValueError("hyperattn_backward needs the workspace of the forward call")
     return _backward_call(False, Q, K, V, out, lse, d_out, b, m, r, causal, n_min, seed, fwd_workspace, bwd_workspace,

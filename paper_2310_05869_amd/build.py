@@ -19,7 +19,7 @@ BUILD = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libhyperattn.so")
 
 SOURCES = ["api.hip", "lsh_hash.hip", "lsh_hash_mfma.hip", "seg_sort.hip", "stage_kernels.hip", "attn_mfma.hip", "attn_generic.hip",
-           "calib.hip", "attn_bwd_mfma.hip", "bwd_kernels.hip", "alg2_kernels.hip", "alg2_mfma.hip"]
+           "calib.hip", "attn_bwd_mfma.hip", "attn_bwd_generic.hip", "bwd_kernels.hip", "alg2_kernels.hip", "alg2_mfma.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

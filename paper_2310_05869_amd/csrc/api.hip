@@ -308,6 +308,11 @@ static int stage_geometry(Geometry* g, int groups, int n, int d, int dtype, int 
 // ---------------------------------------------------------------------------
 // Backward pass
 // ---------------------------------------------------------------------------
+// bf16 tensors: matrix cores; fp32 tensors: the fp32 FMA kernel with the same passes
+static int launch_attn_bwd(const BwdArgs& a, int mode, hipStream_t st) {
+  return use_mfma(a.f.g) ? launch_attn_bwd_mfma(a, mode, st) : launch_attn_bwd_generic(a, mode, st);
+}
+
 static int64_t bwd_sample_rows(const Geometry& g) {
   int64_t rows = 0;
   if (g.m <= 0) return 0;
@@ -349,7 +354,7 @@ static int backward_impl(const void* Q, const void* K, const void* V, const void
   Geometry g;
   int rc = make_geometry(sh, p, &g);
   if (rc != HA_OK) return rc;
-  if (g.dtype != HA_BF16) return HA_ERR_DTYPE;
+  if (out_f32 && g.dtype != HA_BF16) return HA_ERR_DTYPE;
   if (g.levels > kBwdMaxLevels) return HA_ERR_SHAPE;
   if (g.BH == 0 || g.n == 0) return HA_OK;
   if (!Q || !K || !V || !out || !lse || !d_out || !dQ || !dK || !dV || !fws || !bws) return HA_ERR_NULL;
@@ -407,34 +412,34 @@ static int backward_impl(const void* Q, const void* K, const void* V, const void
   }
 
   mark(0);
-  rc = launch_bwd_delta(out, out_f32, d_out, delta, (int64_t)g.BH * g.n, g.d, st);
+  rc = launch_bwd_delta(out, out_f32, d_out, delta, (int64_t)g.BH * g.n, g.d, g.dtype, st);
   if (rc != HA_OK) return rc;
   mark(1);
   if (g.levels > 0) {
     a.out1 = dq_part;
     a.out2 = nullptr;
-    rc = launch_attn_bwd_mfma(a, kBwdDqNode, st);
+    rc = launch_attn_bwd(a, kBwdDqNode, st);
     if (rc != HA_OK) return rc;
   }
   mark(2);
   if (g.causal) {
     a.fin1 = dQ;
     a.lvl1 = g.levels > 0 ? dq_part : nullptr;
-    rc = launch_attn_bwd_mfma(a, kBwdDqExact, st);
+    rc = launch_attn_bwd(a, kBwdDqExact, st);
     if (rc != HA_OK) return rc;
   }
   mark(3);
   if (g.levels > 0) {
     a.out1 = dk_part;
     a.out2 = dv_part;
-    rc = launch_attn_bwd_mfma(a, kBwdDkvBlock, st);
+    rc = launch_attn_bwd(a, kBwdDkvBlock, st);
     if (rc != HA_OK) return rc;
   }
   mark(4);
   if (g.levels > 0 && g.m > 0) {
     a.out1 = samp_k;
     a.out2 = samp_v;
-    rc = launch_attn_bwd_mfma(a, kBwdDkvSamp, st);
+    rc = launch_attn_bwd(a, kBwdDkvSamp, st);
     if (rc != HA_OK) return rc;
     rc = launch_bwd_sample_scatter(a, samp_k, samp_v, dk_part, dv_part, st);
     if (rc != HA_OK) return rc;
@@ -445,7 +450,7 @@ static int backward_impl(const void* Q, const void* K, const void* V, const void
     a.fin2 = dV;
     a.lvl1 = g.levels > 0 ? dk_part : nullptr;
     a.lvl2 = g.levels > 0 ? dv_part : nullptr;
-    rc = launch_attn_bwd_mfma(a, kBwdDkvExact, st);
+    rc = launch_attn_bwd(a, kBwdDkvExact, st);
     if (rc != HA_OK) return rc;
   }
   mark(6);
@@ -712,7 +717,6 @@ int ha_backward_workspace_layout(const ha_shape* shape, const ha_params* params,
   Geometry g;
   const int rc = make_geometry(shape, params, &g);
   if (rc != HA_OK) return rc;
-  if (g.dtype != HA_BF16) return HA_ERR_DTYPE;
   fill_bwd_layout(g, layout);
   return HA_OK;
 }
@@ -779,7 +783,7 @@ int exact_attn_backward(const void* Q, const void* K, const void* V, const void*
   Geometry g;
   int rc = make_geometry(sh, &p, &g);
   if (rc != HA_OK) return rc;
-  if (g.dtype != HA_BF16) return HA_ERR_DTYPE;
+  if (out_f32 && g.dtype != HA_BF16) return HA_ERR_DTYPE;
   if (g.BH == 0 || g.n == 0) return HA_OK;
   if (!Q || !K || !V || !out || !lse || !d_out || !dQ || !dK || !dV || !workspace) return HA_ERR_NULL;
   if (any_misaligned16(Q, K, V, out, out_f32, d_out, dQ, dK, dV) || any_misaligned4(lse)) return HA_ERR_ALIGN;
@@ -800,14 +804,14 @@ int exact_attn_backward(const void* Q, const void* K, const void* V, const void*
   a.dO = d_out;
   a.lse = lse;
   a.delta = (float*)(bb + bl.delta);
-  rc = launch_bwd_delta(out, out_f32, d_out, (float*)(bb + bl.delta), (int64_t)g.BH * g.n, g.d, st);
+  rc = launch_bwd_delta(out, out_f32, d_out, (float*)(bb + bl.delta), (int64_t)g.BH * g.n, g.d, g.dtype, st);
   if (rc != HA_OK) return rc;
   a.fin1 = dQ;
-  rc = launch_attn_bwd_mfma(a, kBwdDqExact, st);
+  rc = launch_attn_bwd(a, kBwdDqExact, st);
   if (rc != HA_OK) return rc;
   a.fin1 = dK;
   a.fin2 = dV;
-  return launch_attn_bwd_mfma(a, kBwdDkvExact, st);
+  return launch_attn_bwd(a, kBwdDkvExact, st);
 }
 
 size_t exact_attn_backward_workspace_bytes(const ha_shape* sh) {

@@ -162,6 +162,14 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
   return *reinterpret_cast<const uint32_t*>(&p);
 }
 
+// One tensor element as fp32 (fp32 tensors as they are, bf16 widened): the kernels without matrix cores.
+template <typename T>
+__device__ inline float load_elem(const T* p);
+template <>
+__device__ inline float load_elem<float>(const float* p) { return *p; }
+template <>
+__device__ inline float load_elem<uint16_t>(const uint16_t* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+
 // Where a finished query row goes.
 struct RowDest {
   bool valid;

@@ -13,13 +13,6 @@ namespace ha {
 constexpr int kGQT = 64;  // queries (= threads) per workgroup
 constexpr int kGKT = 32;  // keys per step
 
-template <typename T>
-__device__ inline float load_elem(const T* p);
-template <>
-__device__ inline float load_elem<float>(const float* p) { return *p; }
-template <>
-__device__ inline float load_elem<uint16_t>(const uint16_t* p) { return __uint_as_float((uint32_t)(*p) << 16); }
-
 __host__ __device__ inline size_t generic_lds_bytes(int d, int b, int m, int mode) {
   size_t s = (size_t)2 * kGKT * d * 4 + 64;
   if (mode == kModeNode) s += (size_t)(((b + m + 63) & ~63) + 64) * 4;

@@ -42,12 +42,15 @@ __host__ __device__ inline int bwd_chunks_per_node(const Geometry& g, int level)
   return (s + clen - 1) / clen;
 }
 
-int launch_attn_bwd_mfma(const BwdArgs& a, int mode, hipStream_t st);
-// delta_i = <dO_i, O_i>; O from its unrounded fp32 copy when O_f32 is non-null, else from the bf16 tensor
-int launch_bwd_delta(const void* O, const float* O_f32, const void* dO, float* delta, int64_t rows, int d, hipStream_t st);
+int64_t bwd_grid(const BwdArgs& a, int mode);  // workgroups of a pass (128 R rows each), the same for both kernels
+int launch_attn_bwd_mfma(const BwdArgs& a, int mode, hipStream_t st);     // bf16 tensors
+int launch_attn_bwd_generic(const BwdArgs& a, int mode, hipStream_t st);  // fp32 tensors
+// delta_i = <dO_i, O_i>; bf16 tensors: O from its unrounded fp32 copy when O_f32 is non-null, else from the tensor
+int launch_bwd_delta(const void* O, const float* O_f32, const void* dO, float* delta, int64_t rows, int d, int dtype,
+                     hipStream_t st);
 int launch_bwd_sample_scatter(const BwdArgs& a, const float* samp_k, const float* samp_v, float* part_k,
                               float* part_v, hipStream_t st);
-// dst (dtype bf16) = base + sum over the levels whose node holds the row on the given side
+// dst (the tensors' dtype, g.dtype) = base + sum over the levels whose node holds the row on the given side
 // (query_side: second half of the node; key side: first half)
 int launch_bwd_combine(const float* base, const float* part, void* dst, const Geometry& g, int query_side,
                        hipStream_t st);

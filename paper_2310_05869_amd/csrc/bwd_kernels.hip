@@ -51,12 +51,39 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const uint16_t* __restri
   if (row < rows && part == 0) delta[row] = s;
 }
 
-int launch_bwd_delta(const void* O, const float* O_f32, const void* dO, float* delta, int64_t rows, int d,
+// fp32 tensors: the same dot product, straight from O and dO.
+template <int D>
+__global__ __launch_bounds__(256) void bwd_delta_f32_kernel(const float* __restrict__ O, const float* __restrict__ G,
+                                                            float* __restrict__ delta, int64_t rows) {
+  constexpr int LPR = D / 8;
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t row = t / LPR;
+  const int part = (int)(t % LPR);
+  float s = 0.f;
+  if (row < rows) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s = __builtin_fmaf(O[row * D + part * 8 + e], G[row * D + part * 8 + e], s);
+  }
+#pragma unroll
+  for (int off = LPR / 2; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+  if (row < rows && part == 0) delta[row] = s;
+}
+
+int launch_bwd_delta(const void* O, const float* O_f32, const void* dO, float* delta, int64_t rows, int d, int dtype,
                      hipStream_t st) {
   if (rows <= 0) return HA_OK;
   const int lpr = d / 8;
   const int64_t threads = rows * lpr;
   const unsigned grid = (unsigned)((threads + 255) / 256);
+  if (dtype == HA_FP32) {
+    if (d == 128)
+      hipLaunchKernelGGL((bwd_delta_f32_kernel<128>), dim3(grid), dim3(256), 0, st, (const float*)O, (const float*)dO, delta, rows);
+    else if (d == 64)
+      hipLaunchKernelGGL((bwd_delta_f32_kernel<64>), dim3(grid), dim3(256), 0, st, (const float*)O, (const float*)dO, delta, rows);
+    else
+      return HA_ERR_SHAPE;
+    return check_launch();
+  }
   if (d == 128)
     hipLaunchKernelGGL((bwd_delta_kernel<128>), dim3(grid), dim3(256), 0, st, (const uint16_t*)O, O_f32, (const uint16_t*)dO, delta, rows);
   else if (d == 64)
@@ -156,9 +183,9 @@ int launch_bwd_sample_scatter(const BwdArgs& a, const float* samp_k, const float
 
 // Row i of the result = base[i] (if any) + sum over levels l, in order, of the
 // level's row for i where i lies on the given side of its level-l node.
-template <int D>
+template <typename T, int D>
 __global__ __launch_bounds__(256) void bwd_combine_kernel(const float* __restrict__ base, const float* __restrict__ part,
-                                                          uint16_t* __restrict__ dst, Geometry g, int query_side) {
+                                                          T* __restrict__ dst, Geometry g, int query_side) {
   constexpr int LPR = D / 8;
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t row = t / LPR;
@@ -186,8 +213,13 @@ __global__ __launch_bounds__(256) void bwd_combine_kernel(const float* __restric
     v0 += *reinterpret_cast<const f32x4*>(part + pr * D + piece * 8);
     v1 += *reinterpret_cast<const f32x4*>(part + pr * D + piece * 8 + 4);
   }
-  const u32x4 pk = {pack_bf16x2(v0.x, v0.y), pack_bf16x2(v0.z, v0.w), pack_bf16x2(v1.x, v1.y), pack_bf16x2(v1.z, v1.w)};
-  *reinterpret_cast<u32x4*>(dst + row * D + piece * 8) = pk;
+  if constexpr (sizeof(T) == 4) {
+    *reinterpret_cast<f32x4*>(dst + row * D + piece * 8) = v0;
+    *reinterpret_cast<f32x4*>(dst + row * D + piece * 8 + 4) = v1;
+  } else {
+    const u32x4 pk = {pack_bf16x2(v0.x, v0.y), pack_bf16x2(v0.z, v0.w), pack_bf16x2(v1.x, v1.y), pack_bf16x2(v1.z, v1.w)};
+    *reinterpret_cast<u32x4*>(dst + row * D + piece * 8) = pk;
+  }
 }
 
 int launch_bwd_combine(const float* base, const float* part, void* dst, const Geometry& g, int query_side,
@@ -196,10 +228,15 @@ int launch_bwd_combine(const float* base, const float* part, void* dst, const Ge
   if (rows <= 0) return HA_OK;
   const int lpr = g.d / 8;
   const unsigned grid = (unsigned)((rows * lpr + 255) / 256);
-  if (g.d == 128)
-    hipLaunchKernelGGL((bwd_combine_kernel<128>), dim3(grid), dim3(256), 0, st, base, part, (uint16_t*)dst, g, query_side);
+  const bool f32 = g.dtype == HA_FP32;
+  if (g.d == 128 && f32)
+    hipLaunchKernelGGL((bwd_combine_kernel<float, 128>), dim3(grid), dim3(256), 0, st, base, part, (float*)dst, g, query_side);
+  else if (g.d == 64 && f32)
+    hipLaunchKernelGGL((bwd_combine_kernel<float, 64>), dim3(grid), dim3(256), 0, st, base, part, (float*)dst, g, query_side);
+  else if (g.d == 128)
+    hipLaunchKernelGGL((bwd_combine_kernel<uint16_t, 128>), dim3(grid), dim3(256), 0, st, base, part, (uint16_t*)dst, g, query_side);
   else if (g.d == 64)
-    hipLaunchKernelGGL((bwd_combine_kernel<64>), dim3(grid), dim3(256), 0, st, base, part, (uint16_t*)dst, g, query_side);
+    hipLaunchKernelGGL((bwd_combine_kernel<uint16_t, 64>), dim3(grid), dim3(256), 0, st, base, part, (uint16_t*)dst, g, query_side);
   else
     return HA_ERR_SHAPE;
   return check_launch();

@@ -22,7 +22,15 @@ asserted against 4e-3 (rounding the fp64 gradient to bf16 alone gives 2.3e-3; me
 most 3.1e-3).  Gradient values below 2^-100 are flushed to zero by the GPU's arithmetic and
 are allowed that much absolute error.
 A dropped term, a wrong mask, sign or weight moves an element by the size of
-the term, hundreds of times the tolerance."""
+the term, hundreds of times the tolerance.
+
+fp32 tensors take the same passes in fp32 FMA arithmetic.  Nothing is rounded to bf16 there; what
+remains is the rounding of fp32 sums: a score or dP is a dot product of d <= 128 terms and a
+gradient element a sum over up to a few thousand pairs, each with relative error at most
+(number of terms) * 2^-24 of the sum of magnitudes in the worst case.  The criterion is
+    |got - ref| <= 2^-14 * bound
+(2^-14 = 2^10 terms * 2^-24) with the same `bound`; measured errors are a few percent of it.
+The relative Frobenius error is asserted against 1e-5."""
 import numpy as np
 import pytest
 
@@ -33,7 +41,9 @@ from ha_testutil import compare_codes, half_ulp_bf16, have_gpu, to_device, to_ho
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not have_gpu(), reason="needs a GPU")]
 
 EPS_OPERANDS = 2.0 ** -8
+EPS_FP32 = 2.0 ** -14     # fp32 tensors, see the module docstring
 FRO_TOL = 4e-3            # iid inputs only (measured: at most 3.1e-3)
+FRO_TOL_FP32 = 1e-5
 TINY = 2.0 ** -100        # values below the smallest normal number are flushed to zero on the GPU
 
 
@@ -50,9 +60,12 @@ def torch():
     return t
 
 
-def _assert_grad_close(got, ref, bound, what, fro_tol=None):
+def _assert_grad_close(got, ref, bound, what, fro_tol=None, dtype="bf16"):
     err = np.abs(got - ref)
-    tol = EPS_OPERANDS * bound + half_ulp_bf16(ref) + TINY
+    if dtype == "bf16":
+        tol = EPS_OPERANDS * bound + half_ulp_bf16(ref) + TINY
+    else:
+        tol = EPS_FP32 * bound + TINY
     fro = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
     with np.errstate(divide="ignore", invalid="ignore"):
         ratio = np.where(tol > 0, err / tol, np.where(err > 0, np.inf, 0.0))
@@ -65,23 +78,25 @@ def _assert_grad_close(got, ref, bound, what, fro_tol=None):
         assert fro <= fro_tol, (what, fro)
 
 
-def _cotangent(shape, seed):
+def _cotangent(shape, seed, dtype="bf16"):
     g = np.random.default_rng(seed).standard_normal(shape).astype(np.float32)
-    return synth_inputs.round_to_bf16(g)
+    return synth_inputs.round_to_bf16(g) if dtype == "bf16" else g
 
 
 def _run_case(ha, torch, cfg, seed_data=77):
     B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
+    dtype = cfg["dtype"]
     Q, K, V = synth_inputs.make_qkv(cfg, seed=seed_data)
-    G = _cotangent(Q.shape, seed_data + 1)
-    dQ_, dK_, dV_, dG_ = (to_device(x, "bf16") for x in (Q, K, V, G))
-    shape = ha.make_shape(B, H, n, d, ha.HA_BF16)
+    G = _cotangent(Q.shape, seed_data + 1, dtype)
+    dQ_, dK_, dV_, dG_ = (to_device(x, dtype) for x in (Q, K, V, G))
+    shape = ha.make_shape(B, H, n, d, ha.HA_BF16 if dtype == "bf16" else ha.HA_FP32)
     params = ha.make_params(cfg["b"], cfg["m"], cfg["r"], cfg["causal"], cfg["n_min"], cfg["seed"])
     ws = ha.alloc_workspace(shape, params)
     kw = dict(causal=cfg["causal"], n_min=cfg["n_min"], seed=cfg["seed"])
-    out32 = torch.empty(dQ_.shape, dtype=torch.float32, device="cuda")
+    out32 = torch.empty(dQ_.shape, dtype=torch.float32, device="cuda") if dtype == "bf16" else None   # fp32 tensors: out is it
     out, lse = ha.hyperattn_forward(dQ_, dK_, dV_, cfg["b"], cfg["m"], cfg["r"], workspace=ws, out_f32=out32, **kw)
-    assert torch.equal(out32.to(torch.bfloat16).view(torch.int16), out.view(torch.int16))  # the copy rounds to the output
+    if dtype == "bf16":
+        assert torch.equal(out32.to(torch.bfloat16).view(torch.int16), out.view(torch.int16))  # the copy rounds to the output
     gq, gk, gv = ha.hyperattn_backward(dQ_, dK_, dV_, out, lse, dG_, cfg["b"], cfg["m"], cfg["r"], fwd_workspace=ws,
                                        out_f32=out32, **kw)
     torch.cuda.synchronize()
@@ -98,10 +113,10 @@ def _run_case(ha, torch, cfg, seed_data=77):
                flip=flips or None)
     rq, rk, rv = orc.hyperattn_backward(Q, K, V, G, **okw)
     bq, bk, bv = orc.hyperattn_backward(Q, K, V, G, absolute=True, **okw)
-    fro = FRO_TOL if cfg["law"] == "iid" else None
-    _assert_grad_close(to_host(gq), rq, bq, "dQ", fro)
-    _assert_grad_close(to_host(gk), rk, bk, "dK", fro)
-    _assert_grad_close(to_host(gv), rv, bv, "dV", fro)
+    fro = (FRO_TOL if dtype == "bf16" else FRO_TOL_FP32) if cfg["law"] == "iid" else None
+    _assert_grad_close(to_host(gq), rq, bq, "dQ", fro, dtype)
+    _assert_grad_close(to_host(gk), rk, bk, "dK", fro, dtype)
+    _assert_grad_close(to_host(gv), rv, bv, "dV", fro, dtype)
     return (gq, gk, gv), (dQ_, dK_, dV_, out, lse, dG_, ws, out32)
 
 
@@ -124,14 +139,28 @@ def test_backward_causal(ha, torch, d, n, n_min, b, m):
     _run_case(ha, torch, cfg)
 
 
+@pytest.mark.parametrize("d,n,b,m,causal,n_min", [(64, 1024, 64, 64, 0, 4096),      # the fp32 configuration of the parity suite
+                                                  (128, 768, 128, 37, 0, 4096),
+                                                  (64, 2048, 64, 32, 1, 256),
+                                                  (128, 1024, 32, 16, 1, 128),
+                                                  (64, 192, 96, 7, 0, 4096),        # block not a multiple of 64, odd m
+                                                  (64, 128, 8, 20, 1, 8)])          # more samples than keys in the deep nodes
+def test_backward_fp32(ha, torch, d, n, b, m, causal, n_min):
+    """fp32 tensors: the fp32 FMA kernels, same passes and buffers as the bf16 path."""
+    print(f"backward fp32 d={d} n={n} b={b} m={m} causal={causal} n_min={n_min}", flush=True)
+    cfg = dict(B=1, H=2, n=n, d=d, dtype="fp32", law="iid", b=b, m=m, r=7, causal=causal, n_min=n_min, seed=2)
+    _run_case(ha, torch, cfg)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 @pytest.mark.parametrize("d,n,causal", [(128, 300, False), (128, 300, True), (64, 1000, True), (64, 257, False)])
-def test_exact_attn_backward(ha, torch, d, n, causal):
-    print(f"exact backward d={d} n={n} causal={causal}", flush=True)
-    cfg = dict(B=1, H=2, n=n, d=d, dtype="bf16", law="iid")
+def test_exact_attn_backward(ha, torch, d, n, causal, dtype):
+    print(f"exact backward d={d} n={n} causal={causal} {dtype}", flush=True)
+    cfg = dict(B=1, H=2, n=n, d=d, dtype=dtype, law="iid")
     Q, K, V = synth_inputs.make_qkv(cfg, seed=5)
-    G = _cotangent(Q.shape, 6)
-    tq, tk, tv, tg = (to_device(x, "bf16") for x in (Q, K, V, G))
-    out32 = torch.empty(tq.shape, dtype=torch.float32, device="cuda")
+    G = _cotangent(Q.shape, 6, dtype)
+    tq, tk, tv, tg = (to_device(x, dtype) for x in (Q, K, V, G))
+    out32 = torch.empty(tq.shape, dtype=torch.float32, device="cuda") if dtype == "bf16" else None
     out, lse = ha.exact_attn_forward(tq, tk, tv, causal=causal, out_f32=out32)
     gq, gk, gv = ha.exact_attn_backward(tq, tk, tv, out, lse, tg, causal=causal, out_f32=out32)
     torch.cuda.synchronize()
@@ -142,7 +171,7 @@ def test_exact_attn_backward(ha, torch, d, n, causal):
     ref = orc.hyperattn_backward(Q, K, V, G, **okw)
     bnd = orc.hyperattn_backward(Q, K, V, G, absolute=True, **okw)
     for got, r_, b_, name in zip((gq, gk, gv), ref, bnd, ("dQ", "dK", "dV")):
-        _assert_grad_close(to_host(got), r_, b_, name, FRO_TOL)
+        _assert_grad_close(to_host(got), r_, b_, name, FRO_TOL if dtype == "bf16" else FRO_TOL_FP32, dtype)
 
 
 def test_backward_on_the_mixture_law(ha, torch):
@@ -190,10 +219,12 @@ def test_backward_is_deterministic_and_leaves_inputs_alone(ha, torch):
 def test_backward_error_paths(ha, torch):
     print("backward errors", flush=True)
     q = torch.zeros((1, 1, 256, 64), dtype=torch.float32, device="cuda")
-    shape = ha.make_shape(1, 1, 256, 64, ha.HA_FP32)
     params = ha.make_params(64, 16, 7, False, 4096, 0)
-    with pytest.raises(ha.HyperAttnError):          # fp32 tensors: no backward path
-        ha.ha_backward_workspace_bytes(shape, params)
+    shape = ha.make_shape(1, 1, 256, 64, ha.HA_FP32)
+    ws32 = ha.alloc_workspace(shape, params)
+    out, lse = ha.hyperattn_forward(q, q, q, 64, 16, 7, workspace=ws32)
+    with pytest.raises(ha.HyperAttnError):          # an unrounded copy of the output exists for bf16 tensors only
+        ha.hyperattn_backward(q, q, q, out, lse, q, 64, 16, 7, fwd_workspace=ws32, out_f32=out.clone())
     qb = q.to(torch.bfloat16)
     shape = ha.make_shape(1, 1, 256, 64, ha.HA_BF16)
     ws = ha.alloc_workspace(shape, params)
