@@ -252,7 +252,8 @@ int ha_merge_unpermute(const float* o_b, const float* lse_b, const float* o_r, c
  * permutations and sample indices; only read here).  bwd_workspace: device,
  * 256-byte aligned, >= ha_backward_workspace_bytes(); overwritten.  All
  * caller-owned; nothing is allocated; kernels are enqueued on `stream` and the
- * call returns without waiting.  Sums over parts are taken in a fixed order:
+ * call returns without waiting.  Sums over parts are taken in a fixed order
+ * (the node parts level by level into one accumulated fp32 row per tensor row):
  * same inputs give bit-identical gradients.
  * Errors: HA_ERR_NULL, HA_ERR_DTYPE, HA_ERR_SHAPE (as hyperattn_forward; more
  * than 24 recursion levels), HA_ERR_WORKSPACE, HA_ERR_LAUNCH.
@@ -268,7 +269,8 @@ int ha_merge_unpermute(const float* o_b, const float* lse_b, const float* o_r, c
  * >= exact_attn_backward_workspace_bytes(shape). */
 typedef struct {
   size_t delta;                      /* fp32 [B*H][n] */
-  size_t dq_part, dk_part, dv_part;  /* fp32 [levels][B*H][n_cov][d] */
+  size_t acc_a, acc_b;               /* fp32 [B*H][n][d] each: the node parts' rows, added up level by level
+                                        (acc_a: dQ, afterwards dK; acc_b: dV) */
   size_t samp_k, samp_v;             /* fp32 rows of the sampled keys per (level, head, node, query chunk, sample) */
   size_t total_bytes;
 } ha_bwd_ws_layout;

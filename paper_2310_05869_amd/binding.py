@@ -37,7 +37,7 @@ class HaWsLayout(ctypes.Structure):
 
 
 class HaBwdWsLayout(ctypes.Structure):
-    _fields_ = [(k, c_size_t) for k in ("delta", "dq_part", "dk_part", "dv_part", "samp_k", "samp_v", "total_bytes")]
+    _fields_ = [(k, c_size_t) for k in ("delta", "acc_a", "acc_b", "samp_k", "samp_v", "total_bytes")]
 
 
 class HaAlg2Options(ctypes.Structure):

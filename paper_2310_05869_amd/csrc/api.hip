@@ -18,11 +18,13 @@
 // draws held fixed; every (query, key) pair that occurs contributes on its own,
 // given the final log row sums and delta = <dO, O>):
 //   delta       row dots of dO and the forward's output
-//   dQ          node pass (query tiles over their key lists), then the base-case
-//               pass, which adds the node rows and writes dQ
-//   dK, dV      block keys of every node; sampled keys of every node (partial
-//               sums per query chunk, reduced in order); then the base-case
-//               pass, which adds the per-level rows and writes dK, dV
+//   dQ          node passes, level by level (query tiles over their key lists),
+//               into one accumulated fp32 row per query; then the base-case
+//               pass, which adds that row and writes dQ
+//   dK, dV      block keys of every node, level by level, into accumulated rows;
+//               sampled keys of every node (partial sums per query chunk) and
+//               their ordered reduction into the same rows, level by level;
+//               then the base-case pass, which adds the rows and writes dK, dV
 #include <cmath>
 #include <cstring>
 
@@ -332,20 +334,20 @@ static void fill_bwd_layout(const Geometry& g, ha_bwd_ws_layout* l) {
     return at;
   };
   const size_t rows = (size_t)g.BH * g.n;
-  const size_t cov = (size_t)g.levels * g.BH * g.n_cov;
   const size_t rowb = (size_t)g.d * 4;
   l->delta = take(rows * 4);
-  l->dq_part = take(cov * rowb);
-  l->dk_part = take(cov * rowb);
-  l->dv_part = take(cov * rowb);
+  // accumulated node rows: dQ first, then (dQ being written out) dK in the same region, dV in the second
+  l->acc_a = take(g.levels > 0 ? rows * rowb : 0);
+  l->acc_b = take(g.levels > 0 ? rows * rowb : 0);
   const size_t srows = (size_t)bwd_sample_rows(g);
   l->samp_k = take(srows * rowb);
   l->samp_v = take(srows * rowb);
   l->total_bytes = off < 256 ? 256 : off;
 }
 
-// ev, when non-null, receives 8 events: start, after delta, dQ of the nodes, dQ of the base case,
-// dK/dV of the block keys, of the sampled keys (with their reduction), of the base case, after the final sums.
+// ev, when non-null, receives 8 events: start, after delta, dQ of the nodes, dQ of the base case (unmasked
+// problems: its conversion), dK/dV of the block keys, of the sampled keys (with their reduction), of the base
+// case, after the conversion of dK and dV (unmasked problems).
 static int backward_impl(const void* Q, const void* K, const void* V, const void* out, const float* out_f32,
                          const float* lse, const void* d_out, void* dQ, void* dK, void* dV, const ha_shape* sh,
                          const ha_params* p,
@@ -369,9 +371,8 @@ static int backward_impl(const void* Q, const void* K, const void* V, const void
   const unsigned char* fb = (const unsigned char*)fws;
   unsigned char* bb = (unsigned char*)bws;
   float* delta = (float*)(bb + bl.delta);
-  float* dq_part = (float*)(bb + bl.dq_part);
-  float* dk_part = (float*)(bb + bl.dk_part);
-  float* dv_part = (float*)(bb + bl.dv_part);
+  float* acc_a = (float*)(bb + bl.acc_a);
+  float* acc_b = (float*)(bb + bl.acc_b);
   float* samp_k = (float*)(bb + bl.samp_k);
   float* samp_v = (float*)(bb + bl.samp_v);
   auto mark = [&](int i) {
@@ -415,51 +416,61 @@ static int backward_impl(const void* Q, const void* K, const void* V, const void
   rc = launch_bwd_delta(out, out_f32, d_out, delta, (int64_t)g.BH * g.n, g.d, g.dtype, st);
   if (rc != HA_OK) return rc;
   mark(1);
-  if (g.levels > 0) {
-    a.out1 = dq_part;
-    a.out2 = nullptr;
-    rc = launch_attn_bwd(a, kBwdDqNode, st);
-    if (rc != HA_OK) return rc;
-  }
+  // node passes: one launch per level, in level order, so that a row's contributions from different levels
+  // are added one after the other
+  const int64_t wgs_per_level = bwd_grid(a, kBwdDqNode);
+  if (wgs_per_level * g.levels > 0x7fffffff) return HA_ERR_SHAPE;
+  auto node_levels = [&](int mode) -> int {
+    for (int l = 0; l < g.levels; ++l) {
+      a.wg_base = (int32_t)(l * wgs_per_level);
+      const int r = launch_attn_bwd(a, mode, st);
+      if (r != HA_OK) return r;
+    }
+    return HA_OK;
+  };
+  a.out1 = acc_a;
+  a.out2 = nullptr;
+  rc = node_levels(kBwdDqNode);
+  if (rc != HA_OK) return rc;
   mark(2);
   if (g.causal) {
     a.fin1 = dQ;
-    a.lvl1 = g.levels > 0 ? dq_part : nullptr;
+    a.lvl1 = g.levels > 0 ? acc_a : nullptr;
     rc = launch_attn_bwd(a, kBwdDqExact, st);
-    if (rc != HA_OK) return rc;
+  } else {  // one node, no base case: its rows are the result
+    rc = launch_bwd_convert(acc_a, dQ, g, st);
   }
+  if (rc != HA_OK) return rc;
   mark(3);
-  if (g.levels > 0) {
-    a.out1 = dk_part;
-    a.out2 = dv_part;
-    rc = launch_attn_bwd(a, kBwdDkvBlock, st);
-    if (rc != HA_OK) return rc;
-  }
+  a.out1 = acc_a;
+  a.out2 = acc_b;
+  rc = node_levels(kBwdDkvBlock);
+  if (rc != HA_OK) return rc;
   mark(4);
   if (g.levels > 0 && g.m > 0) {
     a.out1 = samp_k;
     a.out2 = samp_v;
     rc = launch_attn_bwd(a, kBwdDkvSamp, st);
     if (rc != HA_OK) return rc;
-    rc = launch_bwd_sample_scatter(a, samp_k, samp_v, dk_part, dv_part, st);
-    if (rc != HA_OK) return rc;
+    for (int l = 0; l < g.levels; ++l) {
+      rc = launch_bwd_sample_scatter(a, l, samp_k, samp_v, acc_a, acc_b, st);
+      if (rc != HA_OK) return rc;
+    }
   }
   mark(5);
   if (g.causal) {
     a.fin1 = dK;
     a.fin2 = dV;
-    a.lvl1 = g.levels > 0 ? dk_part : nullptr;
-    a.lvl2 = g.levels > 0 ? dv_part : nullptr;
+    a.lvl1 = g.levels > 0 ? acc_a : nullptr;
+    a.lvl2 = g.levels > 0 ? acc_b : nullptr;
     rc = launch_attn_bwd(a, kBwdDkvExact, st);
     if (rc != HA_OK) return rc;
   }
   mark(6);
-  if (!g.causal) {  // one node, no base case: the level-0 rows are the result
-    rc = launch_bwd_combine(nullptr, dq_part, dQ, g, 1, st);
+  if (!g.causal) {
+    rc = launch_bwd_convert(acc_a, dK, g, st);
     if (rc != HA_OK) return rc;
-    rc = launch_bwd_combine(nullptr, dk_part, dK, g, 0, st);
-    if (rc != HA_OK) return rc;
-    rc = launch_bwd_combine(nullptr, dv_part, dV, g, 0, st);
+    rc = launch_bwd_convert(acc_b, dV, g, st);
     if (rc != HA_OK) return rc;
   }
   mark(7);

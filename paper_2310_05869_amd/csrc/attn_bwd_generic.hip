@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kGNT) void attn_bwd_generic_kernel(BwdArgs a) {
   int64_t samp_row0 = 0;
   int t0 = 0;
   if (MODE == kBwdDqNode || MODE == kBwdDkvBlock) {
-    w = decode_node_tile<kGRT>(f, blockIdx.x);
+    w = decode_node_tile<kGRT>(f, a.wg_base + blockIdx.x);
   } else if (MODE == kBwdDqExact) {
     w = decode_exact_tile<kGRT>(f, blockIdx.x);
   } else if (MODE == kBwdDkvExact) {
@@ -145,10 +145,10 @@ __global__ __launch_bounds__(kGNT) void attn_bwd_generic_kernel(BwdArgs a) {
   int blk_r = -1;
   if (MODE == kBwdDqNode) {
     r_row = f.perm_q[w.seg_off + w.p0 + r_use];
-    out_row = w.seg_off + (r_row - w.nr.q_start);
+    out_row = (int64_t)w.bh * g.n + r_row;
   } else if (MODE == kBwdDkvBlock) {
     r_row = f.perm_k[w.seg_off + w.p0 + r_use];
-    out_row = w.seg_off + (r_row - w.nr.k_start);
+    out_row = (int64_t)w.bh * g.n + r_row;
   } else if (MODE == kBwdDkvSamp) {
     const int j = samp0 + r_use;
     r_row = w.nr.k_start + f.samples[(int64_t)w.nr.heap * g.m + j];
@@ -247,28 +247,38 @@ __global__ __launch_bounds__(kGNT) void attn_bwd_generic_kernel(BwdArgs a) {
   }
   if (!r_valid) return;
 
-  // ---- results: node passes write fp32 rows into the per-level buffers; exact passes write the final
-  // gradient in the tensors' dtype after adding, in level order, the rows of every level whose node holds
-  // this row on the pass's side (queries: second half of the node; keys: first half) ----
+  // ---- results: node passes write (the first level that holds the row on the pass's side) or add (later
+  // levels) fp32 rows of the accumulated gradient; exact passes write the final gradient in the tensors'
+  // dtype after adding the accumulated row where some level holds this row (queries: second half of the
+  // node; keys: first half) ----
   if (!kExact) {
-    store_cols<float, C>((WANT_DS ? a.out1 : a.out2) + out_row * D + c0, acc);
-    return;
-  }
-  const float* lvl = WANT_DS ? a.lvl1 : a.lvl2;
-  if (lvl != nullptr) {
-    for (int l = 0; l < g.levels; ++l) {
-      const int sl = g.n >> (l + 1);
-      const bool second = ((r_row / sl) & 1) != 0;
-      if (second != kDq) continue;
-      const float* pr = lvl + (((int64_t)l * g.BH + w.bh) * g.n_cov + (int64_t)(r_row / (2 * sl)) * sl + (r_row % sl)) * D + c0;
+    float* dst = (WANT_DS ? a.out1 : a.out2) + out_row * D + c0;
+    bool add = false;
+    if (MODE == kBwdDqNode) add = node_levels_hold(g, r_row, true, w.level);
+    if (MODE == kBwdDkvBlock) add = node_levels_hold(g, r_row, false, w.level);
+    if (add) {
 #pragma unroll
       for (int c = 0; c < C; c += 4) {
-        const float4 v = *reinterpret_cast<const float4*>(pr + c);
+        const float4 v = *reinterpret_cast<const float4*>(dst + c);
         acc[c] += v.x;
         acc[c + 1] += v.y;
         acc[c + 2] += v.z;
         acc[c + 3] += v.w;
       }
+    }
+    store_cols<float, C>(dst, acc);
+    return;
+  }
+  const float* lvl = WANT_DS ? a.lvl1 : a.lvl2;
+  if (lvl != nullptr && node_levels_hold(g, r_row, kDq, g.levels)) {
+    const float* pr = lvl + out_row * D + c0;
+#pragma unroll
+    for (int c = 0; c < C; c += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(pr + c);
+      acc[c] += v.x;
+      acc[c + 1] += v.y;
+      acc[c + 2] += v.z;
+      acc[c + 3] += v.w;
     }
   }
   store_cols<T, C>(reinterpret_cast<T*>(WANT_DS ? a.fin1 : a.fin2) + out_row * D + c0, acc);

@@ -27,8 +27,10 @@
 // The dK/dV passes run twice, once accumulating dK (scores, dP, dS) and once
 // dV (scores, P): one accumulator set each, so two waves fit per SIMD.
 //
-// Results leave as fp32 rows into per-part buffers; sums over parts are taken by
-// separate kernels in a fixed order (no floating-point atomics anywhere).
+// Sums over parts are taken in a fixed order, never by floating-point atomics: the node passes run
+// level by level and add their fp32 rows to one accumulated row per tensor row (the first level
+// that holds a row writes it), the sampled keys' rows go through a reduction of their own, and the
+// base-case passes add the accumulated rows in their epilogue and write the final gradient.
 #include <type_traits>
 
 #include "attn_common.h"
@@ -52,7 +54,7 @@ struct BwdLds {
   static constexpr int BUF = 2 * TILE;          // y tile + bt tile
   static constexpr int SC = 2 * kTT * 4;        // per buffer: -L log2(e) and delta of the T rows
   static constexpr int EP_ROW = D * 4 + 16;
-  static constexpr int EP_WAVE = 32 * EP_ROW + 256 + kBwdMaxLevels * 8;  // rows, row ids, level row bases
+  static constexpr int EP_WAVE = 32 * EP_ROW + 256;  // rows, row ids
 };
 
 __host__ __device__ inline int bwd_list_capacity(const Geometry& g, int mode) {
@@ -101,7 +103,7 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
   int64_t samp_row0 = 0;
   int t0 = 0;                                      // exact dK/dV pass: first query row of the T range
   if (MODE == kBwdDqNode || MODE == kBwdDkvBlock) {
-    w = decode_node_tile<kRT>(f, logical_block(blockIdx.x, gridDim.x));
+    w = decode_node_tile<kRT>(f, a.wg_base + logical_block(blockIdx.x, gridDim.x));
   } else if (MODE == kBwdDqExact) {
     w = decode_exact_tile<kRT>(f, logical_block(blockIdx.x, gridDim.x));
   } else if (MODE == kBwdDkvExact) {
@@ -177,10 +179,10 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
   int blk_r = -1;        // sampled-key pass: sorted block of this key
   if (MODE == kBwdDqNode) {
     r_row = f.perm_q[w.seg_off + w.p0 + r_use];
-    out_row = w.seg_off + (r_row - w.nr.q_start);
+    out_row = (int64_t)w.bh * g.n + r_row;
   } else if (MODE == kBwdDkvBlock) {
     r_row = f.perm_k[w.seg_off + w.p0 + r_use];
-    out_row = w.seg_off + (r_row - w.nr.k_start);
+    out_row = (int64_t)w.bh * g.n + r_row;
   } else if (MODE == kBwdDkvSamp) {
     const int j = samp0 + r_use;
     r_row = w.nr.k_start + f.samples[(int64_t)w.nr.heap * g.m + j];
@@ -424,15 +426,12 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
     }
 
     // ---- epilogue: the wave's 32 rows leave through an LDS transpose as whole rows.
-    // Node passes write fp32 rows into the per-level buffers.  Exact passes (the
-    // base case of Algorithm 4) write the final gradient in the tensors' dtype,
-    // after adding the rows of every level whose node holds these rows on the
-    // pass's side (queries: second half of the node; keys: first half).  The 32
-    // rows of a wave lie in one n_min block, so a level holds all or none of them
-    // and then as 32 consecutive rows.
+    // Node passes write or add fp32 rows into the accumulated rows.  Exact passes (the
+    // base case of Algorithm 4) write the final gradient in the tensors' dtype, after
+    // adding the accumulated row where some level's node holds the row on the pass's
+    // side (queries: second half of the node; keys: first half).
     unsigned char* ep = smem + wave * L::EP_WAVE;
     int64_t* ep_rows = reinterpret_cast<int64_t*>(ep + 32 * L::EP_ROW);
-    int64_t* ep_pr = ep_rows + 32;
     if (h == 0) ep_rows[lq] = r_valid ? out_row : (int64_t)-1;
   #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -444,6 +443,11 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
       }
     float* dst32 = kWantDs ? a.out1 : a.out2;
     if (!kExact) {
+      // node passes add to what earlier levels left in the row; all rows of a node lie on the same side of
+      // every ancestor, so the whole workgroup either adds or writes
+      bool add = false;
+      if (MODE == kBwdDqNode) add = node_levels_hold(g, w.nr.q_start, true, w.level);
+      if (MODE == kBwdDkvBlock) add = node_levels_hold(g, w.nr.k_start, false, w.level);
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -451,71 +455,37 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
       for (int idx = lane; idx < 32 * CH; idx += 64) {
         const int row = idx / CH, ch = idx % CH;
         const int64_t r64 = ep_rows[row];
-        if (r64 >= 0)
-          *reinterpret_cast<f32x4*>(dst32 + r64 * D + ch * 4) = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 16);
+        if (r64 < 0) continue;
+        f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 16);
+        f32x4* dp = reinterpret_cast<f32x4*>(dst32 + r64 * D + ch * 4);
+        if (add) v += *dp;
+        *dp = v;
       }
       return;
     }
     uint16_t* dst16 = reinterpret_cast<uint16_t*>(kWantDs ? a.fin1 : a.fin2);
     const float* lvl = kWantDs ? a.lvl1 : a.lvl2;
-    int nfold = 0;
-    if (lvl != nullptr) {
-      const int i0 = w.q0 + 32 * __builtin_amdgcn_readfirstlane(wave);
-      const bool want_second = kDq;
-      for (int l = 0; l < g.levels; ++l) {
-        const int sl = g.n >> (l + 1);
-        const bool second = ((i0 / sl) & 1) != 0;
-        if (second != want_second) continue;
-        if (lane == 0) ep_pr[nfold] = ((int64_t)l * g.BH + w.bh) * g.n_cov + (int64_t)(i0 / (2 * sl)) * sl + (i0 % sl);
-        ++nfold;
-      }
-    }
+    // the 32 rows of a wave lie in one n_min block: the node passes hold all of them or none
+    const int i0 = w.q0 + 32 * __builtin_amdgcn_readfirstlane(wave);
+    const bool fold = lvl != nullptr && node_levels_hold(g, i0, kDq, g.levels);
+    const float* acc_rows = lvl + ((int64_t)w.bh * g.n + i0) * D;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     constexpr int CH8 = D / 8;  // 8-element pieces per row
-    // NF: compile-time count of folded rows so their loads are issued together; 0 = run-time count nfold
-    auto rows_out = [&](auto nf_tag) {
-      constexpr int NF = decltype(nf_tag)::value;
-      const int nf = NF > 0 ? NF : nfold;
-      for (int idx = lane; idx < 32 * CH8; idx += 64) {
-        const int row = idx / CH8, ch = idx % CH8;
-        const int64_t r64 = ep_rows[row];
-        if (r64 < 0) continue;
-        f32x4 v0 = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 32);
-        f32x4 v1 = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 32 + 16);
-        if (NF > 0) {
-          f32x4 p0[NF > 0 ? NF : 1], p1[NF > 0 ? NF : 1];
-  #pragma unroll
-          for (int c = 0; c < NF; ++c) {
-            const float* pp = lvl + (ep_pr[c] + row) * D + ch * 8;
-            p0[c] = *reinterpret_cast<const f32x4*>(pp);
-            p1[c] = *reinterpret_cast<const f32x4*>(pp + 4);
-          }
-  #pragma unroll
-          for (int c = 0; c < NF; ++c) {
-            v0 += p0[c];
-            v1 += p1[c];
-          }
-        } else {
-          for (int c = 0; c < nf; ++c) {
-            const float* pp = lvl + (ep_pr[c] + row) * D + ch * 8;
-            v0 += *reinterpret_cast<const f32x4*>(pp);
-            v1 += *reinterpret_cast<const f32x4*>(pp + 4);
-          }
-        }
-        const u32x4 pk = {pack_bf16x2(v0.x, v0.y), pack_bf16x2(v0.z, v0.w), pack_bf16x2(v1.x, v1.y), pack_bf16x2(v1.z, v1.w)};
-        *reinterpret_cast<u32x4*>(dst16 + r64 * D + ch * 8) = pk;
+    for (int idx = lane; idx < 32 * CH8; idx += 64) {
+      const int row = idx / CH8, ch = idx % CH8;
+      const int64_t r64 = ep_rows[row];
+      if (r64 < 0) continue;
+      f32x4 v0 = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 32);
+      f32x4 v1 = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 32 + 16);
+      if (fold) {
+        const float* pp = acc_rows + (int64_t)row * D + ch * 8;
+        v0 += *reinterpret_cast<const f32x4*>(pp);
+        v1 += *reinterpret_cast<const f32x4*>(pp + 4);
       }
-    };
-    switch (nfold) {
-      case 1: rows_out(std::integral_constant<int, 1>{}); break;
-      case 2: rows_out(std::integral_constant<int, 2>{}); break;
-      case 3: rows_out(std::integral_constant<int, 3>{}); break;
-      case 4: rows_out(std::integral_constant<int, 4>{}); break;
-      case 5: rows_out(std::integral_constant<int, 5>{}); break;
-      case 6: rows_out(std::integral_constant<int, 6>{}); break;
-      default: rows_out(std::integral_constant<int, 0>{}); break;  // none, or more than six
+      const u32x4 pk = {pack_bf16x2(v0.x, v0.y), pack_bf16x2(v0.z, v0.w), pack_bf16x2(v1.x, v1.y), pack_bf16x2(v1.z, v1.w)};
+      *reinterpret_cast<u32x4*>(dst16 + r64 * D + ch * 8) = pk;
     }
   };
   if constexpr (WHAT == kAccBoth) {
@@ -559,7 +529,7 @@ static int launch_bwd_d(const BwdArgs& a, int mode, int grid, hipStream_t st) {
 }
 int64_t bwd_grid(const BwdArgs& a, int mode) {
   const Geometry& g = a.f.g;
-  if (mode == kBwdDqNode || mode == kBwdDkvBlock) return node_grid<kRT>(g);
+  if (mode == kBwdDqNode || mode == kBwdDkvBlock) return g.levels > 0 ? node_grid<kRT>(g) / g.levels : 0;  // one level per launch
   if (mode == kBwdDqExact || mode == kBwdDkvExact) return exact_grid<kRT>(a.f);
   return a.samp_wg_off[g.levels];
 }

@@ -1,7 +1,7 @@
-// Small kernels around the MFMA backward pass: delta_i = <dO_i, O_i>, the
-// ordered reduction of the sampled keys' gradients into the per-level key
-// buffers, and the final sums over the parts of Algorithm 4 (base case plus
-// every level whose node holds the row), written in the tensors' dtype.
+// Small kernels around the backward passes: delta_i = <dO_i, O_i>, the ordered
+// reduction of the sampled keys' gradients of one level into the accumulated
+// key rows, and the conversion of accumulated rows to the tensors' dtype
+// (unmasked problems, whose single node holds the whole result).
 // Every sum is taken in a fixed order: results are bit-reproducible.
 #include "attn_common.h"
 #include "bwd_common.h"
@@ -93,8 +93,8 @@ int launch_bwd_delta(const void* O, const float* O_f32, const void* dO, float* d
   return check_launch();
 }
 
-// Sampled keys' gradients into the level's key buffers.  One wave per sample j
-// of a (head, node); a lane owns four columns of dK (lanes < d/4) or of dV (the
+// Sampled keys' gradients of one level into the accumulated key rows.  One wave per sample j
+// of a (head, node of the level); a lane owns four columns of dK (lanes < d/4) or of dV (the
 // next d/4 lanes).  A key may be drawn more than once: the FIRST sample that
 // drew a key ("owner") adds, in increasing sample order, the sums of every
 // sample of that key, each taken over the node's query chunks in a fixed order;
@@ -102,7 +102,8 @@ int launch_bwd_delta(const void* O, const float* O_f32, const void* dO, float* d
 // order of additions: reproducible bit for bit.
 constexpr int kScatterWaves = 4;
 
-__global__ __launch_bounds__(64 * kScatterWaves) void bwd_sample_scatter_kernel(BwdArgs a, const float* __restrict__ samp_k,
+__global__ __launch_bounds__(64 * kScatterWaves) void bwd_sample_scatter_kernel(BwdArgs a, int level,
+                                                                                const float* __restrict__ samp_k,
                                                                                 const float* __restrict__ samp_v,
                                                                                 float* part_k, float* part_v) {
   __shared__ int32_t keys[4096];
@@ -111,15 +112,13 @@ __global__ __launch_bounds__(64 * kScatterWaves) void bwd_sample_scatter_kernel(
   const int groups = (m + kScatterWaves - 1) / kScatterWaves;
   const int grp = blockIdx.x % groups;
   const int rest = blockIdx.x / groups;
-  const int bh = rest / g.total_nodes;
-  const int heap = rest % g.total_nodes;
-  int level = 0;
-  while ((2 << level) - 1 <= heap) ++level;
-  const int node = heap - ((1 << level) - 1);
-  const NodeRef nr = node_ref(g, level, node);
   const int nodes = g.causal ? (1 << level) : 1;
+  const int bh = rest / nodes;
+  const int node = rest % nodes;
+  const int heap = (1 << level) - 1 + node;
+  const NodeRef nr = node_ref(g, level, node);
   const int cpn = bwd_chunks_per_node(g, level);
-  const int64_t seg_off = ((int64_t)level * g.BH + bh) * g.n_cov + (int64_t)node * nr.s;
+  const int64_t key_row0 = (int64_t)bh * g.n + nr.k_start;  // the node's first key in the accumulated rows
   int64_t lvl_row0 = 0;
 #pragma unroll
   for (int l = 0; l < kBwdMaxLevels; ++l)
@@ -166,53 +165,34 @@ __global__ __launch_bounds__(64 * kScatterWaves) void bwd_sample_scatter_kernel(
     }
   }
   if (active) {
-    f32x4* out = reinterpret_cast<f32x4*>(dst + (seg_off + key) * d + c4);
+    f32x4* out = reinterpret_cast<f32x4*>(dst + (key_row0 + key) * d + c4);
     *out = *out + total;
   }
 }
 
-int launch_bwd_sample_scatter(const BwdArgs& a, const float* samp_k, const float* samp_v, float* part_k,
-                              float* part_v, hipStream_t st) {
+int launch_bwd_sample_scatter(const BwdArgs& a, int level, const float* samp_k, const float* samp_v, float* acc_k,
+                              float* acc_v, hipStream_t st) {
   const Geometry& g = a.f.g;
-  if (g.m <= 0 || g.total_nodes <= 0) return HA_OK;
+  if (g.m <= 0 || level < 0 || level >= g.levels) return HA_OK;
+  const int nodes = g.causal ? (1 << level) : 1;
   const int groups = (g.m + kScatterWaves - 1) / kScatterWaves;
-  hipLaunchKernelGGL(bwd_sample_scatter_kernel, dim3((unsigned)(g.BH * g.total_nodes * groups)),
-                     dim3(64 * kScatterWaves), 0, st, a, samp_k, samp_v, part_k, part_v);
+  const int64_t grid = (int64_t)g.BH * nodes * groups;
+  if (grid > kMaxGrid) return HA_ERR_SHAPE;
+  hipLaunchKernelGGL(bwd_sample_scatter_kernel, dim3((unsigned)grid), dim3(64 * kScatterWaves), 0, st, a, level, samp_k,
+                     samp_v, acc_k, acc_v);
   return check_launch();
 }
 
-// Row i of the result = base[i] (if any) + sum over levels l, in order, of the
-// level's row for i where i lies on the given side of its level-l node.
+// Accumulated fp32 rows to the tensors' dtype.
 template <typename T, int D>
-__global__ __launch_bounds__(256) void bwd_combine_kernel(const float* __restrict__ base, const float* __restrict__ part,
-                                                          T* __restrict__ dst, Geometry g, int query_side) {
+__global__ __launch_bounds__(256) void bwd_convert_kernel(const float* __restrict__ acc, T* __restrict__ dst, int64_t rows) {
   constexpr int LPR = D / 8;
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t row = t / LPR;
   const int piece = (int)(t % LPR);
-  if (row >= (int64_t)g.BH * g.n) return;
-  const int bh = (int)(row / g.n), i = (int)(row % g.n);
-  f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
-  if (base) {
-    v0 = *reinterpret_cast<const f32x4*>(base + row * D + piece * 8);
-    v1 = *reinterpret_cast<const f32x4*>(base + row * D + piece * 8 + 4);
-  }
-  for (int l = 0; l < g.levels; ++l) {
-    int64_t pr;
-    bool on;
-    if (g.causal) {
-      const int s = g.n >> (l + 1);
-      const bool second = ((i / s) & 1) != 0;
-      on = query_side ? second : !second;
-      pr = ((int64_t)l * g.BH + bh) * g.n_cov + (int64_t)(i / (2 * s)) * s + (i % s);
-    } else {
-      on = true;
-      pr = (int64_t)bh * g.n_cov + i;
-    }
-    if (!on) continue;
-    v0 += *reinterpret_cast<const f32x4*>(part + pr * D + piece * 8);
-    v1 += *reinterpret_cast<const f32x4*>(part + pr * D + piece * 8 + 4);
-  }
+  if (row >= rows) return;
+  const f32x4 v0 = *reinterpret_cast<const f32x4*>(acc + row * D + piece * 8);
+  const f32x4 v1 = *reinterpret_cast<const f32x4*>(acc + row * D + piece * 8 + 4);
   if constexpr (sizeof(T) == 4) {
     *reinterpret_cast<f32x4*>(dst + row * D + piece * 8) = v0;
     *reinterpret_cast<f32x4*>(dst + row * D + piece * 8 + 4) = v1;
@@ -222,21 +202,20 @@ __global__ __launch_bounds__(256) void bwd_combine_kernel(const float* __restric
   }
 }
 
-int launch_bwd_combine(const float* base, const float* part, void* dst, const Geometry& g, int query_side,
-                       hipStream_t st) {
+int launch_bwd_convert(const float* acc, void* dst, const Geometry& g, hipStream_t st) {
   const int64_t rows = (int64_t)g.BH * g.n;
   if (rows <= 0) return HA_OK;
   const int lpr = g.d / 8;
   const unsigned grid = (unsigned)((rows * lpr + 255) / 256);
   const bool f32 = g.dtype == HA_FP32;
   if (g.d == 128 && f32)
-    hipLaunchKernelGGL((bwd_combine_kernel<float, 128>), dim3(grid), dim3(256), 0, st, base, part, (float*)dst, g, query_side);
+    hipLaunchKernelGGL((bwd_convert_kernel<float, 128>), dim3(grid), dim3(256), 0, st, acc, (float*)dst, rows);
   else if (g.d == 64 && f32)
-    hipLaunchKernelGGL((bwd_combine_kernel<float, 64>), dim3(grid), dim3(256), 0, st, base, part, (float*)dst, g, query_side);
+    hipLaunchKernelGGL((bwd_convert_kernel<float, 64>), dim3(grid), dim3(256), 0, st, acc, (float*)dst, rows);
   else if (g.d == 128)
-    hipLaunchKernelGGL((bwd_combine_kernel<uint16_t, 128>), dim3(grid), dim3(256), 0, st, base, part, (uint16_t*)dst, g, query_side);
+    hipLaunchKernelGGL((bwd_convert_kernel<uint16_t, 128>), dim3(grid), dim3(256), 0, st, acc, (uint16_t*)dst, rows);
   else if (g.d == 64)
-    hipLaunchKernelGGL((bwd_combine_kernel<uint16_t, 64>), dim3(grid), dim3(256), 0, st, base, part, (uint16_t*)dst, g, query_side);
+    hipLaunchKernelGGL((bwd_convert_kernel<uint16_t, 64>), dim3(grid), dim3(256), 0, st, acc, (uint16_t*)dst, rows);
   else
     return HA_ERR_SHAPE;
   return check_launch();
