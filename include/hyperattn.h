@@ -260,9 +260,10 @@ int ha_merge_unpermute(const float* o_b, const float* lse_b, const float* o_r, c
  *
  * hyperattn_backward_timed: the same, and WAITS for the stream; stage_ms_host
  * (host, 8 floats) receives the times between events on the stream: delta, dQ
- * of the nodes, dQ of the base case, dK/dV of the block keys, dK/dV of the
- * sampled keys with their reduction, dK/dV of the base case, final sums (unmasked
- * problems only; the causal base-case passes add the levels themselves), total.
+ * of the nodes, dQ of the base case (unmasked problems: conversion of the one
+ * node's rows), dK/dV of the block keys, dK/dV of the sampled keys with their
+ * reduction, dK/dV of the base case, conversion of dK and dV (unmasked problems
+ * only; the causal base-case passes write the final tensors themselves), total.
  *
  * exact_attn_backward: gradients of exact_attn_forward (Section 1.1; causal:
  * Section 3.1), the denominator of the forward + backward speed-up.  workspace
