@@ -234,7 +234,7 @@ def backward_bench(args, torch, ha):
                      "achieved": round(bwd_flop / (bwd_ms * 1e-3) / 1e12, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(bwd_flop / (bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                      "traffic": None, "flop_per_launch": bwd_flop, "ms_per_launch": round(bwd_ms, 4),
-                     "note": "algorithmic flops (5 products per pair); the two-pass scheme executes 7"},
+                     "note": "algorithmic flops (5 products per pair); the three-pass scheme executes 8 (3 for dQ, 3 for dK, 2 for dV)"},
     }
     if not args.no_exact:
         eo, el = torch.empty_like(Q), torch.empty_like(lse)
