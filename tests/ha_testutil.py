@@ -43,12 +43,15 @@ def out_tolerance(ref: np.ndarray, dtype: str, absv=None) -> np.ndarray:
     2^-8 * sum_j p_j |v_j|; where the caller passes that sum (`absv`: the oracle
     run on |V|) it is added, otherwise it must fit in the 2e-3 (it does when
     |V| is small, as for the iid workloads).
+    The half-ulp is that of the value that gets rounded, which may lie in the binade
+    above the reference's when the reference sits just under a power of two: it is
+    taken at |ref| plus the rest of the tolerance.
     fp32: 1e-5 absolute plus 1e-5 relative."""
     if dtype == "bf16":
-        tol = 2e-3 + half_ulp_bf16(ref)
+        tol = np.full_like(ref, 2e-3, dtype=np.float64)
         if absv is not None:
             tol = tol + 2.0 ** -8 * absv
-        return tol
+        return tol + half_ulp_bf16(np.abs(ref) + tol)
     return 1e-5 + 1e-5 * np.abs(ref)
 
 
@@ -57,9 +60,10 @@ LSE_TOL = {"bf16": 1e-3, "fp32": 2e-5}
 
 def assert_close(got, ref, dtype, what, absv=None, max_plain_frac=0.0):
     """Element-wise comparison.  Without `absv` the criterion is the plain one of out_tolerance().
-    With `absv` (bf16 only; the caller says in its docstring why the case needs it) an element may
-    also use the operand-rounding allowance 2^-8 sum_j p_j |v_j|; the number of elements that
-    fail the plain criterion is printed and must not exceed max_plain_frac of all elements."""
+    With `absv` (bf16 only) an element may also use the operand-rounding allowance
+    2^-8 sum_j p_j |v_j|, the bound the arithmetic guarantees; the number of elements that fail
+    the plain criterion is printed and must not exceed max_plain_frac of all elements (one
+    element is always allowed: the caller chooses the share by how many keys carry a row)."""
     err = np.abs(got - ref)
     plain = err > out_tolerance(ref, dtype)
     if absv is None:
@@ -69,7 +73,8 @@ def assert_close(got, ref, dtype, what, absv=None, max_plain_frac=0.0):
         frac = plain.mean() if plain.size else 0.0
         print(f"  {what}: {int(plain.sum())} of {plain.size} elements ({frac:.3%}) exceed the plain criterion "
               f"(allowed {max_plain_frac:.3%}); worst excess {float((err - out_tolerance(ref, dtype)).max()):.2e}", flush=True)
-        assert frac <= max_plain_frac, f"{what}: {frac:.3%} of the elements need the operand-rounding allowance"
+        assert plain.sum() <= max(1, int(max_plain_frac * plain.size)), \
+            f"{what}: {frac:.3%} of the elements need the operand-rounding allowance"
     assert not bad.any(), (f"{what}: {bad.sum()} of {bad.size} elements out of tolerance; "
                            f"max abs err {err.max():.3e} (|ref| there {np.abs(ref).ravel()[err.argmax()]:.3e})")
     return float(err.max())

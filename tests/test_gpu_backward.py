@@ -63,7 +63,8 @@ def torch():
 def _assert_grad_close(got, ref, bound, what, fro_tol=None, dtype="bf16"):
     err = np.abs(got - ref)
     if dtype == "bf16":
-        tol = EPS_OPERANDS * bound + half_ulp_bf16(ref) + TINY
+        tol = EPS_OPERANDS * bound + TINY
+        tol = tol + half_ulp_bf16(np.abs(ref) + tol)   # of the value that gets rounded, see ha_testutil.out_tolerance
     else:
         tol = EPS_FP32 * bound + TINY
     fro = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
@@ -338,8 +339,8 @@ def test_forward_and_backward_on_random_small_problems(ha, torch, d, n, n_min, b
         stages = {}
         run_oracle(Q, K, V, cfg, stages=stages)
         flips = compare_codes(np.stack([views["codes_q"].cpu().numpy(), views["codes_k"].cpu().numpy()]), stages, r)
-    # a single sampled key with the weight s/m can carry a row: only then may an element use the
-    # operand-rounding allowance 2^-8 sum_j p_j |v_j| (see tests/test_gpu_parity.py)
+    # the guaranteed bound (with the operand-rounding allowance 2^-8 sum_j p_j |v_j|) for every element; the share
+    # over the plain criterion is capped as in tests/test_gpu_parity.py (few keys can carry a row: 0.5 %)
     ref_out, ref_lse, absv = run_oracle(Q, K, V, cfg, flip=flips or None, with_absv=True)
-    assert_close(to_host(out), ref_out, "bf16", "out", absv if 0 < m < 16 else None, 0.005)
+    assert_close(to_host(out), ref_out, "bf16", "out", absv, 0.005 if (0 < m < 16 or causal) else 1e-5)
     assert_lse_close(to_host(lse), ref_lse, "bf16", "lse")
