@@ -375,11 +375,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
     if (HN) store_rows(vbuf_at(kt + 1), L::VSTR, vreg);
     __syncthreads();
   };
-  // two tiles per trip so the score registers swap roles without copies.  In the loop kt is even at the first
-  // body and odd at the second, so the buffer each fragment read goes to is known at compile time and a block
-  // starts with its first fragment reads; only then does the compiler form the read / MFMA / vector-slice pipeline
-  // that the sched_group_barrier calls ask for (the ISA shows it for the two bodies in the loop, not for the
-  // bodies after it, whose address arithmetic leads their blocks).
+  // two tiles per trip so the score registers swap roles without copies.  The read / MFMA / vector-slice pipeline
+  // that the sched_group_barrier calls ask for is formed where a block starts with its first fragment reads: the
+  // ISA shows it for the two bodies inside the loop (kt's parity, hence every buffer address, is a constant
+  // there), not for the copies of the body after the loop, which handle a list's last one or two tiles.
   f32x16 c2[2];
   float bias_b = 0.f;
   int kt = 0;
