@@ -46,6 +46,18 @@ def measured_traffic_bytes(workload, key):
     return None
 
 
+def host_cpu_model():
+    """The host processor's name as /proc/cpuinfo gives it (empty if unavailable)."""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return ""
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -526,7 +538,7 @@ def main():
         except Exception:
             threads = cores
         result["cpu_baseline"] = {"value": round(cpu_s * 1e3 * B * H / cpu_heads, 1), "unit": "ms", "cores": int(cores),
-                                  "blas_threads": int(threads), "kind": "oracle",
+                                  "blas_threads": int(threads), "cpu": host_cpu_model(), "kind": "oracle",
                                   "sample": f"heads 0..{cpu_heads - 1} of batch 0 of the same workload ({cpu_s:.1f} s "
                                             f"measured), scaled to B*H = {B * H} heads"}
         result["parity_sample_max_abs_err"] = err
