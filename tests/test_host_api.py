@@ -77,6 +77,27 @@ def test_workspace_layout(ha):
     assert lay3.levels == 0 and lay3.total_nodes == 0
 
 
+def test_backward_workspace_layout(ha):
+    """The backward keeps one accumulated fp32 row per tensor row and pass (two buffers, the first one used by dQ
+    and then by dK), delta, and the sampled keys' rows per query chunk: not one buffer per level."""
+    sh = ha.make_shape(1, 32, 131072, 128, ha.HA_BF16)
+    p = ha.make_params(256, 256, 7, True, 4096, 0)
+    lay = ha.binding.HaBwdWsLayout()
+    assert ha.lib().ha_backward_workspace_layout(ctypes.byref(sh), ctypes.byref(p), ctypes.byref(lay)) == 0
+    rows = 32 * 131072
+    assert lay.acc_a - lay.delta == rows * 4 and lay.acc_b - lay.acc_a == rows * 128 * 4
+    assert lay.samp_k - lay.acc_b == rows * 128 * 4
+    # per level: 32 heads x 2^l nodes x ceil(s / 2048) chunks x 256 samples, s = n >> (l + 1): 32 chunks per head and level
+    samp_rows = 5 * 32 * 32 * 256
+    assert lay.samp_v - lay.samp_k == samp_rows * 128 * 4 and lay.total_bytes - lay.samp_v == samp_rows * 128 * 4
+    assert lay.total_bytes == ha.ha_backward_workspace_bytes(sh, p) < 6 * 2 ** 30
+    # fp32 tensors have a backward pass too, with the same buffers
+    assert ha.ha_backward_workspace_bytes(ha.make_shape(1, 32, 131072, 128, ha.HA_FP32), p) == lay.total_bytes
+    # exact attention (the recursion that never splits): delta only
+    p0 = ha.make_params(1, 0, 1, True, 131072, 0)
+    assert ha.ha_backward_workspace_bytes(sh, p0) == rows * 4
+
+
 @pytest.mark.parametrize("shape,params,status", [
     ((1, 1, 1024, 96, 0), (64, 64, 7, 0, 4096, 0), -3),     # d not 64/128
     ((1, 1, 1000, 64, 0), (64, 64, 7, 0, 4096, 0), -3),     # n % b
