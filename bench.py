@@ -325,6 +325,74 @@ def probes(args, torch, ha):
                       "round_of_eight_wave_tiles_d128": tile}), flush=True)
 
 
+def phases(args, torch, ha):
+    """Where the workgroups of the two attention launches spend their cycles: the forward pass through
+    the instrumented instantiation of the attention kernel (ha.hyperattn_forward_stamped), whose
+    workgroups record the shader clock at their phase boundaries."""
+    cfg = dict(synth_inputs.CONFIGS[args.workload])
+    if args.heads > 0 or args.seq > 0:
+        cfg["H"] = args.heads if args.heads > 0 else cfg["H"]
+        cfg["n"] = args.seq if args.seq > 0 else cfg["n"]
+    if cfg["dtype"] != "bf16":
+        sys.exit("bench.py --phases: the instrumented kernel is the bf16 MFMA kernel")
+    (Q, K, V), _ = device_inputs(cfg, torch)
+    B, H, n, d = Q.shape
+    shape = ha.make_shape(B, H, n, d, ha.HA_BF16)
+    params = ha.make_params(cfg["b"], cfg["m"], cfg["r"], cfg["causal"], cfg["n_min"], cfg["seed"])
+    ws = ha.alloc_workspace(shape, params)
+    kw = dict(causal=cfg["causal"], n_min=cfg["n_min"], seed=cfg["seed"], workspace=ws)
+    call = (Q, K, V, cfg["b"], cfg["m"], cfg["r"])
+    for _ in range(max(1, args.warmup)):
+        ha.hyperattn_forward_stamped(*call, **kw)
+    stage = {k: [] for k in ("node_attn", "causal_base", "total")}
+    for _ in range(max(1, args.steps)):     # what the product instantiations take, for comparison
+        ms = ha.hyperattn_forward_timed(*call, **kw)[2]
+        for k in stage:
+            stage[k].append(ms[k])
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    _, _, node_st, base_st = ha.hyperattn_forward_stamped(*call, **kw)
+    e1.record()
+    torch.cuda.synchronize()
+
+    def summary(st, groups):
+        st = st.cpu().numpy().astype(np.int64)
+        if st.shape[0] == 0:
+            return None
+        c = st[:, :5]
+        ph = np.diff(c, axis=1)                     # list, gathers + first scores, loop, epilogue
+        life = c[:, 4] - c[:, 0]
+        ticks = st[:, 6] - st[:, 5]                 # 10 ns units
+        tiles = st[:, 7]
+        rows = []
+        for name, sel in groups(tiles):
+            if not sel.any():
+                continue
+            loop_tiles = np.maximum(tiles[sel] - 1, 1)   # the first score tile is computed ahead of the loop
+            rows.append({"workgroups": name, "count": int(sel.sum()), "tiles": float(tiles[sel].mean()),
+                         "cycles_life": float(life[sel].mean()),
+                         "cycles_key_list": float(ph[sel, 0].mean()),
+                         "cycles_gathers_first_scores": float(ph[sel, 1].mean()),
+                         "cycles_loop": float(ph[sel, 2].mean()),
+                         "cycles_loop_per_tile": float((ph[sel, 2] / loop_tiles).mean()),
+                         "cycles_epilogue": float(ph[sel, 3].mean()),
+                         "shader_clock_GHz": float((life[sel] / np.maximum(ticks[sel], 1)).mean() / 10.0)})
+        return rows
+
+    node = summary(node_st, lambda t: [("all", t >= 0)])
+    base = summary(base_st, lambda t: [("all", t >= 0), ("2-16 tiles", t <= 16), ("17-48 tiles", (t > 16) & (t <= 48)),
+                                       ("49-64 tiles", t > 48)])
+    res = {"metric": "attention workgroup phases", "unit": "shader cycles (mean over the launch's workgroups)",
+           "n_gpus": 1, "config": {"workload": args.workload, "B": B, "H": H, "n": n, "d": d},
+           "node_launch": node, "base_case_launch": base,
+           "stamped_forward_ms": e0.elapsed_time(e1),
+           "product_stage_ms_median": {k: float(np.median(v)) for k, v in stage.items()}}
+    for k in ("node_launch", "base_case_launch"):
+        for row in res[k] or []:
+            log(f"[bench] {k} {row}")
+    print(json.dumps(res), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -337,6 +405,7 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="time the 12-head d=64 sweep shape at every length instead")
     ap.add_argument("--alg2", action="store_true", help="time Algorithm 2 as printed / Lemma 2's value sampling instead")
     ap.add_argument("--probes", action="store_true", help="run the library's issue-rate probes instead")
+    ap.add_argument("--phases", action="store_true", help="cycle stamps of the attention workgroups' phases instead")
     ap.add_argument("--heads", type=int, default=0, help="override the workload's head count (profiling runs whose "
                                                           "32-bit hardware counters a full workload would overflow)")
     ap.add_argument("--seq", type=int, default=0, help="override the workload's sequence length (same purpose)")
@@ -353,6 +422,8 @@ def main():
 
     if args.probes:
         return probes(args, torch, ha)
+    if args.phases:
+        return phases(args, torch, ha)
     if args.sweep:
         return sweep(args, torch, ha)
     if args.alg2:

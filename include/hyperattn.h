@@ -160,6 +160,29 @@ int hyperattn_forward_timed(const void* Q, const void* K, const void* V, void* o
                             void* workspace, size_t workspace_bytes, void* stream,
                             float* stage_ms_host);
 
+/* Measurement variant of hyperattn_forward for bf16 tensors (same computation and
+ * results; HA_ERR_DTYPE otherwise): the two attention launches of the forward pass
+ * (all nodes of Section 4.1 / Algorithm 4; the causal base case) run an instrumented
+ * instantiation of the same kernel, in which every workgroup also writes HA_STAMP_WORDS
+ * 64-bit words into device memory, indexed by its tile number:
+ *   [0] shader-clock reading at entry, [1] once its key list (block keys + kept
+ *   samples) is built, [2] before the loop over key tiles (rows gathered, first
+ *   score tile done), [3] after the loop, [4] at the end (results stored);
+ *   [5], [6] the constant-rate counter (100 MHz) at entry and at the end;
+ *   [7] the number of 64-key tiles of the workgroup.
+ * ha_forward_workgroups gives the number of records of either launch (0 for a launch
+ * the problem does not have, and for fp32 tensors); node_stamps_dev / base_stamps_dev
+ * are device memory of at least that many records (sizes in bytes, checked:
+ * HA_ERR_WORKSPACE), 8-byte aligned, owned by the caller, and may be NULL where the
+ * count is 0.  Asynchronous on `stream` like hyperattn_forward. */
+#define HA_STAMP_WORDS 8
+int ha_forward_workgroups(const ha_shape* shape, const ha_params* params, int64_t* node_wgs, int64_t* base_wgs);
+int hyperattn_forward_stamped(const void* Q, const void* K, const void* V, void* out, float* lse,
+                              const ha_shape* shape, const ha_params* params,
+                              void* workspace, size_t workspace_bytes, void* stream,
+                              int64_t* node_stamps_dev, size_t node_stamps_bytes,
+                              int64_t* base_stamps_dev, size_t base_stamps_bytes);
+
 /* Plain exact attention D^-1 A V (Section 1.1), or D_C^-1 (M^C . A) V with
  * M^C_ij = 1{i >= j} (Section 3.1) when causal != 0; the denominator of the
  * speed-up ratio.  Any n >= 1; d in {64,128}.  Needs no workspace. */

@@ -67,6 +67,9 @@ _SIGNATURES = {
                                                      c_void_p, c_size_t, c_void_p]),
     "hyperattn_forward_timed": (c_int, [c_void_p] * 5 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_size_t,
                                                         c_void_p, POINTER(c_float)]),
+    "ha_forward_workgroups": (c_int, [POINTER(HaShape), POINTER(HaParams), POINTER(c_int64), POINTER(c_int64)]),
+    "hyperattn_forward_stamped": (c_int, [c_void_p] * 5 + [POINTER(HaShape), POINTER(HaParams), c_void_p, c_size_t,
+                                                          c_void_p, c_void_p, c_size_t, c_void_p, c_size_t]),
     "exact_attn_forward": (c_int, [c_void_p] * 5 + [POINTER(HaShape), c_int, c_void_p]),
     "ha_make_projection": (c_int, [c_uint64, c_int32, c_int32, POINTER(c_float)]),
     "ha_make_samples": (c_int, [c_uint64, c_int32, c_int32, c_int32, c_int32, POINTER(c_int32)]),
@@ -338,6 +341,48 @@ def hyperattn_forward_timed(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0, 
                                        workspace.numel(), _stream(stream), ms)
     _check(st, "hyperattn_forward_timed")
     return out, lse, dict(zip(STAGE_NAMES, [float(x) for x in ms]))
+
+
+STAMP_WORDS = 8
+STAMP_NAMES = ("cycles_entry", "cycles_list", "cycles_loop", "cycles_epilogue", "cycles_end", "ticks_entry", "ticks_end",
+               "tiles")
+
+
+def ha_forward_workgroups(shape, params):
+    """(node workgroups, base-case workgroups) of the forward pass's two attention launches."""
+    nw, bw = c_int64(0), c_int64(0)
+    _check(lib().ha_forward_workgroups(ctypes.byref(shape), ctypes.byref(params), ctypes.byref(nw), ctypes.byref(bw)),
+           "ha_forward_workgroups")
+    return int(nw.value), int(bw.value)
+
+
+def hyperattn_forward_stamped(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0, workspace=None, out=None, lse=None,
+                              stream=None):
+    """As hyperattn_forward (bf16 tensors), through the instrumented instantiation of the attention kernel.
+    Returns (out, lse, node_stamps, base_stamps): int64 tensors [workgroups, STAMP_WORDS] in the order of
+    STAMP_NAMES, one row per workgroup of the node launch / the base-case launch."""
+    torch = _torch()
+    _expect_qkv(Q, K=K, V=V, out=out)
+    _expect_f32(Q, tuple(Q.shape[:3]), lse=lse)
+    B, H, n, d = Q.shape
+    shape = make_shape(B, H, n, d, _dtype_code(Q))
+    params = make_params(b, m, r, causal, n_min, seed)
+    if workspace is None:
+        workspace = alloc_workspace(shape, params, Q.device)
+    if out is None:
+        out = torch.empty_like(Q)
+    if lse is None:
+        lse = torch.empty((B, H, n), dtype=torch.float32, device=Q.device)
+    nw, bw = ha_forward_workgroups(shape, params)
+    node_st = torch.zeros((nw, STAMP_WORDS), dtype=torch.int64, device=Q.device)
+    base_st = torch.zeros((bw, STAMP_WORDS), dtype=torch.int64, device=Q.device)
+    _check(lib().hyperattn_forward_stamped(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(out, "out"), _dev(lse, "lse"),
+                                           ctypes.byref(shape), ctypes.byref(params), workspace.data_ptr(),
+                                           workspace.numel(), _stream(stream),
+                                           node_st.data_ptr() if nw else None, node_st.numel() * 8,
+                                           base_st.data_ptr() if bw else None, base_st.numel() * 8),
+           "hyperattn_forward_stamped")
+    return out, lse, node_st, base_st
 
 
 def exact_attn_forward(Q, K, V, causal=False, out=None, lse=None, stream=None, out_f32=None):

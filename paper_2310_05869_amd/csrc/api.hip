@@ -174,8 +174,8 @@ static int run_attention(const AttnArgs& a, int mode, hipStream_t st) {
 
 // Algorithm 4's diagonal blocks: exact causal attention on every block of base_len rows, whose
 // epilogue adds the row sums and outputs of the off-diagonal nodes (part_o / part_l of every level).
-static int run_base_case(const void* Q, const void* K, const void* V, void* out, float* lse, float* out_f32,
-                         const Geometry& g, void* part_o, float* part_l, hipStream_t st) {
+static AttnArgs base_case_args(const void* Q, const void* K, const void* V, void* out, float* lse, float* out_f32,
+                               const Geometry& g, void* part_o, float* part_l) {
   const int64_t head_stride = (int64_t)g.n * g.d;
   AttnArgs a{};
   a.Q = Q;
@@ -194,14 +194,24 @@ static int run_base_case(const void* Q, const void* K, const void* V, void* out,
   a.exact_block = g.base_len;
   a.exact_causal = 1;
   a.merge_levels = g.levels;
+  return a;
+}
+
+static int run_base_case(const void* Q, const void* K, const void* V, void* out, float* lse, float* out_f32,
+                         const Geometry& g, void* part_o, float* part_l, hipStream_t st, long long* stamps = nullptr) {
+  AttnArgs a = base_case_args(Q, K, V, out, lse, out_f32, g, part_o, part_l);
+  a.stamps = stamps;
   return run_attention(a, kModeExact, st);
 }
 
 // ev, when non-null, receives 6 events recorded on the stream: start, after
 // prep, after hashing, after sorting, after the node attention, after the base case.
+// node_stamps / base_stamps, when non-null, select the measuring instantiation of the
+// node launch / the base-case launch and receive its workgroups' stamp records.
 static int forward_impl(const void* Q, const void* K, const void* V, void* out, float* lse, const ha_shape* sh,
                         const ha_params* p, const float* R_dev, const int32_t* samples_dev, void* ws,
-                        size_t ws_bytes, void* stream, hipEvent_t* ev = nullptr, float* out_f32 = nullptr) {
+                        size_t ws_bytes, void* stream, hipEvent_t* ev = nullptr, float* out_f32 = nullptr,
+                        long long* node_stamps = nullptr, long long* base_stamps = nullptr) {
   Geometry g;
   int rc = make_geometry(sh, p, &g);
   if (rc != HA_OK) return rc;
@@ -272,6 +282,7 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
       a.lse = lse;
       a.out_f32 = out_f32;
     }
+    a.stamps = node_stamps;
     rc = run_attention(a, kModeNode, st);
     if (rc != HA_OK) return rc;
   } else {
@@ -281,7 +292,7 @@ static int forward_impl(const void* Q, const void* K, const void* V, void* out, 
   }
   mark(4);
   if (g.causal) {
-    rc = run_base_case(Q, K, V, out, lse, out_f32, g, part_o, part_l, st);
+    rc = run_base_case(Q, K, V, out, lse, out_f32, g, part_o, part_l, st, base_stamps);
     if (rc != HA_OK) return rc;
   }
   mark(5);
@@ -578,6 +589,42 @@ int hyperattn_forward_timed(const void* Q, const void* K, const void* V, void* o
   }
   for (int i = 0; i < 6; ++i) (void)hipEventDestroy(ev[i]);
   return rc;
+}
+
+int ha_forward_workgroups(const ha_shape* shape, const ha_params* params, int64_t* node_wgs, int64_t* base_wgs) {
+  if (!node_wgs || !base_wgs) return HA_ERR_NULL;
+  Geometry g;
+  const int rc = make_geometry(shape, params, &g);
+  if (rc != HA_OK) return rc;
+  *node_wgs = *base_wgs = 0;
+  if (g.BH == 0 || g.n == 0 || !use_mfma(g)) return HA_OK;
+  AttnArgs a{};
+  a.g = g;
+  if (g.levels > 0) *node_wgs = attn_mfma_grid(a, kModeNode);
+  if (g.causal) {
+    const AttnArgs e = base_case_args(nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, g, nullptr, nullptr);
+    *base_wgs = attn_mfma_grid(e, kModeExact);
+  }
+  return HA_OK;
+}
+
+int hyperattn_forward_stamped(const void* Q, const void* K, const void* V, void* out, float* lse,
+                              const ha_shape* shape, const ha_params* params, void* workspace,
+                              size_t workspace_bytes, void* stream, int64_t* node_stamps_dev,
+                              size_t node_stamps_bytes, int64_t* base_stamps_dev, size_t base_stamps_bytes) {
+  if (!shape) return HA_ERR_NULL;
+  if (shape->dtype != HA_BF16) return HA_ERR_DTYPE;  // the instrumented kernel is the MFMA kernel
+  int64_t node_wgs = 0, base_wgs = 0;
+  const int rc = ha_forward_workgroups(shape, params, &node_wgs, &base_wgs);
+  if (rc != HA_OK) return rc;
+  const size_t rec = (size_t)kStampWords * sizeof(int64_t);
+  if ((node_wgs > 0 && !node_stamps_dev) || (base_wgs > 0 && !base_stamps_dev)) return HA_ERR_NULL;
+  if (node_stamps_bytes < (size_t)node_wgs * rec || base_stamps_bytes < (size_t)base_wgs * rec) return HA_ERR_WORKSPACE;
+  if ((((uintptr_t)node_stamps_dev) | ((uintptr_t)base_stamps_dev)) & 7) return HA_ERR_ALIGN;
+  static_assert(sizeof(long long) == sizeof(int64_t), "stamp words are 64-bit");
+  return forward_impl(Q, K, V, out, lse, shape, params, nullptr, nullptr, workspace, workspace_bytes, stream, nullptr,
+                      nullptr, node_wgs > 0 ? reinterpret_cast<long long*>(node_stamps_dev) : nullptr,
+                      base_wgs > 0 ? reinterpret_cast<long long*>(base_stamps_dev) : nullptr);
 }
 
 static int exact_forward_impl(const void* Q, const void* K, const void* V, void* out, float* lse, float* out_f32,

@@ -77,7 +77,9 @@ struct TileRegs {
 };
 
 // NW waves per workgroup (32 queries each); two waves per SIMD in either case.
-template <int D, int MODE, int NW>
+// STAMPS: the measuring instantiation, which also records counter readings at its phase
+// boundaries (a.stamps); the product launches use STAMPS = false and carry none of it.
+template <int D, int MODE, int NW, bool STAMPS = false>
 __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int kQT = 32 * NW;  // queries per workgroup
@@ -94,6 +96,17 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
   unsigned char* bufs = smem;
   int32_t* scratch = reinterpret_cast<int32_t*>(smem + 2 * L::BUF);
   int32_t* list = scratch + 16;
+
+  long long stamp_c[5] = {0, 0, 0, 0, 0}, stamp_w = 0;
+  auto stamp = [&](int i) {
+    if constexpr (STAMPS) {
+      __builtin_amdgcn_sched_barrier(0);
+      stamp_c[i] = (long long)__builtin_readcyclecounter();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  if constexpr (STAMPS) stamp_w = (long long)wall_clock64();
+  stamp(0);
 
   const int bid = logical_block(blockIdx.x, gridDim.x);
   TileWork w;
@@ -139,6 +152,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
   }
   const int ntiles = (nkeys + kKT - 1) / kKT;
   const float bias2 = (MODE == kModeNode && a.g.m > 0) ? log2f((float)w.nr.s / (float)a.g.m) : 0.f;
+  stamp(1);
 
   // ---- tile movers ----
   // K and V rows are fetched with buffer loads: a 32-bit per-lane byte offset
@@ -382,6 +396,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
   f32x16 c2[2];
   float bias_b = 0.f;
   int kt = 0;
+  stamp(2);
   for (; kt + 2 < ntiles; kt += 2) {
     body(kt, c, bias, c2, bias_b, std::true_type{});
     body(kt + 1, c2, bias_b, c, bias, std::true_type{});
@@ -392,6 +407,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
   } else if (kt + 1 == ntiles) {
     body(kt, c, bias, c2, bias_b, std::false_type{});
   }
+  stamp(3);
 
   // ---- epilogue ----
   const float l_tot = l_run + __shfl_xor(l_run, 32);
@@ -601,9 +617,20 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
   } else {
     drain(std::integral_constant<int, 0>{});
   }
+  if constexpr (STAMPS) {
+    stamp(4);
+    if (tid == 0 && a.stamps != nullptr) {
+      long long* rec = a.stamps + (int64_t)kStampWords * bid;
+#pragma unroll
+      for (int i = 0; i < 5; ++i) rec[i] = stamp_c[i];
+      rec[5] = stamp_w;
+      rec[6] = (long long)wall_clock64();
+      rec[7] = ntiles;
+    }
+  }
 }
 
-template <int D, int MODE, int NW>
+template <int D, int MODE, int NW, bool STAMPS = false>
 static int launch_one(const AttnArgs& a, hipStream_t st) {
   const int64_t grid = MODE == kModeNode ? node_grid<32 * NW>(a.g) : exact_grid<32 * NW>(a);
   if (grid <= 0) return HA_OK;
@@ -611,8 +638,8 @@ static int launch_one(const AttnArgs& a, hipStream_t st) {
   size_t lds = mfma_lds_bytes<D>(a.g.b, a.g.m, MODE);
   if (lds < (size_t)NW * EpLds<D>::WAVE) lds = (size_t)NW * EpLds<D>::WAVE;
   static std::atomic<uint64_t> lds_set{0};  // per instantiation: devices on which the LDS limit is raised
-  if (allow_full_lds(reinterpret_cast<const void*>(&attn_mfma_kernel<D, MODE, NW>), lds_set) != HA_OK) return HA_ERR_LAUNCH;
-  hipLaunchKernelGGL((attn_mfma_kernel<D, MODE, NW>), dim3((unsigned)grid), dim3(64 * NW), lds, st, a);
+  if (allow_full_lds(reinterpret_cast<const void*>(&attn_mfma_kernel<D, MODE, NW, STAMPS>), lds_set) != HA_OK) return HA_ERR_LAUNCH;
+  hipLaunchKernelGGL((attn_mfma_kernel<D, MODE, NW, STAMPS>), dim3((unsigned)grid), dim3(64 * NW), lds, st, a);
   return check_launch();
 }
 
@@ -631,8 +658,19 @@ static int launch_one(const AttnArgs& a, hipStream_t st) {
 // loops of the base case prefer two 4-wave workgroups per CU.
 constexpr int kWideExactMinRows = 8192;
 
+int64_t attn_mfma_grid(const AttnArgs& a, int mode) {
+  return mode == kModeNode ? node_grid<32 * HA_NW_NODE>(a.g) : exact_grid<32 * HA_NW_EXACT>(a);
+}
+
 int launch_attn_mfma(const AttnArgs& a, int mode, hipStream_t st) {
   if (a.g.dtype != HA_BF16) return HA_ERR_DTYPE;
+  if (a.stamps != nullptr) {  // the measuring instantiations: the four-wave forms the forward pass launches
+    if (a.g.d == 128)
+      return mode == kModeNode ? launch_one<128, kModeNode, HA_NW_NODE, true>(a, st) : launch_one<128, kModeExact, HA_NW_EXACT, true>(a, st);
+    if (a.g.d == 64)
+      return mode == kModeNode ? launch_one<64, kModeNode, HA_NW_NODE, true>(a, st) : launch_one<64, kModeExact, HA_NW_EXACT, true>(a, st);
+    return HA_ERR_SHAPE;
+  }
   const bool wide = mode == kModeExact && !a.exact_causal && a.merge_levels == 0 &&
                     a.exact_block >= kWideExactMinRows && a.exact_rows_q >= kWideExactMinRows;
   if (a.g.d == 128) {

@@ -108,7 +108,15 @@ struct AttnArgs {
   int32_t exact_block;                 // rows per independent diagonal block (== rows for full attention)
   int32_t exact_causal;
   int32_t merge_levels;                // exact mode: merge part_o/part_l of this many levels into the result
+  // measurement only (null in every product call): kStampWords 64-bit words per workgroup, indexed by the
+  // workgroup's logical tile number, written by the instrumented instantiation of the MFMA kernel
+  long long* stamps;
 };
+
+// Words of a workgroup's stamp record: shader-clock readings at entry, after the key list is built,
+// before the tile loop (first scores done), after the loop and at the end; the constant-rate
+// counter at entry and at the end; the number of key tiles.
+constexpr int kStampWords = HA_STAMP_WORDS;
 
 // launchers (defined in the .hip files)
 int launch_lsh_hash(const void* X, uint8_t* codes, int64_t rows, int d, int dtype, const float* R_dev,
@@ -124,6 +132,7 @@ int launch_seg_sort_flat(const uint8_t* codes, int32_t* perm, int32_t* pos, int 
 int launch_prep(float* R_ws, const float* R_dev, const uint16_t* R_bf16_host, int32_t* samples_ws,
                 const int32_t* samples_dev, const Geometry& g, uint64_t seed, hipStream_t st);
 int launch_attn_mfma(const AttnArgs& a, int mode, hipStream_t st);
+int64_t attn_mfma_grid(const AttnArgs& a, int mode);  // workgroups of the four-wave launch of that mode
 int launch_attn_generic(const AttnArgs& a, int mode, hipStream_t st);
 int launch_gather_rows(const void* src, const int32_t* idx, void* dst, int groups, int n, int d, int dtype,
                        hipStream_t st);

@@ -11,6 +11,8 @@ does not average out, may an element also use the allowance
 number of elements that need the allowance is printed and must stay below
 0.5 % (measured: at most 0.17 %); everywhere else the plain criterion is the
 assertion."""
+import ctypes
+
 import numpy as np
 import pytest
 
@@ -487,6 +489,48 @@ def test_forward_and_backward_replay_in_a_hip_graph(ha, torch):
         same += [torch.equal(a.view(torch.int16), c.view(torch.int16)) for a, c in zip(g_bufs["grads"], e_bufs["grads"])]
         assert all(same), (rep, same)
         assert torch.isfinite(g_bufs["out"].float()).all()
+
+
+def test_stamped_forward_equals_the_forward_and_its_stamps_are_ordered(ha, torch):
+    """The instrumented instantiation of the attention kernel computes what the product one does, bit for bit,
+    and every workgroup's record is consistent: clock readings in phase order, the tile counts of the causal
+    base case (query tile i of a block sees 2 (i + 1) key tiles) and of the nodes (block keys plus kept samples)."""
+    print("stamped forward", flush=True)
+    B, H, n, d, b, m, r, n_min = 1, 3, 4096, 128, 256, 128, 5, 1024
+    kw = dict(causal=True, n_min=n_min, seed=9)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(21)
+    Q, K, V = [(torch.randn((B, H, n, d), generator=gen, device="cuda") * d ** -0.25).to(torch.bfloat16) for _ in range(3)]
+    out, lse = ha.hyperattn_forward(Q, K, V, b, m, r, **kw)
+    out2, lse2, node_st, base_st = ha.hyperattn_forward_stamped(Q, K, V, b, m, r, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16)) and torch.equal(lse, lse2)
+    levels = 2                                        # 4096 -> 2048 -> 1024 = n_min
+    assert node_st.shape == (levels * B * H * (n // 2) // 128, ha.STAMP_WORDS)
+    assert base_st.shape == (B * H * n // 128, ha.STAMP_WORDS)
+    for st in (node_st.cpu().numpy(), base_st.cpu().numpy()):
+        c = st[:, :5]
+        assert (np.diff(c, axis=1) >= 0).all() and (c[:, 0] > 0).all()
+        assert (st[:, 6] >= st[:, 5]).all()
+        assert ((c[:, 4] - c[:, 0]) < 50_000_000).all()       # a workgroup lives microseconds, not seconds
+    tiles = np.sort(base_st[:, 7].cpu().numpy())
+    per_block = n_min // 128
+    want = np.sort(np.tile(2 * (np.arange(per_block) + 1), B * H * n // n_min))
+    assert np.array_equal(tiles, want)
+    nt = node_st[:, 7].cpu().numpy()
+    assert (nt >= b // 64).all() and (nt <= (b + m) // 64).all() and (nt > b // 64).any()
+    # fp32 tensors have no instrumented kernel; a short record buffer is refused
+    with pytest.raises(ha.HyperAttnError):
+        ha.hyperattn_forward_stamped(Q.float(), K.float(), V.float(), b, m, r, **kw)
+    shape = ha.make_shape(B, H, n, d, ha.HA_BF16)
+    params = ha.make_params(b, m, r, True, n_min, 9)
+    assert ha.ha_forward_workgroups(shape, params) == (node_st.shape[0], base_st.shape[0])
+    ws = ha.alloc_workspace(shape, params)
+    rc = ha.lib().hyperattn_forward_stamped(Q.data_ptr(), K.data_ptr(), V.data_ptr(), out2.data_ptr(), lse2.data_ptr(),
+                                            ctypes.byref(shape), ctypes.byref(params), ws.data_ptr(), ws.numel(), None, node_st.data_ptr(),
+                                            node_st.numel() * 8 - 8, base_st.data_ptr(), base_st.numel() * 8)
+    assert rc != 0
+    torch.cuda.synchronize()
 
 
 def test_measurement_aids(ha, torch):

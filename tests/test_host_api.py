@@ -98,6 +98,21 @@ def test_backward_workspace_layout(ha):
     assert ha.ha_backward_workspace_bytes(sh, p0) == rows * 4
 
 
+def test_forward_workgroup_counts(ha):
+    """Records of the stamped forward: one per 128-query tile of every node (levels x half the rows when causal)
+    and of the base case; none for fp32 tensors, which run the kernel without matrix cores."""
+    p = ha.make_params(256, 256, 7, True, 4096, 0)
+    assert ha.ha_forward_workgroups(ha.make_shape(1, 32, 131072, 128, ha.HA_BF16), p) == (5 * 32 * 65536 // 128, 32 * 131072 // 128)
+    assert ha.ha_forward_workgroups(ha.make_shape(1, 32, 131072, 128, ha.HA_FP32), p) == (0, 0)
+    pu = ha.make_params(256, 256, 7, False, 4096, 0)
+    assert ha.ha_forward_workgroups(ha.make_shape(2, 4, 32768, 64, ha.HA_BF16), pu) == (8 * 32768 // 128, 0)
+    assert ha.ha_forward_workgroups(ha.make_shape(1, 0, 32768, 64, ha.HA_BF16), pu) == (0, 0)
+    nw, bw = ctypes.c_int64(0), ctypes.c_int64(0)
+    bad = ha.make_shape(1, 1, 1000, 64, ha.HA_BF16)
+    assert ha.lib().ha_forward_workgroups(ctypes.byref(bad), ctypes.byref(pu), ctypes.byref(nw), ctypes.byref(bw)) == -3
+    assert ha.lib().ha_forward_workgroups(ctypes.byref(bad), ctypes.byref(pu), None, ctypes.byref(bw)) != 0
+
+
 @pytest.mark.parametrize("shape,params,status", [
     ((1, 1, 1024, 96, 0), (64, 64, 7, 0, 4096, 0), -3),     # d not 64/128
     ((1, 1, 1000, 64, 0), (64, 64, 7, 0, 4096, 0), -3),     # n % b
