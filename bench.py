@@ -368,7 +368,8 @@ def phases(args, torch, ha):
         for name, sel in groups(tiles):
             if not sel.any():
                 continue
-            loop_tiles = np.maximum(tiles[sel] - 1, 1)   # the first score tile is computed ahead of the loop
+            # the loop forms tiles - 1 score tiles (the first one is computed ahead of it) and tiles P V products
+            loop_tiles = np.maximum(tiles[sel] - 0.5, 0.5)
             rows.append({"workgroups": name, "count": int(sel.sum()), "tiles": float(tiles[sel].mean()),
                          "cycles_life": float(life[sel].mean()),
                          "cycles_key_list": float(ph[sel, 0].mean()),

@@ -95,13 +95,37 @@ __host__ __device__ inline int64_t exact_grid(const AttnArgs& a) {
 
 constexpr int64_t kMaxGrid = 0x7fffffff;  // workgroup ids are decoded as 32-bit integers
 
+// The first index values a thread contributes to the key list (block key `tid`, sample `tid` and
+// its sorted block): fetched ahead of the list's construction so that a caller can put other
+// loads of the same round trip in flight beside them.
+struct KeyListHead {
+  int pk0, l0, blk0;
+};
+
+template <int NT>
+__device__ inline KeyListHead key_list_fetch(const AttnArgs& a, const TileWork& w) {
+  const Geometry& g = a.g;
+  const int tid = threadIdx.x;
+  const int nb = a.use_block ? g.b : 0;
+  const int m = (a.samples != nullptr) ? g.m : 0;
+  KeyListHead kh{0, 0, 0};
+  if (tid < nb) kh.pk0 = a.perm_k ? a.perm_k[w.seg_off + w.t * g.b + tid] : w.nr.k_start + w.t * g.b + tid;
+  if (tid < m) {
+    kh.l0 = a.samples[(int64_t)w.nr.heap * g.m + tid];
+    if (a.samp_blk) kh.blk0 = a.samp_blk[((int64_t)w.bh * g.total_nodes + w.nr.heap) * g.m + tid];
+    else kh.blk0 = (a.pos_k ? a.pos_k[w.seg_off + kh.l0] : kh.l0) / g.b;
+  }
+  return kh;
+}
+
 // Builds the key list of a node tile in LDS.  `list` has room for b + m entries
 // rounded up to a multiple of 64; `scratch` for (NT/64 + 1) ints.  All NT
 // threads call it; on return (after its final barrier) list[0..pad) holds row
 // indices within the head, *nb_out the block keys and the return value nkeys.
+// `kh` = key_list_fetch's values of the calling thread.
 template <int NT>
 __device__ inline int build_key_list(const AttnArgs& a, const TileWork& w, int32_t* list, int32_t* scratch,
-                                     int* nb_out) {
+                                     int* nb_out, const KeyListHead& kh) {
   const Geometry& g = a.g;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -117,11 +141,7 @@ __device__ inline int build_key_list(const AttnArgs& a, const TileWork& w, int32
     else *blk = (a.pos_k ? a.pos_k[w.seg_off + l] : l) / g.b;
     return l;
   };
-  // the first chunk of both sources is fetched before anything is consumed, so
-  // the two global round trips overlap (b, m <= NT is the common case)
-  int pk0 = 0, l0 = 0, blk0 = 0;
-  if (tid < nb) pk0 = block_key(tid);
-  if (tid < m) l0 = sample_of(tid, &blk0);
+  const int pk0 = kh.pk0, l0 = kh.l0, blk0 = kh.blk0;
   if (tid < nb) list[tid] = pk0;
   for (int i = tid + NT; i < nb; i += NT) list[i] = block_key(i);
   int base = nb;
@@ -153,6 +173,12 @@ __device__ inline int build_key_list(const AttnArgs& a, const TileWork& w, int32
   __syncthreads();
   *nb_out = nb;
   return nkeys;
+}
+
+template <int NT>
+__device__ inline int build_key_list(const AttnArgs& a, const TileWork& w, int32_t* list, int32_t* scratch,
+                                     int* nb_out) {
+  return build_key_list<NT>(a, w, list, scratch, nb_out, key_list_fetch<NT>(a, w));
 }
 
 __device__ inline uint32_t pack_bf16x2(float lo, float hi) {

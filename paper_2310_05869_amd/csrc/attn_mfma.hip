@@ -118,7 +118,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
   const uint16_t* Vh = reinterpret_cast<const uint16_t*>(a.V) + (int64_t)w.bh * a.k_bh_stride;
 
   // ---- this lane's query row: B operand of S^T = K Q^T, kept in registers.
-  // Issued first so the (gathered) row is in flight while the key list is built.
+  // Node mode: the key list's first index values and the row's own index (through P_Q) travel
+  // in one round trip; the (gathered) row is then in flight while the key list is built.
+  KeyListHead klh{0, 0, 0};
+  if (MODE == kModeNode) klh = key_list_fetch<kNT>(a, w);
   const int r_in_tile = wave * 32 + lq;
   RowDest dest;
   int qrow_load;   // row to load (always a valid row)
@@ -145,7 +148,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
 
   int nb, nkeys;
   if (MODE == kModeNode) {
-    nkeys = build_key_list<kNT>(a, w, list, scratch, &nb);
+    nkeys = build_key_list<kNT>(a, w, list, scratch, &nb, klh);
   } else {
     nkeys = max(0, w.k1 - w.k0);
     nb = 0x7fffffff;
@@ -506,14 +509,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
           const int64_t at = pr * D + 32 * dt + 8 * g4 + 4 * h;
-          f32x4 v;
-          if (a.part_bf16) {
-            const u32x2 raw = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint16_t*>(a.part_o) + at);
-            v = (f32x4){__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xFFFF0000u),
-                        __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xFFFF0000u)};
-          } else {
-            v = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(a.part_o) + at);
-          }
+          const u32x2 raw = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint16_t*>(a.part_o) + at);
+          const f32x4 v = {__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xFFFF0000u),
+                           __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xFFFF0000u)};
           o[dt][4 * g4] += wl * v.x;
           o[dt][4 * g4 + 1] += wl * v.y;
           o[dt][4 * g4 + 2] += wl * v.z;
@@ -528,7 +526,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
 
   unsigned char* dst_base = to_partial ? reinterpret_cast<unsigned char*>(a.part_o) : reinterpret_cast<unsigned char*>(a.out);
   if (dst_base == nullptr) return;
-  const bool out_fp32 = to_partial && !a.part_bf16;
+  const bool out_fp32 = to_partial && !a.part_bf16;  // the stage calls take their partial rows in fp32
   constexpr int rs = EpLds<D>::ROW;
   if (h == 0) ep_rows[lq] = dest.valid ? row_dst : (int64_t)-1;
 #pragma unroll
@@ -543,59 +541,66 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   constexpr int CH = D / 8;  // 8-element pieces per row
-  // NF = number of partial rows folded into every row; a compile-time count so
-  // that all their loads are issued before the first is consumed
+  // NF = number of partial rows folded into every row (bf16 rows of the node launch); a compile-time
+  // count, and the pieces of a lane walked in groups whose partial-row loads are ALL issued before
+  // the first is consumed: one global round trip per group instead of one per piece.  The loads are
+  // unconditional (a row that is not stored re-reads the wave's first row) and only the stores are
+  // guarded: with loads under a branch the compiler's wait counts fall back to "everything", which
+  // also waits for the previous piece's stores to reach memory.
+  if (ep_rows[0] < 0) return;  // a wave whose rows all lie past the end (valid rows are a prefix)
   auto drain = [&](auto nf_tag) {
     constexpr int NF = decltype(nf_tag)::value;
-    int64_t prc[NF > 0 ? NF : 1];
+    constexpr int IT = 32 * CH / 64;                 // pieces per lane
+    constexpr int GROUP = NF <= 4 ? IT : IT / 2;     // 16-byte loads in flight per lane: GROUP * NF <= 32
+    const uint16_t* prow[NF > 0 ? NF : 1];
 #pragma unroll
-    for (int c = 0; c < NF; ++c) prc[c] = ep_pr[c];
-#pragma unroll 2
-    for (int idx = lane; idx < 32 * CH; idx += 64) {
-      const int row = idx / CH, ch = idx % CH;
-      const int64_t r64 = ep_rows[row];
-      if (r64 < 0) continue;
-      u32x4 raw[NF > 0 ? NF : 1][2];
+    for (int c = 0; c < NF; ++c) prow[c] = reinterpret_cast<const uint16_t*>(a.part_o) + ep_pr[c] * D;
 #pragma unroll
-      for (int c = 0; c < NF; ++c) {
-        const int64_t at = (prc[c] + row) * D + ch * 8;
-        if (a.part_bf16) {
-          raw[c][0] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(a.part_o) + at);
-        } else {
-          raw[c][0] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const float*>(a.part_o) + at);
-          raw[c][1] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const float*>(a.part_o) + at + 4);
-        }
+    for (int g0 = 0; g0 < IT; g0 += GROUP) {
+      int64_t r64[GROUP];
+      u32x4 raw[GROUP][NF > 0 ? NF : 1];
+#pragma unroll
+      for (int it = 0; it < GROUP; ++it) {
+        const int idx = lane + 64 * (g0 + it);
+        const int row = idx / CH, ch = idx % CH;
+        r64[it] = ep_rows[row];
+        const int row_ld = r64[it] >= 0 ? row : 0;
+#pragma unroll
+        for (int c = 0; c < NF; ++c) raw[it][c] = *reinterpret_cast<const u32x4*>(prow[c] + row_ld * D + ch * 8);
       }
-      f32x4 v0 = *reinterpret_cast<const f32x4*>(ep + row * rs + ch * 32);
-      f32x4 v1 = *reinterpret_cast<const f32x4*>(ep + row * rs + ch * 32 + 16);
 #pragma unroll
-      for (int c = 0; c < NF; ++c) {
-        const float wl = ep_w[row * kMaxFold + c];
-        f32x4 p0, p1;
-        if (a.part_bf16) {
-          const u32x4 q = raw[c][0];
-          p0 = (f32x4){__uint_as_float(q.x << 16), __uint_as_float(q.x & 0xFFFF0000u),
-                       __uint_as_float(q.y << 16), __uint_as_float(q.y & 0xFFFF0000u)};
-          p1 = (f32x4){__uint_as_float(q.z << 16), __uint_as_float(q.z & 0xFFFF0000u),
-                       __uint_as_float(q.w << 16), __uint_as_float(q.w & 0xFFFF0000u)};
-        } else {
-          p0 = __builtin_bit_cast(f32x4, raw[c][0]);
-          p1 = __builtin_bit_cast(f32x4, raw[c][1]);
-        }
-        if (wl != 0.f) {  // a partial with an empty row sum carries no defined values
+      for (int it = 0; it < GROUP; ++it) {
+        const int idx = lane + 64 * (g0 + it);
+        const int row = idx / CH, ch = idx % CH;
+        f32x4 v0 = *reinterpret_cast<const f32x4*>(ep + row * rs + ch * 32);
+        f32x4 v1 = *reinterpret_cast<const f32x4*>(ep + row * rs + ch * 32 + 16);
+#pragma unroll
+        for (int c = 0; c < NF; ++c) {
+          float wl = ep_w[row * kMaxFold + c];
+          const u32x4 q = raw[it][c];
+          f32x4 p0 = {__uint_as_float(q.x << 16), __uint_as_float(q.x & 0xFFFF0000u),
+                      __uint_as_float(q.y << 16), __uint_as_float(q.y & 0xFFFF0000u)};
+          f32x4 p1 = {__uint_as_float(q.z << 16), __uint_as_float(q.z & 0xFFFF0000u),
+                      __uint_as_float(q.w << 16), __uint_as_float(q.w & 0xFFFF0000u)};
+          if (!(wl != 0.f)) {  // a partial with an empty row sum carries no defined values
+            p0 = (f32x4){0.f, 0.f, 0.f, 0.f};
+            p1 = p0;
+            wl = 0.f;
+          }
           v0 += wl * p0;
           v1 += wl * p1;
         }
-      }
-      if (out_fp32) {
-        f32x4* dp = reinterpret_cast<f32x4*>(dst_base + (r64 * D + ch * 8) * 4);
-        dp[0] = v0;
-        dp[1] = v1;
-      } else {
+        if (r64[it] < 0) continue;
+        if (out_fp32) {
+          f32x4* dp = reinterpret_cast<f32x4*>(dst_base + (r64[it] * D + ch * 8) * 4);
+          dp[0] = v0;
+          dp[1] = v1;
+          continue;
+        }
         const u32x4 pk = {pack_bf16x2(v0.x, v0.y), pack_bf16x2(v0.z, v0.w), pack_bf16x2(v1.x, v1.y), pack_bf16x2(v1.z, v1.w)};
-        *reinterpret_cast<u32x4*>(dst_base + (r64 * D + ch * 8) * 2) = pk;
+        *reinterpret_cast<u32x4*>(dst_base + (r64[it] * D + ch * 8) * 2) = pk;
         if (!to_partial && a.out_f32 != nullptr) {  // unrounded copy of the final output, for the backward's delta
-          f32x4* fp = reinterpret_cast<f32x4*>(a.out_f32 + r64 * D + ch * 8);
+          f32x4* fp = reinterpret_cast<f32x4*>(a.out_f32 + r64[it] * D + ch * 8);
           fp[0] = v0;
           fp[1] = v1;
         }
@@ -664,6 +669,7 @@ int64_t attn_mfma_grid(const AttnArgs& a, int mode) {
 
 int launch_attn_mfma(const AttnArgs& a, int mode, hipStream_t st) {
   if (a.g.dtype != HA_BF16) return HA_ERR_DTYPE;
+  if (mode == kModeExact && a.merge_levels > 0 && !a.part_bf16) return HA_ERR_DTYPE;  // this kernel folds bf16 partial rows
   if (a.stamps != nullptr) {  // the measuring instantiations: the four-wave forms the forward pass launches
     if (a.g.d == 128)
       return mode == kModeNode ? launch_one<128, kModeNode, HA_NW_NODE, true>(a, st) : launch_one<128, kModeExact, HA_NW_EXACT, true>(a, st);
