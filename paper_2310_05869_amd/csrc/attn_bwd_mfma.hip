@@ -112,8 +112,8 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
     const int tpb = (eb + kRT - 1) / kRT;
     const int nblk = (f.exact_rows_q + eb - 1) / eb;
     const int idx = logical_block(blockIdx.x, gridDim.x);
-    const int ktile = idx % tpb;
     const int rest = idx / tpb;
+    const int ktile = (idx % tpb + rest) % tpb;  // starting tile rotated per block: see decode_exact_tile
     const int blk = rest % nblk;
     w.bh = rest / nblk;
     w.q0 = blk * eb + ktile * kRT;  // first KEY row of this tile
