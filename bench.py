@@ -363,7 +363,7 @@ def phases(args, torch, ha):
         ph = np.diff(c, axis=1)                     # list, gathers + first scores, loop, epilogue
         life = c[:, 4] - c[:, 0]
         ticks = st[:, 6] - st[:, 5]                 # 10 ns units
-        tiles = st[:, 7]
+        tiles = ha.stamp_place(st[:, 7])[0]
         rows = []
         for name, sel in groups(tiles):
             if not sel.any():
@@ -380,17 +380,58 @@ def phases(args, torch, ha):
                          "shader_clock_GHz": float((life[sel] / np.maximum(ticks[sel], 1)).mean() / 10.0)})
         return rows
 
+    def residency(st):
+        """How the launch's workgroups reached the CUs, from where and when each ran: share of the launch during
+        which a CU held 0 / 1 / 2 of them, time until a finished workgroup was replaced, and the work (key tiles)
+        each shader engine of an XCD was given."""
+        st = st.cpu().numpy().astype(np.int64)
+        if st.shape[0] == 0:
+            return None
+        tiles, xcd, se, cu = ha.stamp_place(st[:, 7])
+        t0, t1 = st[:, 5], st[:, 6]
+        start, span = t0.min(), t1.max() - t0.min()
+        key = (xcd * 8 + se) * 16 + cu
+        held = np.zeros(3)
+        gaps, ends = [], []
+        for k in np.unique(key):
+            a, b = np.sort(t0[key == k]), np.sort(t1[key == k])
+            ev = np.concatenate([np.stack([a, np.ones_like(a)], 1), np.stack([b, -np.ones_like(b)], 1)])
+            ev = ev[np.argsort(ev[:, 0], kind="stable")]
+            c, last = 0, start
+            for t, dv in ev:
+                held[min(c, 2)] += t - last
+                last, c = t, c + int(dv)
+            held[0] += start + span - last
+            if len(a) > 2:
+                gaps.append(a[2:] - b[:-2])      # the i-th end frees a slot for the (i + 2)-th start (two slots per CU)
+            ends.append(b.max() - start)
+        gaps = np.concatenate(gaps) if gaps else np.zeros(1)
+        per_se = [[int(tiles[(xcd == x) & (se == e)].sum()) for e in np.unique(se)] for x in np.unique(xcd)]
+        xcd_end = [float((t1[xcd == x].max() - start) / span) for x in np.unique(xcd)]
+        return {"CUs": int(len(np.unique(key))), "span_ms": float(span) * 1e-5,
+                "share_of_launch_with_0_1_2_resident": [float(v) for v in held / held.sum()],
+                "replacement_us_mean_median_p90": [float(gaps.mean()) * 0.01, float(np.median(gaps)) * 0.01,
+                                                   float(np.percentile(gaps, 90)) * 0.01],
+                "workgroups_per_engine_xcd0": [int(((xcd == xcd.min()) & (se == e)).sum()) for e in np.unique(se)],
+                "key_tiles_per_engine_by_xcd": per_se,
+                "xcd_end_over_span": xcd_end,
+                "cu_last_end_over_span_min_mean": [float(np.min(ends) / span), float(np.mean(ends) / span)]}
+
     node = summary(node_st, lambda t: [("all", t >= 0)])
     base = summary(base_st, lambda t: [("all", t >= 0), ("2-16 tiles", t <= 16), ("17-48 tiles", (t > 16) & (t <= 48)),
                                        ("49-64 tiles", t > 48)])
     res = {"metric": "attention workgroup phases", "unit": "shader cycles (mean over the launch's workgroups)",
            "n_gpus": 1, "config": {"workload": args.workload, "B": B, "H": H, "n": n, "d": d},
            "node_launch": node, "base_case_launch": base,
+           "node_residency": residency(node_st), "base_case_residency": residency(base_st),
            "stamped_forward_ms": e0.elapsed_time(e1),
            "product_stage_ms_median": {k: float(np.median(v)) for k, v in stage.items()}}
     for k in ("node_launch", "base_case_launch"):
         for row in res[k] or []:
             log(f"[bench] {k} {row}")
+    for k in ("node_residency", "base_case_residency"):
+        if res[k]:
+            log(f"[bench] {k} {res[k]}")
     print(json.dumps(res), flush=True)
 
 

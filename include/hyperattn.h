@@ -169,7 +169,9 @@ int hyperattn_forward_timed(const void* Q, const void* K, const void* V, void* o
  *   samples) is built, [2] before the loop over key tiles (rows gathered, first
  *   score tile done), [3] after the loop, [4] at the end (results stored);
  *   [5], [6] the constant-rate counter (100 MHz) at entry and at the end;
- *   [7] the number of 64-key tiles of the workgroup.
+ *   [7] bits 0-15 the number of 64-key tiles of the workgroup; bits 16-47 the hardware id
+ *   register of its first wave (bits 8-11 of that value: CU, 13-15: shader engine);
+ *   bits 48-51 the number of its XCD.
  * ha_forward_workgroups gives the number of records of either launch (0 for a launch
  * the problem does not have, and for fp32 tensors); node_stamps_dev / base_stamps_dev
  * are device memory of at least that many records (sizes in bytes, checked:

@@ -345,7 +345,12 @@ def hyperattn_forward_timed(Q, K, V, b, m, r, causal=False, n_min=4096, seed=0, 
 
 STAMP_WORDS = 8
 STAMP_NAMES = ("cycles_entry", "cycles_list", "cycles_loop", "cycles_epilogue", "cycles_end", "ticks_entry", "ticks_end",
-               "tiles")
+               "tiles_and_place")
+
+
+def stamp_place(word):
+    """Splits word 7 of stamp records (an int64 numpy array or tensor): tiles, XCD, shader engine, CU."""
+    return word & 0xFFFF, (word >> 48) & 0xF, (word >> (16 + 13)) & 0x7, (word >> (16 + 8)) & 0xF
 
 
 def ha_forward_workgroups(shape, params):

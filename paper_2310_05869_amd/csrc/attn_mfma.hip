@@ -630,7 +630,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
       for (int i = 0; i < 5; ++i) rec[i] = stamp_c[i];
       rec[5] = stamp_w;
       rec[6] = (long long)wall_clock64();
-      rec[7] = ntiles;
+      // where it ran: the hardware id register (wave, SIMD, CU, shader engine) and the XCD number
+      const unsigned hw = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));   // HW_ID, all 32 bits
+      const unsigned xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));  // XCC_ID, bits 0-3
+      rec[7] = (long long)(ntiles & 0xffff) | ((long long)hw << 16) | ((long long)(xcc & 15u) << 48);
     }
   }
 }

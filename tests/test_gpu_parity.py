@@ -513,11 +513,12 @@ def test_stamped_forward_equals_the_forward_and_its_stamps_are_ordered(ha, torch
         assert (np.diff(c, axis=1) >= 0).all() and (c[:, 0] > 0).all()
         assert (st[:, 6] >= st[:, 5]).all()
         assert ((c[:, 4] - c[:, 0]) < 50_000_000).all()       # a workgroup lives microseconds, not seconds
-    tiles = np.sort(base_st[:, 7].cpu().numpy())
+    tiles = np.sort(ha.stamp_place(base_st[:, 7].cpu().numpy())[0])
     per_block = n_min // 128
     want = np.sort(np.tile(2 * (np.arange(per_block) + 1), B * H * n // n_min))
     assert np.array_equal(tiles, want)
-    nt = node_st[:, 7].cpu().numpy()
+    nt, xcd, se, cu = ha.stamp_place(node_st[:, 7].cpu().numpy())
+    assert (xcd < 8).all() and len(set(zip(xcd.tolist(), se.tolist(), cu.tolist()))) <= 256
     assert (nt >= b // 64).all() and (nt <= (b + m) // 64).all() and (nt > b // 64).any()
     # fp32 tensors have no instrumented kernel; a short record buffer is refused
     with pytest.raises(ha.HyperAttnError):
