@@ -442,24 +442,45 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
         *reinterpret_cast<f32x4*>(ep + lq * L::EP_ROW + col * 4) = v;
       }
     float* dst32 = kWantDs ? a.out1 : a.out2;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // Rows that are not stored (past the end of the tile; valid rows are a prefix) re-read the wave's first
+    // row, so that every load below is unconditional and all of them are requested before the first is
+    // used; only the stores sit under a branch.  With loads under a branch the compiler's wait counts
+    // fall back to "everything", and each piece would also wait for the previous piece's stores.
+    const int64_t row_first = ep_rows[0];
+    if (row_first < 0) return;
     if (!kExact) {
       // node passes add to what earlier levels left in the row; all rows of a node lie on the same side of
       // every ancestor, so the whole workgroup either adds or writes
       bool add = false;
       if (MODE == kBwdDqNode) add = node_levels_hold(g, w.nr.q_start, true, w.level);
       if (MODE == kBwdDkvBlock) add = node_levels_hold(g, w.nr.k_start, false, w.level);
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      constexpr int CH = D / 4;  // 16-byte pieces per fp32 row
-      for (int idx = lane; idx < 32 * CH; idx += 64) {
+      constexpr int CH = D / 4;            // 16-byte pieces per fp32 row
+      constexpr int IT = 32 * CH / 64;     // pieces per lane
+      int64_t r64[IT];
+      f32x4 prev[IT];
+#pragma unroll
+      for (int it = 0; it < IT; ++it) {
+        const int idx = lane + 64 * it;
+        r64[it] = ep_rows[idx / CH];
+        prev[it] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      }
+      if (add) {
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+          const int ch = (lane + 64 * it) % CH;
+          const int64_t rr = r64[it] >= 0 ? r64[it] : row_first;
+          prev[it] = *reinterpret_cast<const f32x4*>(dst32 + rr * D + ch * 4);
+        }
+      }
+#pragma unroll
+      for (int it = 0; it < IT; ++it) {
+        const int idx = lane + 64 * it;
         const int row = idx / CH, ch = idx % CH;
-        const int64_t r64 = ep_rows[row];
-        if (r64 < 0) continue;
-        f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 16);
-        f32x4* dp = reinterpret_cast<f32x4*>(dst32 + r64 * D + ch * 4);
-        if (add) v += *dp;
-        *dp = v;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 16) + prev[it];
+        if (r64[it] >= 0) *reinterpret_cast<f32x4*>(dst32 + r64[it] * D + ch * 4) = v;
       }
       return;
     }
@@ -469,23 +490,34 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
     const int i0 = w.q0 + 32 * __builtin_amdgcn_readfirstlane(wave);
     const bool fold = lvl != nullptr && node_levels_hold(g, i0, kDq, g.levels);
     const float* acc_rows = lvl + ((int64_t)w.bh * g.n + i0) * D;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    constexpr int CH8 = D / 8;  // 8-element pieces per row
-    for (int idx = lane; idx < 32 * CH8; idx += 64) {
-      const int row = idx / CH8, ch = idx % CH8;
-      const int64_t r64 = ep_rows[row];
-      if (r64 < 0) continue;
-      f32x4 v0 = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 32);
-      f32x4 v1 = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 32 + 16);
-      if (fold) {
+    constexpr int CH8 = D / 8;             // 8-element pieces per row
+    constexpr int IT8 = 32 * CH8 / 64;     // pieces per lane
+    int64_t r64[IT8];
+    f32x4 p0[IT8], p1[IT8];
+#pragma unroll
+    for (int it = 0; it < IT8; ++it) {
+      r64[it] = ep_rows[(lane + 64 * it) / CH8];
+      p0[it] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      p1[it] = p0[it];
+    }
+    if (fold) {
+#pragma unroll
+      for (int it = 0; it < IT8; ++it) {
+        const int idx = lane + 64 * it;
+        const int row = r64[it] >= 0 ? idx / CH8 : 0, ch = idx % CH8;
         const float* pp = acc_rows + (int64_t)row * D + ch * 8;
-        v0 += *reinterpret_cast<const f32x4*>(pp);
-        v1 += *reinterpret_cast<const f32x4*>(pp + 4);
+        p0[it] = *reinterpret_cast<const f32x4*>(pp);
+        p1[it] = *reinterpret_cast<const f32x4*>(pp + 4);
       }
+    }
+#pragma unroll
+    for (int it = 0; it < IT8; ++it) {
+      const int idx = lane + 64 * it;
+      const int row = idx / CH8, ch = idx % CH8;
+      const f32x4 v0 = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 32) + p0[it];
+      const f32x4 v1 = *reinterpret_cast<const f32x4*>(ep + row * L::EP_ROW + ch * 32 + 16) + p1[it];
       const u32x4 pk = {pack_bf16x2(v0.x, v0.y), pack_bf16x2(v0.z, v0.w), pack_bf16x2(v1.x, v1.y), pack_bf16x2(v1.z, v1.w)};
-      *reinterpret_cast<u32x4*>(dst16 + r64 * D + ch * 8) = pk;
+      if (r64[it] >= 0) *reinterpret_cast<u32x4*>(dst16 + r64[it] * D + ch * 8) = pk;
     }
   };
   if constexpr (WHAT == kAccBoth) {
