@@ -303,7 +303,14 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
     const float shift = bias - ((m_run == -INFINITY) ? 0.f : m_run);
 
     // ---- scores of tile kt+1 (matrix cores)  ||  weights of tile kt (vector ALU) ----
+    // The wave takes issue priority over its SIMD neighbour for this block, its densest one (an MFMA and a
+    // slice of exponentials per slot), and gives it back for the P V block, whose slots the neighbour's
+    // vector work fills: measured -3 % on the causal base case, -2 % on the node launch (any of the
+    // neighbouring placements of the two instructions measured the same; priority during P V alone: no gain;
+    // the d = 64 node launch, where vector issue binds, loses 2 % with it and goes without).
+    constexpr bool kPrio = D == 128 || MODE == kModeExact;
     bf16x8 pf[4];
+    if constexpr (kPrio) __builtin_amdgcn_s_setprio(1);
     {
       if (HN) {
 #pragma unroll
@@ -358,6 +365,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
         }
       }
     }
+    if constexpr (kPrio) __builtin_amdgcn_s_setprio(0);
     if (HN) mask_tile(cn, kt + 1, bias_n);
 
     // ---- O^T += V^T P^T of tile kt (matrix cores)  ||  row maximum of tile kt+1 ----
