@@ -346,6 +346,10 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
           cs[i] = 0.f;
           es[i] = 0.f;
         }
+        // the wave holds issue priority over its SIMD neighbour while it issues its S^T / dP^T products (measured:
+        // dQ of the base case -9 %, its dK / dV -3 %; the short loops of the block passes lose 1-2 % and go without)
+        constexpr bool kPrio = kExact || MODE == kBwdDkvSamp;
+        if constexpr (kPrio) __builtin_amdgcn_s_setprio(1);
         {
           const unsigned char* yp0 = yb + (32 * sub + lq) * L::TSTR + 16 * h;
           const unsigned char* bp0 = bb + (32 * sub + lq) * L::TSTR + 16 * h;
@@ -356,6 +360,7 @@ __global__ __launch_bounds__(kBNT, 2) void attn_bwd_kernel(BwdArgs a) {
               es = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(bp0 + 32 * j), areg[j], es, 0, 0, 0);
           }
         }
+        if constexpr (kPrio) __builtin_amdgcn_s_setprio(0);
         f32x4 nlq = {0.f, 0.f, 0.f, 0.f}, dq4 = {0.f, 0.f, 0.f, 0.f};  // -L log2(e), delta of four T rows (dK/dV passes)
   #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
