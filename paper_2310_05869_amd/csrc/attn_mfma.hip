@@ -76,11 +76,11 @@ struct TileRegs {
   static constexpr int NKC = kKT * CPR / NT;     // K (and V) chunks per thread
 };
 
-// NW waves per workgroup (32 queries each); two waves per SIMD in either case.
+// NW waves per workgroup (32 queries each); two waves per SIMD at d = 128, three (four-wave workgroups) at d = 64.
 // STAMPS: the measuring instantiation, which also records counter readings at its phase
 // boundaries (a.stamps); the product launches use STAMPS = false and carry none of it.
 template <int D, int MODE, int NW, bool STAMPS = false>
-__global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
+__global__ __launch_bounds__(64 * NW, (D == 64 && NW == 4) ? 3 : 2) void attn_mfma_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int kQT = 32 * NW;  // queries per workgroup
   constexpr int kNT = 64 * NW;  // threads
@@ -287,11 +287,12 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
   auto body = [&](int kt, f32x16 (&c)[2], float& bias, f32x16 (&cn)[2], float& bias_n, auto has_next) {
     constexpr bool HN = decltype(has_next)::value;
     const bool more_k = kt + 2 < ntiles;
-    // The d = 64 exact kernel requests the next tiles inside the score block (below), in the shadow of its
-    // MFMAs: it then fits 166 registers, a third workgroup per CU, and the base case and exact attention
-    // take 9 % less.  At d = 128 the same move measures +-0.5 %, and node mode, whose requests first read
-    // the key list from LDS, loses 7 % that way: both issue them here, ahead of the block.
-    constexpr bool kRequestInBlock = MODE == kModeExact && D == 64;
+    // The d = 64 kernels request the next tiles inside the score block (below), in the shadow of its MFMAs:
+    // they then fit 168 registers (the node kernel with five spilled ones), a third workgroup per CU, and
+    // take 8-10 % less (node launch, base case and exact attention alike).  At d = 128 the same move
+    // measures +-0.5 % in exact mode and +7 % in node mode, whose requests first read the key list from
+    // LDS: there they are issued here, ahead of the block.
+    constexpr bool kRequestInBlock = D == 64;
     if constexpr (!kRequestInBlock) {
       if (more_k) load_rows(kt + 2, krsrc, kreg);
       if (HN) load_rows(kt + 1, vrsrc, vreg);
