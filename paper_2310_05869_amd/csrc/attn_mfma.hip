@@ -368,7 +368,7 @@ __global__ __launch_bounds__(64 * NW, (D == 64 && NW == 4) ? 3 : 2) void attn_mf
         // issue order: a few fragment reads ahead, then per MFMA one more read and
         // a slice of the vector work, which fits inside the MFMA's 32 cycles
         constexpr int kPre = 4;
-        constexpr int kValu = (KS == 8) ? 5 : 14;  // d = 128: 5 measured best of 2 ... 9 (by half a percent)
+        constexpr int kValu = (KS == 8) ? 5 : 18;  // d = 128: 5 measured best of 2 ... 9 (by half a percent); d = 64: 18 of 7 ... 26 (by 2 %)
         __builtin_amdgcn_sched_group_barrier(0x100, kPre, 0);
 #pragma unroll
         for (int j = 0; j < 2 * KS; ++j) {
