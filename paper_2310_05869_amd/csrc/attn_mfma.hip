@@ -682,8 +682,8 @@ static int launch_one(const AttnArgs& a, hipStream_t st) {
 #define HA_NW_EXACT 4
 #endif
 
-// Unmasked exact attention over long key ranges shares each K / V tile among 8
-// waves (one workgroup per CU): 3-4 % faster there at d = 128; causal tiles and the short
+// Exact attention over long key ranges, causal or not, shares each K / V tile among 8
+// waves (one workgroup per CU): 3-4 % faster there at d = 128; the short
 // loops of the base case prefer two 4-wave workgroups per CU.
 constexpr int kWideExactMinRows = 8192;
 
@@ -701,7 +701,7 @@ int launch_attn_mfma(const AttnArgs& a, int mode, hipStream_t st) {
       return mode == kModeNode ? launch_one<64, kModeNode, HA_NW_NODE, true>(a, st) : launch_one<64, kModeExact, HA_NW_EXACT, true>(a, st);
     return HA_ERR_SHAPE;
   }
-  const bool wide = mode == kModeExact && !a.exact_causal && a.merge_levels == 0 &&
+  const bool wide = mode == kModeExact && a.merge_levels == 0 &&
                     a.exact_block >= kWideExactMinRows && a.exact_rows_q >= kWideExactMinRows;
   if (a.g.d == 128) {
     if (mode == kModeNode) return launch_one<128, kModeNode, HA_NW_NODE>(a, st);

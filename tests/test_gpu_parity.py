@@ -635,19 +635,24 @@ def test_forward_on_a_side_stream_and_under_graph_capture(ha, torch):
 
 
 def test_exact_attention_wide_workgroups_sampled_rows(ha, torch):
-    """Unmasked exact attention at n = 8192 takes the 8-wave form of the kernel; rows
+    """Exact attention at n = 8192, causal or not, takes the 8-wave form of the kernel at d = 128; rows
     sampled across the sequence are checked against the definition."""
     print("exact attention, 8-wave workgroups", flush=True)
-    for d in (128, 64):
+    for d, causal in ((128, False), (128, True), (64, False)):
         cfg = dict(B=1, H=2, n=8192, d=d, dtype="bf16", law="iid")
         Q, K, V = synth_inputs.make_qkv(cfg, seed=17)
-        out, lse = ha.exact_attn_forward(*(to_device(x, "bf16") for x in (Q, K, V)), causal=False)
+        out, lse = ha.exact_attn_forward(*(to_device(x, "bf16") for x in (Q, K, V)), causal=causal)
         torch.cuda.synchronize()
-        rows = np.array([0, 1, 31, 32, 127, 128, 255, 4095, 4096, 8000, 8191])
+        rows = np.array([0, 1, 31, 32, 127, 128, 255, 256, 4095, 4096, 8000, 8191])
         for hd in range(2):
-            ref_o, ref_l = orc.exact_attention(Q[0, hd][rows], K[0, hd], V[0, hd])
-            assert_close(to_host(out[0, hd])[rows], ref_o, "bf16", f"out d={d} head {hd}")
-            assert_lse_close(to_host(lse[0, hd])[rows], ref_l, "bf16", f"lse d={d} head {hd}")
+            if causal:
+                ref = [orc.exact_attention(Q[0, hd][i:i + 1], K[0, hd][:i + 1], V[0, hd][:i + 1]) for i in rows]
+                ref_o = np.concatenate([r[0] for r in ref])
+                ref_l = np.concatenate([r[1] for r in ref])
+            else:
+                ref_o, ref_l = orc.exact_attention(Q[0, hd][rows], K[0, hd], V[0, hd])
+            assert_close(to_host(out[0, hd])[rows], ref_o, "bf16", f"out d={d} causal={causal} head {hd}")
+            assert_lse_close(to_host(lse[0, hd])[rows], ref_l, "bf16", f"lse d={d} causal={causal} head {hd}")
 
 
 @pytest.mark.parametrize("H,n,n_min,b,m,r,causal", [
